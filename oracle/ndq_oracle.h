@@ -1,0 +1,132 @@
+/*
+ * ndq_oracle.h -- CPU oracle for dithered (DQSG) and nested dithered (NDQSG)
+ * quantization of stochastic-gradient vectors.
+ *
+ * THIS IS TEST INFRASTRUCTURE, NOT THE PRODUCT.  It is a plain, slow, scalar
+ * restatement of the method (Sec. 2.1 Definition and Remark 1; Sec. 3.1 eq. (2)
+ * and Algorithm 1; Sec. 3.2 eqs. (7)-(8) and Algorithm 2) used only to check the
+ * GPU library and to be timed beside it.  It shares no code with the GPU path.
+ *
+ * Precision.  The paper fixes none.  Every step that decides an integer (the
+ * quantization index, the coset representative) is taken in IEEE-754 binary32,
+ * the precision the GPU kernels use, so that codes can be compared bit for bit.
+ * Decoded values are binary32 as well because they feed the next worker's coset
+ * decision in Algorithm 2; oracle_dq_value_f64 gives the same quantity in
+ * binary64 from the definition, and the tests bound the difference.
+ *
+ * Free choices the paper leaves open (all pinned here, see each function):
+ *   - the random-number generator: Philox4x32-10 (Salmon et al., SC'11), counter
+ *     (i>>2 low, i>>2 high, step, worker), key (seed low, seed high);
+ *   - the dither grid: 2^24 mid-points of equal cells of [-1/2, 1/2);
+ *   - "nearest integer" ties: to even;
+ *   - number of levels L (odd L is the paper's 2M+1 case; even L uses
+ *     indices -L/2 .. L/2-1);
+ *   - the bitstream: fixed-width codes, LSB first.
+ *
+ * Parity unpinned by the paper (our own definitions, pinned only by round-trip
+ * and brute-force tests): packed-byte layout, code offset q_min, dither grid.
+ */
+#ifndef NDQ_ORACLE_H
+#define NDQ_ORACLE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* ---- dither stream (Remark 1; Algorithm 1 "generate u_p using seed s_p") ---- */
+
+/* One Philox4x32-10 block: out = Philox(ctr, key). */
+void oracle_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]);
+
+/* Unit dither v_i in (-1/2, 1/2) for element i of (seed, step, worker); the
+ * dither of the paper is u_i = Delta * v_i. */
+float oracle_unit_dither(uint64_t seed, uint32_t step, uint32_t worker, uint64_t i);
+
+/* ---- scalar building blocks (take the unit dither v explicitly) ---- */
+
+/* bits per code: ceil(log2(x)), x in [2,256]; 0 if x out of range */
+uint32_t oracle_code_bits(uint32_t x);
+
+/* Step for a bucket with max-norm kappa and L levels: 2*kappa/(L-1); steps
+ * below 2^-100 are treated as an all-zero bucket and returned as 0. */
+float oracle_step_from_kappa(float kappa, uint32_t levels);
+
+/* 1/Delta, or 0 when Delta == 0 (all-zero bucket). */
+float oracle_inv_step(float delta);
+
+/* eq. (2) / Alg. 1 worker: clipped index q = round(g/Delta + v) in
+ * [-(L/2), -(L/2)+L-1]; returns the code c = q - q_min in [0, L). */
+uint32_t oracle_dq_code(float g, float inv_delta, float v, uint32_t levels);
+
+/* Alg. 1 server: g~ = Delta * (q - v) with q = code + q_min. */
+float oracle_dq_value(uint32_t code, float delta, float v, uint32_t levels);
+double oracle_dq_value_f64(uint32_t code, double delta, double v, uint32_t levels);
+
+/* unclipped fine index round(g/Delta + v) (saturated at +-2^24) */
+int32_t oracle_fine_index(float g, float inv_delta, float v);
+
+/* eq. (7) with alpha = 1, Delta_2 = M*Delta_1: the fine index modulo M in [0, M). */
+uint32_t oracle_nested_code(float g, float inv_delta, float v, uint32_t M);
+
+/* eq. (8) with alpha = 1: the integer congruent to m (mod M) nearest to
+ * y/Delta + v; the decoded value is Delta * (that integer - v). */
+int32_t oracle_coset_index(uint32_t m, float y, float inv_delta, float v, uint32_t M);
+float oracle_index_value(int32_t q, float delta, float v);
+
+/* ---- bitstream ---- */
+size_t oracle_packed_bytes(size_t n, uint32_t bits); /* ceil(n*bits/8) rounded up to 16 */
+size_t oracle_num_buckets(size_t n, uint32_t bucket); /* bucket==0 -> 1 */
+/* code i occupies stream bits [i*b,(i+1)*b), bit k = bit (k%8) of byte k/8; padding zero */
+void oracle_pack(const uint32_t* codes, size_t n, uint32_t bits, uint8_t* out);
+void oracle_unpack(const uint8_t* in, size_t n, uint32_t bits, uint32_t* codes);
+
+/* ---- vector calls, mirroring the library's entry points ---- */
+
+/* seed s_p, iteration, worker p, and the index within the worker's whole
+ * gradient of the first element of this call (0 unless a slice is processed). */
+typedef struct { uint64_t seed; uint32_t step; uint32_t worker; uint64_t offset; } oracle_dither;
+
+/* the n unit dithers a call with this descriptor draws */
+void oracle_unit_dithers(oracle_dither d, size_t n, float* v_out);
+
+/* dtype: 0 = binary32, 1 = bfloat16 (widened exactly). */
+void oracle_absmax(const void* g, int dtype, size_t n, uint32_t bucket, float* kappa_out);
+
+/* Worker side of Alg. 1.  bucket==0: one step for the whole vector: `delta` if
+ * delta > 0, else 2*max|g|/(L-1); bucket>0: one step per bucket from its own
+ * max-norm.  Writes the packed codes and the steps. */
+void oracle_dq_encode(const void* g, int dtype, size_t n, float delta, uint32_t levels,
+                      uint32_t bucket, oracle_dither d, uint8_t* codes_out, float* steps_out);
+
+/* Server side of Alg. 1.  accumulate: out += g~ instead of out = g~. */
+void oracle_dq_decode(const uint8_t* codes, size_t n, uint32_t levels, uint32_t bucket,
+                      const float* steps, oracle_dither d, float* out, int accumulate);
+
+/* Worker side of Alg. 2 for p in P2.  `levels` only sets the fine step. */
+void oracle_nested_encode(const void* g, int dtype, size_t n, float delta, uint32_t levels,
+                          uint32_t M, uint32_t bucket, oracle_dither d, uint8_t* codes_out,
+                          float* steps_out);
+
+/* Server side of Alg. 2 for p in P2; side information y_i = side[i]*side_scale. */
+void oracle_nested_decode(const uint8_t* codes, size_t n, uint32_t M, uint32_t bucket,
+                          const float* steps, oracle_dither d, const float* side,
+                          float side_scale, float* out, int accumulate);
+
+/* Alg. 1 server: out_i = scale * sum_w gs[w][i], w ascending. */
+void oracle_aggregate(const float* const* gs, uint32_t W, size_t n, float scale, float* out);
+
+/* diagnostics: unclipped fine indices of a vector (for counting coset decode errors) */
+void oracle_fine_indices(const void* g, int dtype, size_t n, uint32_t bucket, const float* steps,
+                         oracle_dither d, int32_t* q_out);
+/* coset-resolved indices the nested decoder used (same inputs as oracle_nested_decode) */
+void oracle_coset_indices(const uint8_t* codes, size_t n, uint32_t M, uint32_t bucket,
+                          const float* steps, oracle_dither d, const float* side,
+                          float side_scale, int32_t* q_out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif
