@@ -1,0 +1,150 @@
+/*
+ * ndq.h -- C ABI of libndq: dithered (DQSG) and nested dithered (NDQSG)
+ * quantization of stochastic-gradient vectors on one AMD MI355X (gfx950).
+ *
+ * Method: A. Abdi, F. Fekri, "Nested Dithered Quantization for Communication
+ * Reduction in Distributed Training" (arXiv 1904.01197).  A worker holds a
+ * gradient vector g, a step Delta (or a number of levels and a max-norm scale),
+ * a dither seed s_p and the iteration number; it sends quantization indices and
+ * scale factors (Algorithm 1, "Workers"; Algorithm 2, "Workers").  The server
+ * holds the indices, the scale factors and the same seed, and for nested
+ * workers the side information: the mean of what it has decoded so far
+ * (Algorithm 1, "Server"; Algorithm 2, "Server").
+ *
+ * Conventions for every entry point
+ *   - All data pointers are DEVICE pointers owned by the caller; `d` (the dither
+ *     descriptor) and the pointer array of ndq_aggregate are HOST pointers, read
+ *     before the call returns.
+ *   - The library never allocates, frees, retains or synchronises.  A call only
+ *     enqueues kernels on `stream` (a hipStream_t passed as void*; NULL = the
+ *     default stream) and returns.
+ *   - Return value: 0 on success, a negative ndq_status on error; on error
+ *     nothing has been enqueued.  n == 0 is a successful no-op.
+ *   - g, codes, out and side must be 16-byte aligned; steps 4-byte aligned.
+ *     bucket must be 0 or a multiple of 64; d->offset a multiple of 4 (and of
+ *     bucket when a slice of a bucketed vector is processed).
+ *   - Inputs must be finite; this is not checked.
+ *   - No global state: calls are thread-safe.  Calls that write the same buffers
+ *     on different streams race.
+ *
+ * Arithmetic (binary32, round-to-nearest-even, no contraction)
+ *   unit dither   v_i = (k + 1/2) 2^-24 - 1/2, k = top 24 bits of word (I mod 4) of
+ *                 Philox4x32-10(counter = (I/4 low, I/4 high, step, worker),
+ *                 key = (seed low, seed high)), I = offset + i.  The dither of
+ *                 the paper is u_i = Delta v_i; it is never transmitted (Sec. 2.1,
+ *                 Remark 1).
+ *   step          Delta_b = 2 kappa_b / (L-1), kappa_b = max |g_i| over bucket b
+ *                 (Sec. 3.1 eq. (2) and the partitioning paragraph after Lemma 2);
+ *                 Delta_b < 2^-100 is sent as 0 (all-zero bucket).  1/Delta_b := 0
+ *                 when Delta_b == 0.
+ *   DQSG index    q_i = clip(rint(fma(g_i, 1/Delta_b, v_i)), -(L/2), -(L/2)+L-1),
+ *                 code c_i = q_i + L/2 (integer division).
+ *   DQSG value    g~_i = Delta_b * ((float)q_i - v_i)         (Algorithm 1, server)
+ *   nested code   m_i = rint(fma(g_i, 1/Delta_b, v_i)) mod M, in [0, M)
+ *                 (eq. (7) with alpha = 1 and Delta_2 = M Delta_1: the position of
+ *                 the fine bin relative to the coarse one)
+ *   nested value  y_i = side_i * side_scale; k = rint((fma(y_i, 1/Delta_b, v_i) - m_i)/M);
+ *                 q^_i = m_i + M k; g~_i = Delta_b * ((float)q^_i - v_i)
+ *                 (eq. (8) with alpha = 1: the point of the coset nearest to y_i)
+ *   bitstream     code i occupies stream bits [i b, (i+1) b), b = ndq_code_bits(L or M);
+ *                 stream bit k is bit (k mod 8) of byte k/8; the stream is padded
+ *                 with zero bits to ndq_packed_bytes(n, b) bytes.
+ */
+#ifndef NDQ_H
+#define NDQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { NDQ_F32 = 0, NDQ_BF16 = 1 } ndq_dtype;
+
+typedef enum {
+    NDQ_OK = 0,
+    NDQ_EINVAL = -1,       /* NULL pointer, levels/M outside [2,256], bad bucket, bad W */
+    NDQ_EALIGN = -2,       /* pointer, bucket or offset alignment violated             */
+    NDQ_EUNSUPPORTED = -3, /* size beyond what one call supports (n >= 2^40)           */
+    NDQ_ELAUNCH = -4       /* the HIP runtime refused a launch                         */
+} ndq_status;
+
+/* Identity of a dither stream: the seed s_p shared by worker p and the server
+ * (Algorithm 1, initialisation), the training iteration (stands for the "seed
+ * update" of Algorithm 1), the worker p, and the index within the worker's
+ * whole gradient of the first element handed to this call (0 unless the vector
+ * is processed in slices). */
+typedef struct {
+    uint64_t seed;
+    uint32_t step;
+    uint32_t worker;
+    uint64_t offset;
+} ndq_dither;
+
+/* Bits per code: ceil(log2(x)) for x = levels or M in [2,256]; 0 otherwise.
+ * (Sec. 3.2, last paragraph: log2(Delta_2/Delta_1) bits per nested value.) */
+uint32_t ndq_code_bits(uint32_t levels_or_M);
+
+/* Size in bytes of a packed code stream: ceil(n*bits/8) rounded up to 16. */
+size_t ndq_packed_bytes(size_t n, uint32_t bits);
+
+/* Number of scale factors: 1 if bucket == 0, else ceil(n/bucket). */
+size_t ndq_num_buckets(size_t n, uint32_t bucket);
+
+/* Max-norm scale factors kappa_b = max |g_i| per bucket (Sec. 3.1 eq. (2): the
+ * scale factor kappa = ||g||_inf; Algorithm 1 worker step "kappa_p").
+ * g: n elements of type dt.  kappa_out: ndq_num_buckets(n, bucket) floats. */
+int ndq_absmax(const void* g, ndq_dtype dt, size_t n, uint32_t bucket, float* kappa_out,
+               void* stream);
+
+/* Worker side of Algorithm 1 (generate dither, quantization index, send kappa and
+ * q): writes the packed DQSG codes of g and the step of every bucket.
+ *   bucket == 0, delta > 0 : one preset step delta (Algorithm 1 initialisation)
+ *   bucket == 0, delta <= 0: one step 2 max|g| / (levels-1) for the whole vector
+ *   bucket  > 0            : one step per bucket from the bucket's own max-norm
+ * codes_out: ndq_packed_bytes(n, ndq_code_bits(levels)) bytes, fully written.
+ * steps_out: ndq_num_buckets(n, bucket) floats -- the transmitted scale factors
+ * (Delta_b = 2 kappa_b/(L-1) travels in place of kappa_b: the same 32 bits). */
+int ndq_dq_encode(const void* g, ndq_dtype dt, size_t n, float delta, uint32_t levels,
+                  uint32_t bucket, const ndq_dither* d, void* codes_out, float* steps_out,
+                  void* stream);
+
+/* Server side of Algorithm 1 (regenerate the dither, reconstruct g~_p).
+ * accumulate == 0: out_i = g~_i; accumulate != 0: out_i += g~_i (running sum of
+ * the workers decoded so far).  out: n floats. */
+int ndq_dq_decode(const void* codes, size_t n, uint32_t levels, uint32_t bucket,
+                  const float* steps, const ndq_dither* d, float* out, int accumulate,
+                  void* stream);
+
+/* Worker side of Algorithm 2 for a worker of group P2 (eq. (7), alpha = 1): the
+ * fine index modulo M.  The step is chosen exactly as in ndq_dq_encode
+ * (`levels` only fixes the fine step; it does not clip).
+ * codes_out: ndq_packed_bytes(n, ndq_code_bits(M)) bytes. */
+int ndq_nested_encode(const void* g, ndq_dtype dt, size_t n, float delta, uint32_t levels,
+                      uint32_t M, uint32_t bucket, const ndq_dither* d, void* codes_out,
+                      float* steps_out, void* stream);
+
+/* Server side of Algorithm 2 for a worker of group P2 (eq. (8), alpha = 1).
+ * The side information is y_i = side[i] * side_scale, so `side` may be the
+ * running SUM of the gradients decoded so far and side_scale = 1/count (the
+ * "update the mean" step of Algorithm 2).  accumulate as in ndq_dq_decode; out
+ * may be the same buffer as side (in-place update of the running sum), but
+ * must not overlap it otherwise. */
+int ndq_nested_decode(const void* codes, size_t n, uint32_t M, uint32_t bucket,
+                      const float* steps, const ndq_dither* d, const float* side,
+                      float side_scale, float* out, int accumulate, void* stream);
+
+/* Server side of Algorithm 1, last step: out_i = scale * sum_w gs[w][i], summed
+ * in ascending w.  gs: HOST array of W device pointers (1 <= W <= 1024), each n
+ * floats; out may be one of the inputs only if W <= 32. */
+int ndq_aggregate(const float* const* gs, uint32_t W, size_t n, float scale, float* out,
+                  void* stream);
+
+/* Static, human-readable text for a status code. */
+const char* ndq_strerror(int rc);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NDQ_H */

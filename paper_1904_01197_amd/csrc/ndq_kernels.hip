@@ -1,0 +1,621 @@
+// libndq kernels and C ABI (gfx950).  See include/ndq.h for the contract.
+//
+// Every kernel is a streaming pass: one wave owns one tile of a few thousand
+// consecutive elements, issues all of its 16-byte loads up front, regenerates
+// the dither with Philox in registers and writes 16-byte (values) or 8-byte
+// (packed codes) coalesced stores.  Nothing here is a contraction, so no MFMA;
+// LDS is used only to transpose the small packed codes into stream order.
+#include <hip/hip_runtime.h>
+
+#include "ndq.h"
+#include "ndq_device.hpp"
+
+namespace ndq {
+
+// ---------------------------------------------------------------------------
+// Encoder: Algorithm 1 worker block (DQSG) / Algorithm 2 worker block (NDQSG)
+// ---------------------------------------------------------------------------
+struct EncodeArgs {
+    const void* g;
+    unsigned char* codes;
+    float* steps;          // written (fused / preset) or read (two-pass)
+    Tiling tl;
+    uint64_t index0;       // dither offset of element 0
+    uint64_t total_bytes;  // size of the packed stream incl. zero padding
+    DitherStream ds;
+    Quant qp;
+    float preset_step;     // > 0: bucket == 0 with a caller-set step
+};
+
+template <int DT> struct EncTile { static constexpr uint32_t N = kWave * Elem<DT>::E * kRows; };
+
+// Quantizes the tile held in `raw` and leaves its packed codes in `stage`
+// (stream order).  CHECK: the tile is ragged, zero the codes past `len`.
+template <int DT, int MODE, bool CHECK>
+__device__ __forceinline__ void quantize_tile(const uint4 (&raw)[kRows], uint32_t len, float inv,
+                                              uint64_t block0, const DitherStream& ds,
+                                              const Quant& qp, unsigned char* stage, int lane)
+{
+    using T = Elem<DT>;
+    constexpr int E = T::E;
+    const uint32_t bits = qp.bits;
+#pragma unroll
+    for (int r = 0; r < kRows; ++r) {
+        const uint32_t o = (uint32_t)r * kWave * E + (uint32_t)lane * E;
+        uint32_t quad[E / 4];
+#pragma unroll
+        for (int h = 0; h < E / 4; ++h) {
+            float v[4];
+            dither4(ds, block0 + (o >> 2) + h, v);
+            uint32_t chunk = 0;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                uint32_t c = encode_one<MODE>(T::get(raw[r], 4 * h + k), inv, v[k], qp);
+                if (CHECK && o + 4 * h + k >= len) c = 0;
+                chunk |= c << (k * bits);
+            }
+            quad[h] = chunk;
+        }
+        // eight consecutive codes -> `bits` bytes at byte (o/8)*bits of the tile's stream
+        uint32_t lo = quad[0], hi;
+        bool writer = true;
+        if (E == 8) {
+            hi = quad[E / 4 - 1];
+        } else {
+            hi = __shfl_down(lo, 1, kWave);
+            writer = (lane & 1) == 0;
+        }
+        const uint64_t chunk8 = (uint64_t)lo | ((uint64_t)hi << (4 * bits));
+        if (writer) {
+            unsigned char* p = stage + (o >> 3) * bits;
+            switch (bits) {
+                case 1: *p = (unsigned char)chunk8; break;
+                case 2: *(uint16_t*)p = (uint16_t)chunk8; break;
+                case 4: *(uint32_t*)p = (uint32_t)chunk8; break;
+                case 8: *(uint64_t*)p = chunk8; break;
+                default:
+                    for (uint32_t k = 0; k < bits; ++k) p[k] = (unsigned char)(chunk8 >> (8 * k));
+            }
+        }
+    }
+}
+
+// FUSED: the bucket fits one tile; its max-norm is reduced in registers and
+// the step is written.  Otherwise the step is the preset one or read from
+// `steps` (filled by absmax_kernel + steps_from_kappa_kernel).
+template <int DT, int MODE, bool FUSED>
+__global__ __launch_bounds__(kBlock) void encode_kernel(EncodeArgs a)
+{
+    using T = Elem<DT>;
+    constexpr uint32_t TILE = EncTile<DT>::N;
+    __shared__ __align__(16) unsigned char stage_all[kWavesPerBlock][TILE + 8];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x / kWave;
+    unsigned char* stage = stage_all[wave];
+
+    const uint32_t tile_id = blockIdx.x * kWavesPerBlock + wave;
+    const TileRef t = locate_tile(a.tl, tile_id, TILE);
+    const uint32_t bits = a.qp.bits;
+    if (t.len != 0) {
+        const typename T::scalar* tile = (const typename T::scalar*)a.g + t.start;
+        uint4 raw[kRows];
+#pragma unroll
+        for (int r = 0; r < kRows; ++r)
+            raw[r] = load_row<DT>(tile, (uint32_t)r * kWave * T::E + (uint32_t)lane * T::E, t.len);
+
+        float step;
+        if (FUSED) {
+            float m = 0.0f;
+#pragma unroll
+            for (int r = 0; r < kRows; ++r)
+#pragma unroll
+                for (int k = 0; k < T::E; ++k) m = __builtin_fmaxf(m, __builtin_fabsf(T::get(raw[r], k)));
+            step = step_from_kappa(wave_max(m), a.qp.levels);
+            if (lane == 0) a.steps[t.bucket] = step;
+        } else if (a.preset_step > 0.0f) {
+            step = a.preset_step;
+            if (tile_id == 0 && lane == 0) a.steps[0] = step;
+        } else {
+            step = a.steps[t.bucket];
+        }
+        const float inv = inv_step(step);
+        const uint64_t block0 = (a.index0 + t.start) >> 2;
+        if (t.len == TILE)
+            quantize_tile<DT, MODE, false>(raw, t.len, inv, block0, a.ds, a.qp, stage, lane);
+        else
+            quantize_tile<DT, MODE, true>(raw, t.len, inv, block0, a.ds, a.qp, stage, lane);
+        if (lane == 0) *(uint64_t*)(stage + (size_t)TILE / 8 * bits) = 0;  // pad unit
+    }
+    __syncthreads();
+    if (t.len != 0) {
+        const uint64_t byte0 = (t.start >> 3) * bits;                 // tile start is a multiple of 64
+        const bool last = t.start + t.len == a.tl.n;
+        const uint64_t nbytes = last ? a.total_bytes - byte0 : (uint64_t)(t.len >> 3) * bits;
+        const uint32_t units = (uint32_t)(nbytes >> 3);
+        uint64_t* dst = (uint64_t*)(a.codes + byte0);
+        const uint64_t* src = (const uint64_t*)stage;
+        for (uint32_t u = lane; u < units; u += kWave) dst[u] = src[u];
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Max-norm per bucket (two-pass path and ndq_absmax)
+// ---------------------------------------------------------------------------
+__global__ void fill_zero_kernel(uint32_t* p, uint64_t n)
+{
+    const uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0u;
+}
+
+template <int DT>
+__global__ __launch_bounds__(kBlock) void absmax_kernel(const void* g, Tiling tl, uint32_t* kappa_bits)
+{
+    using T = Elem<DT>;
+    constexpr uint32_t TILE = EncTile<DT>::N;
+    const int lane = threadIdx.x & (kWave - 1);
+    const uint32_t tile_id = blockIdx.x * kWavesPerBlock + threadIdx.x / kWave;
+    const TileRef t = locate_tile(tl, tile_id, TILE);
+    if (t.len == 0) return;
+    const typename T::scalar* tile = (const typename T::scalar*)g + t.start;
+    float m = 0.0f;
+#pragma unroll
+    for (int r = 0; r < kRows; ++r) {
+        const uint4 raw = load_row<DT>(tile, (uint32_t)r * kWave * T::E + (uint32_t)lane * T::E, t.len);
+#pragma unroll
+        for (int k = 0; k < T::E; ++k) m = __builtin_fmaxf(m, __builtin_fabsf(T::get(raw, k)));
+    }
+    m = wave_max(m);
+    // non-negative floats order like their bit patterns
+    if (lane == 0) atomicMax(kappa_bits + t.bucket, __float_as_uint(m));
+}
+
+__global__ void steps_from_kappa_kernel(float* steps, uint64_t K, uint32_t levels)
+{
+    const uint64_t b = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (b < K) steps[b] = step_from_kappa(steps[b], levels);
+}
+
+// ---------------------------------------------------------------------------
+// Decoder: Algorithm 1 server block (DQSG) / Algorithm 2 server loop (NDQSG)
+// ---------------------------------------------------------------------------
+struct DecodeArgs {
+    const unsigned char* codes;
+    const float* steps;
+    const float* side;     // nested modes
+    float* out;
+    Tiling tl;
+    uint64_t index0;
+    DitherStream ds;
+    Quant qp;
+    float side_scale;
+};
+
+constexpr uint32_t kDecTile = kWave * 4 * kRows;   // 2048 outputs per wave
+
+enum Acc { kStore = 0, kAccumulate = 1, kAccumulateInPlace = 2 };  // in place: out == side
+
+template <int MODE, int ACC>
+__global__ __launch_bounds__(kBlock) void decode_kernel(DecodeArgs a)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    const uint32_t tile_id = blockIdx.x * kWavesPerBlock + threadIdx.x / kWave;
+    const TileRef t = locate_tile(a.tl, tile_id, kDecTile);
+    if (t.len == 0) return;
+    const uint32_t bits = a.qp.bits;
+    const uint32_t mask = (1u << bits) - 1u;
+    const bool straddle = (32u % (4u * bits)) != 0u;   // four codes may cross a 32-bit word
+    const uint32_t* codes32 = (const uint32_t*)(a.codes + (t.start >> 3) * bits);
+    const float* side = a.side + t.start;
+    float* out = a.out + t.start;
+    const float step = a.steps[t.bucket];
+    const float inv = inv_step(step);
+    const uint64_t block0 = (a.index0 + t.start) >> 2;
+
+    uint32_t packed[kRows];
+    float4 y[kRows], prev[kRows];
+#pragma unroll
+    for (int r = 0; r < kRows; ++r) {
+        const uint32_t o = (uint32_t)r * kWave * 4 + (uint32_t)lane * 4;
+        packed[r] = 0;
+        y[r] = make_float4(0.f, 0.f, 0.f, 0.f);
+        prev[r] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (o < t.len) {
+            const uint32_t bit = o * bits;
+            const uint32_t w = bit >> 5, sh = bit & 31u;
+            uint64_t window = codes32[w];
+            if (straddle && sh + 4u * bits > 32u) window |= (uint64_t)codes32[w + 1] << 32;
+            packed[r] = (uint32_t)(window >> sh);
+            if (o + 4 <= t.len) {
+                if (MODE != kDq) y[r] = *(const float4*)(side + o);
+                if (ACC == kAccumulate) prev[r] = *(const float4*)(out + o);
+            } else {
+                float ys[4] = {0.f, 0.f, 0.f, 0.f}, ps[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (uint32_t k = 0; k < 4; ++k)
+                    if (o + k < t.len) {
+                        if (MODE != kDq) ys[k] = side[o + k];
+                        if (ACC == kAccumulate) ps[k] = out[o + k];
+                    }
+                y[r] = make_float4(ys[0], ys[1], ys[2], ys[3]);
+                prev[r] = make_float4(ps[0], ps[1], ps[2], ps[3]);
+            }
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < kRows; ++r) {
+        const uint32_t o = (uint32_t)r * kWave * 4 + (uint32_t)lane * 4;
+        if (o >= t.len) continue;
+        float v[4];
+        dither4(a.ds, block0 + (o >> 2), v);
+        const float ys[4] = {y[r].x, y[r].y, y[r].z, y[r].w};
+        const float ps[4] = {prev[r].x, prev[r].y, prev[r].z, prev[r].w};
+        float res[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const uint32_t c = (packed[r] >> (k * bits)) & mask;
+            int32_t q;
+            if (MODE == kDq) {
+                q = (int32_t)c + a.qp.q_min;
+            } else {
+                const float yk = ys[k] * a.side_scale;
+                q = coset_index<MODE>(c, yk, inv, v[k], a.qp);
+            }
+            const float val = index_value(q, step, v[k]);
+            if (ACC == kStore) res[k] = val;
+            else if (ACC == kAccumulate) res[k] = ps[k] + val;
+            else res[k] = ys[k] + val;
+        }
+        if (o + 4 <= t.len) {
+            *(float4*)(out + o) = make_float4(res[0], res[1], res[2], res[3]);
+        } else {
+#pragma unroll
+            for (uint32_t k = 0; k < 4; ++k)
+                if (o + k < t.len) out[o + k] = res[k];
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Aggregation: Algorithm 1 server, "compute the average"
+// ---------------------------------------------------------------------------
+constexpr uint32_t kAggMax = 32;
+struct AggArgs {
+    const float* g[kAggMax];
+    float* out;
+    uint64_t n;
+    uint32_t W;
+    int continue_sum;   // start from out (partial sum of an earlier group of workers)
+    int finish;         // multiply by scale
+    float scale;
+};
+
+__global__ __launch_bounds__(kBlock) void aggregate_kernel(AggArgs a)
+{
+    const uint64_t i4 = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+    const uint64_t i = i4 * 4;
+    if (i >= a.n) return;
+    if (i + 4 <= a.n) {
+        float4 acc = a.continue_sum ? *(const float4*)(a.out + i) : make_float4(0.f, 0.f, 0.f, 0.f);
+        for (uint32_t w0 = 0; w0 < a.W; w0 += 8) {
+            float4 x[8];
+#pragma unroll
+            for (uint32_t j = 0; j < 8; ++j)
+                if (w0 + j < a.W) x[j] = *(const float4*)(a.g[w0 + j] + i);
+#pragma unroll
+            for (uint32_t j = 0; j < 8; ++j)
+                if (w0 + j < a.W) {
+                    acc.x = acc.x + x[j].x; acc.y = acc.y + x[j].y;
+                    acc.z = acc.z + x[j].z; acc.w = acc.w + x[j].w;
+                }
+        }
+        if (a.finish) { acc.x = a.scale * acc.x; acc.y = a.scale * acc.y; acc.z = a.scale * acc.z; acc.w = a.scale * acc.w; }
+        *(float4*)(a.out + i) = acc;
+    } else {
+        for (uint64_t e = i; e < a.n; ++e) {
+            float acc = a.continue_sum ? a.out[e] : 0.0f;
+            for (uint32_t w = 0; w < a.W; ++w) acc = acc + a.g[w][e];
+            a.out[e] = a.finish ? a.scale * acc : acc;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Host side: validation and dispatch
+// ---------------------------------------------------------------------------
+static uint32_t code_bits(uint32_t x)
+{
+    if (x < 2u || x > 256u) return 0u;
+    uint32_t b = 0u;
+    while ((1u << b) < x) ++b;
+    return b;
+}
+
+static size_t packed_bytes(size_t n, uint32_t bits)
+{
+    const size_t bytes = (n * (size_t)bits + 7u) / 8u;
+    return (bytes + 15u) / 16u * 16u;
+}
+
+static bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
+static bool aligned4(const void* p) { return ((uintptr_t)p & 3u) == 0; }
+constexpr uint64_t kMaxN = (uint64_t)1 << 40;
+
+static int make_tiling(uint64_t n, uint32_t bucket, uint32_t tile, Tiling* tl)
+{
+    tl->n = n;
+    tl->bucket_len = bucket ? bucket : n;
+    const uint64_t K = bucket ? (n + bucket - 1) / bucket : 1;
+    const uint64_t tpb = (tl->bucket_len + tile - 1) / tile;
+    if (tpb * K >= ((uint64_t)1 << 31) || tpb >= ((uint64_t)1 << 31)) return NDQ_EUNSUPPORTED;
+    tl->tiles_per_bucket = (uint32_t)tpb;
+    tl->total_tiles = (uint32_t)(tpb * K);
+    return NDQ_OK;
+}
+
+static int make_quant(uint32_t levels, uint32_t M, bool nested, Quant* qp)
+{
+    if (levels < 2u || levels > 256u) return NDQ_EINVAL;
+    if (nested && (M < 2u || M > 256u)) return NDQ_EINVAL;
+    qp->levels = levels;
+    qp->q_min = -(int32_t)(levels / 2u);
+    qp->q_min_f = (float)qp->q_min;
+    qp->q_max_f = (float)(qp->q_min + (int32_t)levels - 1);
+    qp->M = nested ? M : 1u;
+    qp->M_f = (float)qp->M;
+    qp->inv_M_f = 1.0f / qp->M_f;   // exact when M is a power of two, unused otherwise
+    qp->bits = code_bits(nested ? M : levels);
+    return NDQ_OK;
+}
+
+static bool is_pow2(uint32_t x) { return (x & (x - 1u)) == 0u; }
+
+static DitherStream make_stream(const ndq_dither* d)
+{
+    DitherStream s;
+    s.key0 = (uint32_t)d->seed;
+    s.key1 = (uint32_t)(d->seed >> 32);
+    s.step = d->step;
+    s.worker = d->worker;
+    return s;
+}
+
+static int launched() { return hipGetLastError() == hipSuccess ? NDQ_OK : NDQ_ELAUNCH; }
+
+static uint32_t blocks_for(uint32_t tiles) { return (tiles + kWavesPerBlock - 1) / kWavesPerBlock; }
+
+template <int DT>
+static int run_absmax(const void* g, const Tiling& tl, uint64_t K, float* kappa, hipStream_t s)
+{
+    hipLaunchKernelGGL(fill_zero_kernel, dim3((uint32_t)((K + 255) / 256)), dim3(256), 0, s,
+                       (uint32_t*)kappa, K);
+    if (launched() != NDQ_OK) return NDQ_ELAUNCH;
+    hipLaunchKernelGGL(absmax_kernel<DT>, dim3(blocks_for(tl.total_tiles)), dim3(kBlock), 0, s, g, tl,
+                       (uint32_t*)kappa);
+    return launched();
+}
+
+template <int DT, int MODE>
+static int run_encode(const EncodeArgs& a, bool fused, hipStream_t s)
+{
+    const dim3 grid(blocks_for(a.tl.total_tiles)), block(kBlock);
+    if (fused) hipLaunchKernelGGL((encode_kernel<DT, MODE, true>), grid, block, 0, s, a);
+    else hipLaunchKernelGGL((encode_kernel<DT, MODE, false>), grid, block, 0, s, a);
+    return launched();
+}
+
+static int encode_common(const void* g, ndq_dtype dt, size_t n, float delta, uint32_t levels,
+                         uint32_t M, bool nested, uint32_t bucket, const ndq_dither* d,
+                         void* codes_out, float* steps_out, void* stream)
+{
+    EncodeArgs a;
+    int rc = make_quant(levels, M, nested, &a.qp);
+    if (rc != NDQ_OK) return rc;
+    if (dt != NDQ_F32 && dt != NDQ_BF16) return NDQ_EINVAL;
+    if (!d) return NDQ_EINVAL;
+    if (n == 0) return NDQ_OK;
+    if (!g || !codes_out || !steps_out) return NDQ_EINVAL;
+    if (!(delta == delta)) return NDQ_EINVAL;
+    if (n >= kMaxN) return NDQ_EUNSUPPORTED;
+    if (!aligned16(g) || !aligned16(codes_out) || !aligned4(steps_out)) return NDQ_EALIGN;
+    if (bucket % 64u != 0u || (d->offset & 3u) != 0u) return NDQ_EALIGN;
+
+    const uint32_t tile = dt == NDQ_F32 ? EncTile<0>::N : EncTile<1>::N;
+    rc = make_tiling(n, bucket, tile, &a.tl);
+    if (rc != NDQ_OK) return rc;
+    a.g = g;
+    a.codes = (unsigned char*)codes_out;
+    a.steps = steps_out;
+    a.index0 = d->offset;
+    a.total_bytes = packed_bytes(n, a.qp.bits);
+    a.ds = make_stream(d);
+    a.preset_step = (bucket == 0u && delta > 0.0f) ? delta : 0.0f;
+    hipStream_t s = (hipStream_t)stream;
+
+    const bool fused = bucket != 0u && bucket <= tile;
+    if (!fused && a.preset_step == 0.0f) {
+        // two passes: max-norm per bucket, then steps, then the encoder reads them
+        const uint64_t K = bucket ? (n + bucket - 1) / bucket : 1;
+        rc = dt == NDQ_F32 ? run_absmax<0>(g, a.tl, K, steps_out, s)
+                           : run_absmax<1>(g, a.tl, K, steps_out, s);
+        if (rc != NDQ_OK) return rc;
+        hipLaunchKernelGGL(steps_from_kappa_kernel, dim3((uint32_t)((K + 255) / 256)), dim3(256), 0,
+                           s, steps_out, K, levels);
+        if (launched() != NDQ_OK) return NDQ_ELAUNCH;
+    }
+    const int mode = !nested ? kDq : (is_pow2(M) ? kNestedPow2 : kNestedAnyM);
+    if (dt == NDQ_F32) {
+        if (mode == kDq) return run_encode<0, kDq>(a, fused, s);
+        if (mode == kNestedPow2) return run_encode<0, kNestedPow2>(a, fused, s);
+        return run_encode<0, kNestedAnyM>(a, fused, s);
+    }
+    if (mode == kDq) return run_encode<1, kDq>(a, fused, s);
+    if (mode == kNestedPow2) return run_encode<1, kNestedPow2>(a, fused, s);
+    return run_encode<1, kNestedAnyM>(a, fused, s);
+}
+
+template <int MODE>
+static int run_decode(const DecodeArgs& a, int acc, hipStream_t s)
+{
+    const dim3 grid(blocks_for(a.tl.total_tiles)), block(kBlock);
+    if (acc == kStore) hipLaunchKernelGGL((decode_kernel<MODE, kStore>), grid, block, 0, s, a);
+    else if (acc == kAccumulate) hipLaunchKernelGGL((decode_kernel<MODE, kAccumulate>), grid, block, 0, s, a);
+    else hipLaunchKernelGGL((decode_kernel<MODE, kAccumulateInPlace>), grid, block, 0, s, a);
+    return launched();
+}
+
+static int decode_common(const void* codes, size_t n, uint32_t levels, uint32_t M, bool nested,
+                         uint32_t bucket, const float* steps, const ndq_dither* d,
+                         const float* side, float side_scale, float* out, int accumulate,
+                         void* stream)
+{
+    DecodeArgs a;
+    int rc = make_quant(levels, M, nested, &a.qp);
+    if (rc != NDQ_OK) return rc;
+    if (!d) return NDQ_EINVAL;
+    if (n == 0) return NDQ_OK;
+    if (!codes || !steps || !out || (nested && !side)) return NDQ_EINVAL;
+    if (n >= kMaxN) return NDQ_EUNSUPPORTED;
+    if (!aligned16(codes) || !aligned16(out) || !aligned4(steps) || (nested && !aligned16(side)))
+        return NDQ_EALIGN;
+    if (bucket % 64u != 0u || (d->offset & 3u) != 0u) return NDQ_EALIGN;
+    if (nested && side != out) {
+        // partial overlap of side and out would race between waves
+        const uintptr_t s0 = (uintptr_t)side, o0 = (uintptr_t)out, len = (uintptr_t)n * 4u;
+        if (s0 < o0 + len && o0 < s0 + len) return NDQ_EINVAL;
+    }
+    rc = make_tiling(n, bucket, kDecTile, &a.tl);
+    if (rc != NDQ_OK) return rc;
+    a.codes = (const unsigned char*)codes;
+    a.steps = steps;
+    a.side = nested ? side : out;
+    a.out = out;
+    a.index0 = d->offset;
+    a.ds = make_stream(d);
+    a.side_scale = side_scale;
+    hipStream_t s = (hipStream_t)stream;
+    int acc = accumulate ? kAccumulate : kStore;
+    if (nested && accumulate && side == out) acc = kAccumulateInPlace;
+    if (!nested) return run_decode<kDq>(a, acc, s);
+    if (is_pow2(M)) return run_decode<kNestedPow2>(a, acc, s);
+    return run_decode<kNestedAnyM>(a, acc, s);
+}
+
+}  // namespace ndq
+
+// ---------------------------------------------------------------------------
+// C ABI
+// ---------------------------------------------------------------------------
+extern "C" {
+
+uint32_t ndq_code_bits(uint32_t levels_or_M) { return ndq::code_bits(levels_or_M); }
+
+size_t ndq_packed_bytes(size_t n, uint32_t bits) { return ndq::packed_bytes(n, bits); }
+
+size_t ndq_num_buckets(size_t n, uint32_t bucket)
+{
+    return bucket ? (n + bucket - 1u) / bucket : 1u;
+}
+
+int ndq_absmax(const void* g, ndq_dtype dt, size_t n, uint32_t bucket, float* kappa_out,
+               void* stream)
+{
+    using namespace ndq;
+    if (dt != NDQ_F32 && dt != NDQ_BF16) return NDQ_EINVAL;
+    if (!kappa_out) return NDQ_EINVAL;
+    if (n >= kMaxN) return NDQ_EUNSUPPORTED;
+    if (!aligned4(kappa_out) || bucket % 64u != 0u) return NDQ_EALIGN;
+    hipStream_t s = (hipStream_t)stream;
+    if (n == 0) {   // one (empty) bucket: its max-norm is 0
+        if (bucket != 0u) return NDQ_OK;
+        hipLaunchKernelGGL(fill_zero_kernel, dim3(1), dim3(256), 0, s, (uint32_t*)kappa_out, (uint64_t)1);
+        return launched();
+    }
+    if (!g) return NDQ_EINVAL;
+    if (!aligned16(g)) return NDQ_EALIGN;
+    Tiling tl;
+    const uint32_t tile = dt == NDQ_F32 ? EncTile<0>::N : EncTile<1>::N;
+    int rc = make_tiling(n, bucket, tile, &tl);
+    if (rc != NDQ_OK) return rc;
+    const uint64_t K = bucket ? (n + bucket - 1) / bucket : 1;
+    return dt == NDQ_F32 ? run_absmax<0>(g, tl, K, kappa_out, s) : run_absmax<1>(g, tl, K, kappa_out, s);
+}
+
+int ndq_dq_encode(const void* g, ndq_dtype dt, size_t n, float delta, uint32_t levels,
+                  uint32_t bucket, const ndq_dither* d, void* codes_out, float* steps_out,
+                  void* stream)
+{
+    return ndq::encode_common(g, dt, n, delta, levels, 0u, false, bucket, d, codes_out, steps_out,
+                              stream);
+}
+
+int ndq_nested_encode(const void* g, ndq_dtype dt, size_t n, float delta, uint32_t levels,
+                      uint32_t M, uint32_t bucket, const ndq_dither* d, void* codes_out,
+                      float* steps_out, void* stream)
+{
+    return ndq::encode_common(g, dt, n, delta, levels, M, true, bucket, d, codes_out, steps_out,
+                              stream);
+}
+
+int ndq_dq_decode(const void* codes, size_t n, uint32_t levels, uint32_t bucket,
+                  const float* steps, const ndq_dither* d, float* out, int accumulate,
+                  void* stream)
+{
+    return ndq::decode_common(codes, n, levels, 0u, false, bucket, steps, d, nullptr, 1.0f, out,
+                              accumulate, stream);
+}
+
+int ndq_nested_decode(const void* codes, size_t n, uint32_t M, uint32_t bucket,
+                      const float* steps, const ndq_dither* d, const float* side,
+                      float side_scale, float* out, int accumulate, void* stream)
+{
+    // `levels` plays no part in decoding: the step travels in `steps`
+    return ndq::decode_common(codes, n, 2u, M, true, bucket, steps, d, side, side_scale, out,
+                              accumulate, stream);
+}
+
+int ndq_aggregate(const float* const* gs, uint32_t W, size_t n, float scale, float* out,
+                  void* stream)
+{
+    using namespace ndq;
+    if (!gs || W < 1u || W > 1024u) return NDQ_EINVAL;
+    if (n == 0) return NDQ_OK;
+    if (!out) return NDQ_EINVAL;
+    if (n >= kMaxN) return NDQ_EUNSUPPORTED;
+    if (!aligned16(out)) return NDQ_EALIGN;
+    for (uint32_t w = 0; w < W; ++w) {
+        if (!gs[w]) return NDQ_EINVAL;
+        if (!aligned16(gs[w])) return NDQ_EALIGN;
+        if (W > kAggMax && gs[w] == out) return NDQ_EINVAL;
+    }
+    const uint64_t threads = (n + 3) / 4;
+    const uint64_t blocks = (threads + kBlock - 1) / kBlock;
+    if (blocks >= ((uint64_t)1 << 31)) return NDQ_EUNSUPPORTED;
+    for (uint32_t w0 = 0; w0 < W; w0 += kAggMax) {
+        AggArgs a;
+        a.W = (W - w0 < kAggMax) ? W - w0 : kAggMax;
+        for (uint32_t j = 0; j < kAggMax; ++j) a.g[j] = j < a.W ? gs[w0 + j] : nullptr;
+        a.out = out;
+        a.n = n;
+        a.continue_sum = w0 != 0u;
+        a.finish = w0 + kAggMax >= W;
+        a.scale = scale;
+        hipLaunchKernelGGL(aggregate_kernel, dim3((uint32_t)blocks), dim3(kBlock), 0,
+                           (hipStream_t)stream, a);
+        if (launched() != NDQ_OK) return NDQ_ELAUNCH;
+    }
+    return NDQ_OK;
+}
+
+const char* ndq_strerror(int rc)
+{
+    switch (rc) {
+        case NDQ_OK: return "success";
+        case NDQ_EINVAL: return "invalid argument (null pointer, levels or M outside [2,256], overlapping buffers, bad W)";
+        case NDQ_EALIGN: return "alignment violated (16-byte data pointers, bucket multiple of 64, offset multiple of 4)";
+        case NDQ_EUNSUPPORTED: return "vector too long for one call";
+        case NDQ_ELAUNCH: return "the HIP runtime refused a kernel launch";
+        default: return "unknown ndq status";
+    }
+}
+
+}  // extern "C"

@@ -1,0 +1,184 @@
+"""ctypes binding of libndq (include/ndq.h): argument marshalling only.
+
+Every function has the name and the argument order of its C entry point and
+takes torch CUDA tensors where the C function takes device pointers; kernels
+are enqueued on torch's current stream.  Output tensors may be passed in
+(to reuse memory) or are allocated with torch.  There is no CPU fallback: if
+``libndq.so`` has not been built, loading raises.
+"""
+import ctypes as C
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SO = os.path.join(_HERE, "libndq.so")
+
+NDQ_F32, NDQ_BF16 = 0, 1
+NDQ_OK, NDQ_EINVAL, NDQ_EALIGN, NDQ_EUNSUPPORTED, NDQ_ELAUNCH = 0, -1, -2, -3, -4
+
+EXPORTS = ("ndq_code_bits", "ndq_packed_bytes", "ndq_num_buckets", "ndq_absmax", "ndq_dq_encode",
+           "ndq_dq_decode", "ndq_nested_encode", "ndq_nested_decode", "ndq_aggregate",
+           "ndq_strerror")
+
+
+class ndq_dither(C.Structure):
+    """Mirror of the C struct: (seed, step, worker, offset)."""
+    _fields_ = [("seed", C.c_uint64), ("step", C.c_uint32), ("worker", C.c_uint32),
+                ("offset", C.c_uint64)]
+
+
+class NdqError(RuntimeError):
+    def __init__(self, rc, what):
+        self.rc = rc
+        super().__init__("%s failed: %s (%d)" % (what, ndq_strerror(rc), rc))
+
+
+_lib = None
+
+
+def lib():
+    """The loaded shared library (loads it on first use)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_SO):
+            raise RuntimeError(
+                "libndq.so is not built (%s); run `python -m paper_1904_01197_amd.build` or "
+                "__graft_entry__.build() first -- there is no fallback path" % _SO)
+        L = C.CDLL(_SO)
+        vp, sz, u32, f32, ci = C.c_void_p, C.c_size_t, C.c_uint32, C.c_float, C.c_int
+        dp = C.POINTER(ndq_dither)
+        L.ndq_code_bits.argtypes, L.ndq_code_bits.restype = [u32], u32
+        L.ndq_packed_bytes.argtypes, L.ndq_packed_bytes.restype = [sz, u32], sz
+        L.ndq_num_buckets.argtypes, L.ndq_num_buckets.restype = [sz, u32], sz
+        L.ndq_absmax.argtypes, L.ndq_absmax.restype = [vp, ci, sz, u32, vp, vp], ci
+        L.ndq_dq_encode.argtypes = [vp, ci, sz, f32, u32, u32, dp, vp, vp, vp]
+        L.ndq_dq_encode.restype = ci
+        L.ndq_dq_decode.argtypes = [vp, sz, u32, u32, vp, dp, vp, ci, vp]
+        L.ndq_dq_decode.restype = ci
+        L.ndq_nested_encode.argtypes = [vp, ci, sz, f32, u32, u32, u32, dp, vp, vp, vp]
+        L.ndq_nested_encode.restype = ci
+        L.ndq_nested_decode.argtypes = [vp, sz, u32, u32, vp, dp, vp, f32, vp, ci, vp]
+        L.ndq_nested_decode.restype = ci
+        L.ndq_aggregate.argtypes, L.ndq_aggregate.restype = [vp, u32, sz, f32, vp, vp], ci
+        L.ndq_strerror.argtypes, L.ndq_strerror.restype = [ci], C.c_char_p
+        _lib = L
+    return _lib
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dt(g):
+    if g.dtype == torch.float32:
+        return NDQ_F32
+    if g.dtype == torch.bfloat16:
+        return NDQ_BF16
+    raise TypeError("gradient must be float32 or bfloat16")
+
+
+def _dev(t, what):
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.is_contiguous()):
+        raise TypeError("%s must be a contiguous CUDA tensor" % what)
+    return C.c_void_p(t.data_ptr())
+
+
+def _check(rc, what):
+    if rc != NDQ_OK:
+        raise NdqError(rc, what)
+
+
+def ndq_strerror(rc):
+    return lib().ndq_strerror(rc).decode()
+
+
+def ndq_code_bits(levels_or_M):
+    return lib().ndq_code_bits(levels_or_M)
+
+
+def ndq_packed_bytes(n, bits):
+    return lib().ndq_packed_bytes(n, bits)
+
+
+def ndq_num_buckets(n, bucket):
+    return lib().ndq_num_buckets(n, bucket)
+
+
+def ndq_absmax(g, bucket, kappa_out=None):
+    n = g.numel()
+    if kappa_out is None:
+        kappa_out = torch.empty(ndq_num_buckets(n, bucket), dtype=torch.float32, device=g.device)
+    _check(lib().ndq_absmax(_dev(g, "g"), _dt(g), n, bucket, _dev(kappa_out, "kappa_out"),
+                            _stream()), "ndq_absmax")
+    return kappa_out
+
+
+def _enc_outputs(g, bits, bucket, codes_out, steps_out):
+    n = g.numel()
+    if codes_out is None:
+        codes_out = torch.empty(ndq_packed_bytes(n, bits), dtype=torch.uint8, device=g.device)
+    if steps_out is None:
+        steps_out = torch.empty(ndq_num_buckets(n, bucket), dtype=torch.float32, device=g.device)
+    if codes_out.numel() * codes_out.element_size() < ndq_packed_bytes(n, bits):
+        raise ValueError("codes_out too small")
+    if steps_out.numel() < ndq_num_buckets(n, bucket):
+        raise ValueError("steps_out too small")
+    return codes_out, steps_out
+
+
+def ndq_dq_encode(g, delta, levels, bucket, d, codes_out=None, steps_out=None):
+    """-> (codes uint8 tensor, steps float32 tensor)"""
+    codes_out, steps_out = _enc_outputs(g, ndq_code_bits(levels), bucket, codes_out, steps_out)
+    _check(lib().ndq_dq_encode(_dev(g, "g"), _dt(g), g.numel(), delta, levels, bucket, C.byref(d),
+                               _dev(codes_out, "codes_out"), _dev(steps_out, "steps_out"),
+                               _stream()), "ndq_dq_encode")
+    return codes_out, steps_out
+
+
+def ndq_nested_encode(g, delta, levels, M, bucket, d, codes_out=None, steps_out=None):
+    codes_out, steps_out = _enc_outputs(g, ndq_code_bits(M), bucket, codes_out, steps_out)
+    _check(lib().ndq_nested_encode(_dev(g, "g"), _dt(g), g.numel(), delta, levels, M, bucket,
+                                   C.byref(d), _dev(codes_out, "codes_out"),
+                                   _dev(steps_out, "steps_out"), _stream()), "ndq_nested_encode")
+    return codes_out, steps_out
+
+
+def ndq_dq_decode(codes, n, levels, bucket, steps, d, out=None, accumulate=False):
+    if out is None:
+        if accumulate:
+            raise ValueError("accumulate needs an existing out")
+        out = torch.empty(n, dtype=torch.float32, device=codes.device)
+    if out.dtype != torch.float32 or out.numel() < n:
+        raise ValueError("out must hold n float32")
+    _check(lib().ndq_dq_decode(_dev(codes, "codes"), n, levels, bucket, _dev(steps, "steps"),
+                               C.byref(d), _dev(out, "out"), int(bool(accumulate)), _stream()),
+           "ndq_dq_decode")
+    return out
+
+
+def ndq_nested_decode(codes, n, M, bucket, steps, d, side, side_scale=1.0, out=None,
+                      accumulate=False):
+    if out is None:
+        if accumulate:
+            raise ValueError("accumulate needs an existing out")
+        out = torch.empty(n, dtype=torch.float32, device=codes.device)
+    if out.dtype != torch.float32 or out.numel() < n or side.dtype != torch.float32:
+        raise ValueError("out and side must hold n float32")
+    _check(lib().ndq_nested_decode(_dev(codes, "codes"), n, M, bucket, _dev(steps, "steps"),
+                                   C.byref(d), _dev(side, "side"), side_scale, _dev(out, "out"),
+                                   int(bool(accumulate)), _stream()), "ndq_nested_decode")
+    return out
+
+
+def ndq_aggregate(gs, scale=1.0, out=None):
+    n = gs[0].numel()
+    for g in gs:
+        if g.dtype != torch.float32 or g.numel() != n:
+            raise ValueError("all inputs must be float32 of equal length")
+    if out is None:
+        out = torch.empty(n, dtype=torch.float32, device=gs[0].device)
+    ptrs = (C.c_void_p * len(gs))(*[_dev(g, "gs[w]").value for g in gs])
+    _check(lib().ndq_aggregate(C.cast(ptrs, C.c_void_p), len(gs), n, scale, _dev(out, "out"),
+                               _stream()), "ndq_aggregate")
+    return out

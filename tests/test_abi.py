@@ -1,0 +1,101 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports
+every function the header declares, its size helpers agree with the oracle's,
+and argument validation rejects bad calls before anything is launched."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_1904_01197_amd import ndq
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "ndq.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ndq_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = _declared_functions()
+    assert set(names) == set(ndq.EXPORTS)
+    lib = ndq.lib()
+    for name in names:
+        assert getattr(lib, name) is not None
+
+
+def test_size_helpers_agree_with_oracle():
+    for x in range(0, 300):
+        assert ndq.ndq_code_bits(x) == oracle.code_bits(x)
+    for n in (0, 1, 7, 8, 9, 127, 128, 129, 65536, 25557032, 11173962, 1 << 27):
+        for bits in range(1, 9):
+            assert ndq.ndq_packed_bytes(n, bits) == oracle.packed_bytes(n, bits)
+            assert ndq.ndq_packed_bytes(n, bits) % 16 == 0
+        for bucket in (0, 64, 2048, 4096):
+            assert ndq.ndq_num_buckets(n, bucket) == oracle.num_buckets(n, bucket)
+    assert ndq.ndq_num_buckets(25557032, 2048) == 12480
+    assert ndq.ndq_num_buckets(1 << 27, 4096) == 32768
+    assert ndq.ndq_packed_bytes(65536, 2) == 16384
+
+
+def test_dither_struct_layout_matches_oracle_and_header():
+    assert C.sizeof(ndq.ndq_dither) == 24 == C.sizeof(oracle.Dither)
+    assert ndq.ndq_dither.offset.offset == 16 and ndq.ndq_dither.worker.offset == 12
+
+
+def test_validation_rejects_bad_arguments_without_a_gpu():
+    lib = ndq.lib()
+    d = ndq.ndq_dither(0, 0, 0, 0)
+    p = C.c_void_p(0x1000)           # aligned, never dereferenced: every call below fails first
+    null = C.c_void_p(0)
+    assert lib.ndq_dq_encode(p, 0, 64, 0.0, 1, 0, C.byref(d), p, p, null) == ndq.NDQ_EINVAL
+    assert lib.ndq_dq_encode(p, 0, 64, 0.0, 257, 0, C.byref(d), p, p, null) == ndq.NDQ_EINVAL
+    assert lib.ndq_dq_encode(p, 7, 64, 0.0, 4, 0, C.byref(d), p, p, null) == ndq.NDQ_EINVAL
+    assert lib.ndq_dq_encode(null, 0, 64, 0.0, 4, 0, C.byref(d), p, p, null) == ndq.NDQ_EINVAL
+    assert lib.ndq_dq_encode(p, 0, 64, 0.0, 4, 0, None, p, p, null) == ndq.NDQ_EINVAL
+    assert lib.ndq_dq_encode(p, 0, 64, float("nan"), 4, 0, C.byref(d), p, p, null) == ndq.NDQ_EINVAL
+    assert lib.ndq_dq_encode(p, 0, 64, 0.0, 4, 100, C.byref(d), p, p, null) == ndq.NDQ_EALIGN
+    assert lib.ndq_dq_encode(C.c_void_p(0x1004), 0, 64, 0.0, 4, 0, C.byref(d), p, p, null) \
+        == ndq.NDQ_EALIGN
+    assert lib.ndq_dq_encode(p, 0, 1 << 40, 0.0, 4, 0, C.byref(d), p, p, null) \
+        == ndq.NDQ_EUNSUPPORTED
+    d_bad = ndq.ndq_dither(0, 0, 0, 2)
+    assert lib.ndq_dq_encode(p, 0, 64, 0.0, 4, 0, C.byref(d_bad), p, p, null) == ndq.NDQ_EALIGN
+    assert lib.ndq_nested_encode(p, 0, 64, 0.0, 4, 1, 0, C.byref(d), p, p, null) == ndq.NDQ_EINVAL
+    assert lib.ndq_nested_decode(p, 64, 300, 0, p, C.byref(d), p, 1.0, p, 0, null) == ndq.NDQ_EINVAL
+    assert lib.ndq_nested_decode(p, 64, 4, 0, p, C.byref(d), null, 1.0, p, 0, null) == ndq.NDQ_EINVAL
+    q = C.c_void_p(0x1010)           # side and out overlap partially
+    assert lib.ndq_nested_decode(p, 64, 4, 0, p, C.byref(d), p, 1.0, q, 1, null) == ndq.NDQ_EINVAL
+    assert lib.ndq_dq_decode(p, 64, 4, 32, p, C.byref(d), p, 0, null) == ndq.NDQ_EALIGN
+    assert lib.ndq_aggregate(null, 2, 64, 1.0, p, null) == ndq.NDQ_EINVAL
+    ptrs = (C.c_void_p * 2)(0x1000, 0x2000)
+    assert lib.ndq_aggregate(C.cast(ptrs, C.c_void_p), 0, 64, 1.0, p, null) == ndq.NDQ_EINVAL
+    assert lib.ndq_aggregate(C.cast(ptrs, C.c_void_p), 2000, 64, 1.0, p, null) == ndq.NDQ_EINVAL
+    assert lib.ndq_absmax(p, 0, 64, 100, p, null) == ndq.NDQ_EALIGN
+    # n == 0 is a successful no-op that launches nothing
+    assert lib.ndq_dq_encode(null, 0, 0, 0.0, 4, 0, C.byref(d), null, null, null) == ndq.NDQ_OK
+    assert lib.ndq_dq_decode(null, 0, 4, 0, null, C.byref(d), null, 0, null) == ndq.NDQ_OK
+    assert lib.ndq_aggregate(C.cast(ptrs, C.c_void_p), 2, 0, 1.0, null, null) == ndq.NDQ_OK
+    for rc in (0, -1, -2, -3, -4, -99):
+        assert len(ndq.ndq_strerror(rc)) > 0
+
+
+def test_workload_generators_are_seeded_and_chunked():
+    from paper_1904_01197_amd import workloads as W
+    wl = W.CONFIGS[5]
+    a = W.gradient(wl, 1, n=3 * W.CHUNK + 17)
+    b = W.gradient(wl, 1, n=3 * W.CHUNK + 17)
+    assert np.array_equal(a, b) and a.dtype == np.uint16
+    assert np.array_equal(a[W.CHUNK:2 * W.CHUNK], W.gradient_chunk(wl, 1, 1, 3 * W.CHUNK + 17))
+    assert not np.array_equal(a, W.gradient(wl, 2, n=3 * W.CHUNK + 17))
+    x = np.array([1.0, 1.00390625, 1.01171875, -3.0e38, 1e-40], dtype=np.float32)
+    assert np.array_equal(W.bf16_bits_to_f32(W.f32_to_bf16_bits(x))[:3],
+                          np.array([1.0, 1.0, 1.015625], dtype=np.float32))
+    g2 = W.gradients(W.CONFIGS[2])
+    assert abs(np.corrcoef(g2[0], g2[1])[0, 1] - 0.9) < 0.005
+    g4 = W.gradients(W.CONFIGS[4], n=1 << 18)
+    assert abs(np.corrcoef(g4[1], g4[2])[0, 1] - 0.917) < 0.01
