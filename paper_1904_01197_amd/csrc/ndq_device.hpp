@@ -14,7 +14,14 @@ namespace ndq {
 constexpr int kWave = 64;           // CDNA wavefront
 constexpr int kWavesPerBlock = 4;   // 256-thread workgroups, waves work independently
 constexpr int kBlock = kWave * kWavesPerBlock;
-constexpr int kRows = 8;            // 16-byte loads in flight per lane and tile
+#ifndef NDQ_ENC_ROWS
+#define NDQ_ENC_ROWS 8
+#endif
+#ifndef NDQ_DEC_ROWS
+#define NDQ_DEC_ROWS 8
+#endif
+constexpr int kEncRows = NDQ_ENC_ROWS;   // 16-byte loads in flight per lane and encoder tile
+constexpr int kDecRows = NDQ_DEC_ROWS;   // 16-byte stores per lane and decoder tile
 
 // ---------------------------------------------------------------------------
 // Dither (Sec. 2.1 Remark 1: the receiver regenerates the dither from the same
@@ -175,12 +182,14 @@ template <> struct Elem<1> {               // bfloat16, widened exactly
     }
 };
 
-// Loads E elements at element offset `o` of a tile with `len` valid elements;
-// elements past the end read as zero.  The 16-byte path needs o % E == 0.
-template <int DT>
+// Loads E elements at element offset `o` of a tile with `len` valid elements.
+// FULL: the whole tile is valid, a plain 16-byte load (o % E == 0).  Otherwise
+// elements past the end read as zero.
+template <int DT, bool FULL>
 __device__ __forceinline__ uint4 load_row(const void* tile, uint32_t o, uint32_t len)
 {
     using T = Elem<DT>;
+    if (FULL) return *(const uint4*)((const typename T::scalar*)tile + o);
     uint4 raw = make_uint4(0u, 0u, 0u, 0u);
     if (o + T::E <= len) {
         raw = *(const uint4*)((const typename T::scalar*)tile + o);

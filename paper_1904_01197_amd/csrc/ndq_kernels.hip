@@ -27,31 +27,56 @@ struct EncodeArgs {
     float preset_step;     // > 0: bucket == 0 with a caller-set step
 };
 
-template <int DT> struct EncTile { static constexpr uint32_t N = kWave * Elem<DT>::E * kRows; };
+template <int DT> struct EncTile { static constexpr uint32_t N = kWave * Elem<DT>::E * kEncRows; };
 
-// Quantizes the tile held in `raw` and leaves its packed codes in `stage`
-// (stream order).  CHECK: the tile is ragged, zero the codes past `len`.
-template <int DT, int MODE, bool CHECK>
-__device__ __forceinline__ void quantize_tile(const uint4 (&raw)[kRows], uint32_t len, float inv,
-                                              uint64_t block0, const DitherStream& ds,
-                                              const Quant& qp, unsigned char* stage, int lane)
+// One wave encodes one tile: loads it (all 16-byte loads issued back to back),
+// finds the step, quantizes, and leaves the packed codes in `stage` in stream
+// order.  FULL: every element of the tile is valid -- no guards anywhere.
+template <int DT, int MODE, bool FUSED, bool FULL>
+__device__ __forceinline__ void encode_tile(const EncodeArgs& a, const TileRef& t, uint32_t tile_id,
+                                            unsigned char* stage, int lane)
 {
     using T = Elem<DT>;
     constexpr int E = T::E;
-    const uint32_t bits = qp.bits;
+    const uint32_t bits = a.qp.bits;
+    const typename T::scalar* tile = (const typename T::scalar*)a.g + t.start;
+    uint4 raw[kEncRows];
 #pragma unroll
-    for (int r = 0; r < kRows; ++r) {
+    for (int r = 0; r < kEncRows; ++r)
+        raw[r] = load_row<DT, FULL>(tile, (uint32_t)r * kWave * E + (uint32_t)lane * E, t.len);
+
+    float step;
+    if (FUSED) {
+        // the bucket is this tile: kappa = max|g| in registers (Sec. 3.1 eq. (2))
+        float m = 0.0f;
+#pragma unroll
+        for (int r = 0; r < kEncRows; ++r)
+#pragma unroll
+            for (int k = 0; k < E; ++k) m = __builtin_fmaxf(m, __builtin_fabsf(T::get(raw[r], k)));
+        step = step_from_kappa(wave_max(m), a.qp.levels);
+        if (lane == 0) a.steps[t.bucket] = step;
+    } else if (a.preset_step > 0.0f) {
+        step = a.preset_step;
+        if (tile_id == 0 && lane == 0) a.steps[0] = step;
+    } else {
+        step = a.steps[t.bucket];
+    }
+    const float inv = inv_step(step);
+    const uint64_t block0 = (a.index0 + t.start) >> 2;
+
+#pragma unroll
+    for (int r = 0; r < kEncRows; ++r) {
         const uint32_t o = (uint32_t)r * kWave * E + (uint32_t)lane * E;
         uint32_t quad[E / 4];
 #pragma unroll
         for (int h = 0; h < E / 4; ++h) {
             float v[4];
-            dither4(ds, block0 + (o >> 2) + h, v);
+            dither4(a.ds, block0 + (o >> 2) + h, v);
             uint32_t chunk = 0;
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
-                uint32_t c = encode_one<MODE>(T::get(raw[r], 4 * h + k), inv, v[k], qp);
-                if (CHECK && o + 4 * h + k >= len) c = 0;
+                uint32_t c = encode_one<MODE>(T::get(raw[r], 4 * h + k), inv, v[k], a.qp);
+                if (!FULL && o + 4 * h + k >= t.len) c = 0;
                 chunk |= c << (k * bits);
             }
             quad[h] = chunk;
@@ -78,6 +103,7 @@ __device__ __forceinline__ void quantize_tile(const uint4 (&raw)[kRows], uint32_
             }
         }
     }
+    if (lane == 0) *(uint64_t*)(stage + (size_t)EncTile<DT>::N / 8 * bits) = 0;  // pad unit
 }
 
 // FUSED: the bucket fits one tile; its max-norm is reduced in registers and
@@ -86,7 +112,6 @@ __device__ __forceinline__ void quantize_tile(const uint4 (&raw)[kRows], uint32_
 template <int DT, int MODE, bool FUSED>
 __global__ __launch_bounds__(kBlock) void encode_kernel(EncodeArgs a)
 {
-    using T = Elem<DT>;
     constexpr uint32_t TILE = EncTile<DT>::N;
     __shared__ __align__(16) unsigned char stage_all[kWavesPerBlock][TILE + 8];
     const int lane = threadIdx.x & (kWave - 1);
@@ -96,36 +121,8 @@ __global__ __launch_bounds__(kBlock) void encode_kernel(EncodeArgs a)
     const uint32_t tile_id = blockIdx.x * kWavesPerBlock + wave;
     const TileRef t = locate_tile(a.tl, tile_id, TILE);
     const uint32_t bits = a.qp.bits;
-    if (t.len != 0) {
-        const typename T::scalar* tile = (const typename T::scalar*)a.g + t.start;
-        uint4 raw[kRows];
-#pragma unroll
-        for (int r = 0; r < kRows; ++r)
-            raw[r] = load_row<DT>(tile, (uint32_t)r * kWave * T::E + (uint32_t)lane * T::E, t.len);
-
-        float step;
-        if (FUSED) {
-            float m = 0.0f;
-#pragma unroll
-            for (int r = 0; r < kRows; ++r)
-#pragma unroll
-                for (int k = 0; k < T::E; ++k) m = __builtin_fmaxf(m, __builtin_fabsf(T::get(raw[r], k)));
-            step = step_from_kappa(wave_max(m), a.qp.levels);
-            if (lane == 0) a.steps[t.bucket] = step;
-        } else if (a.preset_step > 0.0f) {
-            step = a.preset_step;
-            if (tile_id == 0 && lane == 0) a.steps[0] = step;
-        } else {
-            step = a.steps[t.bucket];
-        }
-        const float inv = inv_step(step);
-        const uint64_t block0 = (a.index0 + t.start) >> 2;
-        if (t.len == TILE)
-            quantize_tile<DT, MODE, false>(raw, t.len, inv, block0, a.ds, a.qp, stage, lane);
-        else
-            quantize_tile<DT, MODE, true>(raw, t.len, inv, block0, a.ds, a.qp, stage, lane);
-        if (lane == 0) *(uint64_t*)(stage + (size_t)TILE / 8 * bits) = 0;  // pad unit
-    }
+    if (t.len == TILE) encode_tile<DT, MODE, FUSED, true>(a, t, tile_id, stage, lane);
+    else if (t.len != 0) encode_tile<DT, MODE, FUSED, false>(a, t, tile_id, stage, lane);
     __syncthreads();
     if (t.len != 0) {
         const uint64_t byte0 = (t.start >> 3) * bits;                 // tile start is a multiple of 64
@@ -157,13 +154,21 @@ __global__ __launch_bounds__(kBlock) void absmax_kernel(const void* g, Tiling tl
     const TileRef t = locate_tile(tl, tile_id, TILE);
     if (t.len == 0) return;
     const typename T::scalar* tile = (const typename T::scalar*)g + t.start;
+    uint4 raw[kEncRows];
+    if (t.len == TILE) {
+#pragma unroll
+        for (int r = 0; r < kEncRows; ++r)
+            raw[r] = load_row<DT, true>(tile, (uint32_t)r * kWave * T::E + (uint32_t)lane * T::E, t.len);
+    } else {
+#pragma unroll
+        for (int r = 0; r < kEncRows; ++r)
+            raw[r] = load_row<DT, false>(tile, (uint32_t)r * kWave * T::E + (uint32_t)lane * T::E, t.len);
+    }
     float m = 0.0f;
 #pragma unroll
-    for (int r = 0; r < kRows; ++r) {
-        const uint4 raw = load_row<DT>(tile, (uint32_t)r * kWave * T::E + (uint32_t)lane * T::E, t.len);
+    for (int r = 0; r < kEncRows; ++r)
 #pragma unroll
-        for (int k = 0; k < T::E; ++k) m = __builtin_fmaxf(m, __builtin_fabsf(T::get(raw, k)));
-    }
+        for (int k = 0; k < T::E; ++k) m = __builtin_fmaxf(m, __builtin_fabsf(T::get(raw[r], k)));
     m = wave_max(m);
     // non-negative floats order like their bit patterns
     if (lane == 0) atomicMax(kappa_bits + t.bucket, __float_as_uint(m));
@@ -190,20 +195,17 @@ struct DecodeArgs {
     float side_scale;
 };
 
-constexpr uint32_t kDecTile = kWave * 4 * kRows;   // 2048 outputs per wave
+constexpr uint32_t kDecTile = kWave * 4 * kDecRows;   // outputs per wave
 
 enum Acc { kStore = 0, kAccumulate = 1, kAccumulateInPlace = 2 };  // in place: out == side
 
-template <int MODE, int ACC>
-__global__ __launch_bounds__(kBlock) void decode_kernel(DecodeArgs a)
+// One wave decodes one tile.  FULL: every element valid, no guards.  STRADDLE:
+// the code width does not divide 8, so four codes may cross a 32-bit word.
+template <int MODE, int ACC, bool FULL, bool STRADDLE>
+__device__ __forceinline__ void decode_tile(const DecodeArgs& a, const TileRef& t, int lane)
 {
-    const int lane = threadIdx.x & (kWave - 1);
-    const uint32_t tile_id = blockIdx.x * kWavesPerBlock + threadIdx.x / kWave;
-    const TileRef t = locate_tile(a.tl, tile_id, kDecTile);
-    if (t.len == 0) return;
     const uint32_t bits = a.qp.bits;
     const uint32_t mask = (1u << bits) - 1u;
-    const bool straddle = (32u % (4u * bits)) != 0u;   // four codes may cross a 32-bit word
     const uint32_t* codes32 = (const uint32_t*)(a.codes + (t.start >> 3) * bits);
     const float* side = a.side + t.start;
     float* out = a.out + t.start;
@@ -211,21 +213,25 @@ __global__ __launch_bounds__(kBlock) void decode_kernel(DecodeArgs a)
     const float inv = inv_step(step);
     const uint64_t block0 = (a.index0 + t.start) >> 2;
 
-    uint32_t packed[kRows];
-    float4 y[kRows], prev[kRows];
+    uint32_t packed[kDecRows];
+    float4 y[kDecRows], prev[kDecRows];
 #pragma unroll
-    for (int r = 0; r < kRows; ++r) {
+    for (int r = 0; r < kDecRows; ++r) {
         const uint32_t o = (uint32_t)r * kWave * 4 + (uint32_t)lane * 4;
         packed[r] = 0;
         y[r] = make_float4(0.f, 0.f, 0.f, 0.f);
         prev[r] = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (o < t.len) {
+        if (FULL || o < t.len) {
             const uint32_t bit = o * bits;
             const uint32_t w = bit >> 5, sh = bit & 31u;
-            uint64_t window = codes32[w];
-            if (straddle && sh + 4u * bits > 32u) window |= (uint64_t)codes32[w + 1] << 32;
-            packed[r] = (uint32_t)(window >> sh);
-            if (o + 4 <= t.len) {
+            if (STRADDLE) {
+                uint64_t window = codes32[w];
+                if (sh + 4u * bits > 32u) window |= (uint64_t)codes32[w + 1] << 32;
+                packed[r] = (uint32_t)(window >> sh);
+            } else {
+                packed[r] = codes32[w] >> sh;
+            }
+            if (FULL || o + 4 <= t.len) {
                 if (MODE != kDq) y[r] = *(const float4*)(side + o);
                 if (ACC == kAccumulate) prev[r] = *(const float4*)(out + o);
             } else {
@@ -242,9 +248,9 @@ __global__ __launch_bounds__(kBlock) void decode_kernel(DecodeArgs a)
         }
     }
 #pragma unroll
-    for (int r = 0; r < kRows; ++r) {
+    for (int r = 0; r < kDecRows; ++r) {
         const uint32_t o = (uint32_t)r * kWave * 4 + (uint32_t)lane * 4;
-        if (o >= t.len) continue;
+        if (!FULL && o >= t.len) continue;
         float v[4];
         dither4(a.ds, block0 + (o >> 2), v);
         const float ys[4] = {y[r].x, y[r].y, y[r].z, y[r].w};
@@ -265,7 +271,7 @@ __global__ __launch_bounds__(kBlock) void decode_kernel(DecodeArgs a)
             else if (ACC == kAccumulate) res[k] = ps[k] + val;
             else res[k] = ys[k] + val;
         }
-        if (o + 4 <= t.len) {
+        if (FULL || o + 4 <= t.len) {
             *(float4*)(out + o) = make_float4(res[0], res[1], res[2], res[3]);
         } else {
 #pragma unroll
@@ -273,6 +279,16 @@ __global__ __launch_bounds__(kBlock) void decode_kernel(DecodeArgs a)
                 if (o + k < t.len) out[o + k] = res[k];
         }
     }
+}
+
+template <int MODE, int ACC, bool STRADDLE>
+__global__ __launch_bounds__(kBlock) void decode_kernel(DecodeArgs a)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    const uint32_t tile_id = blockIdx.x * kWavesPerBlock + threadIdx.x / kWave;
+    const TileRef t = locate_tile(a.tl, tile_id, kDecTile);
+    if (t.len == kDecTile) decode_tile<MODE, ACC, true, STRADDLE>(a, t, lane);
+    else if (t.len != 0) decode_tile<MODE, ACC, false, STRADDLE>(a, t, lane);
 }
 
 // ---------------------------------------------------------------------------
@@ -453,14 +469,22 @@ static int encode_common(const void* g, ndq_dtype dt, size_t n, float delta, uin
     return run_encode<1, kNestedAnyM>(a, fused, s);
 }
 
+template <int MODE, bool STRADDLE>
+static int run_decode2(const DecodeArgs& a, int acc, hipStream_t s)
+{
+    const dim3 grid(blocks_for(a.tl.total_tiles)), block(kBlock);
+    if (acc == kStore) hipLaunchKernelGGL((decode_kernel<MODE, kStore, STRADDLE>), grid, block, 0, s, a);
+    else if (acc == kAccumulate) hipLaunchKernelGGL((decode_kernel<MODE, kAccumulate, STRADDLE>), grid, block, 0, s, a);
+    else hipLaunchKernelGGL((decode_kernel<MODE, kAccumulateInPlace, STRADDLE>), grid, block, 0, s, a);
+    return launched();
+}
+
 template <int MODE>
 static int run_decode(const DecodeArgs& a, int acc, hipStream_t s)
 {
-    const dim3 grid(blocks_for(a.tl.total_tiles)), block(kBlock);
-    if (acc == kStore) hipLaunchKernelGGL((decode_kernel<MODE, kStore>), grid, block, 0, s, a);
-    else if (acc == kAccumulate) hipLaunchKernelGGL((decode_kernel<MODE, kAccumulate>), grid, block, 0, s, a);
-    else hipLaunchKernelGGL((decode_kernel<MODE, kAccumulateInPlace>), grid, block, 0, s, a);
-    return launched();
+    // four b-bit codes sit inside one 32-bit word exactly when 4b divides 32
+    const bool straddle = (32u % (4u * a.qp.bits)) != 0u;
+    return straddle ? run_decode2<MODE, true>(a, acc, s) : run_decode2<MODE, false>(a, acc, s);
 }
 
 static int decode_common(const void* codes, size_t n, uint32_t levels, uint32_t M, bool nested,
