@@ -4,7 +4,7 @@
 One "step" is one pass of the whole path over one batch of synthetic gradients
 already resident in HBM: every worker's encode (scale, dither, quantize, pack),
 then the server's decode chain with side information and running-sum
-aggregation.  Prints ONE JSON line (see README / DESIGN for the fields).
+aggregation.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 5] [--no-cpu]
 """
