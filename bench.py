@@ -33,6 +33,9 @@ def parse_args():
     ap.add_argument("--cpu-sample", type=int, default=1 << 27,
                     help="elements per worker the oracle is timed on")
     ap.add_argument("--kernel-reps", type=int, default=20)
+    ap.add_argument("--schedule", choices=["serial", "overlap"], default="serial",
+                    help="serial: all launches on one stream; overlap: encoders and decoders "
+                         "on two streams (encode w+1 beside decode w)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch a plain copy of 2^28 floats (ndq_aggregate with W=1, "
                          "scale=1: 1 GiB read + 1 GiB written) so that a counter run has a "
@@ -110,12 +113,17 @@ def main():
         del src, dst
 
     # ---- whole path: W warm-up steps, then exactly K timed steps ----------------
+    if args.schedule == "overlap":
+        ts = pipeline.TwoStreams(wl.W)
+        one_step = lambda: pipeline.step_overlapped(wl, dev, bufs, ds, ts, preset)
+    else:
+        one_step = lambda: pipeline.step(wl, dev, bufs, ds, preset)
     for _ in range(args.warmup):
-        pipeline.step(wl, dev, bufs, ds, preset)
+        one_step()
     torch.cuda.synchronize()
     t_start = time.perf_counter()
     for _ in range(args.steps):
-        pipeline.step(wl, dev, bufs, ds, preset)
+        one_step()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t_start
     ms_per_step = elapsed * 1e3 / args.steps
@@ -209,7 +217,7 @@ def main():
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": wl.name, "W": wl.W, "n_per_worker": n, "input_dtype": wl.dtype,
-                   "bucket": wl.bucket, "plan": ["%s%d" % p for p in wl.plan],
+                   "bucket": wl.bucket, "schedule": args.schedule, "plan": ["%s%d" % p for p in wl.plan],
                    "launches_per_step": sum(r["launches_per_step"] for r in kernels)},
         "gelem_per_s": round(wl.W * n / (ms_per_step * 1e-3) / 1e9, 3),
         "step_algorithmic_bytes": step_bytes,

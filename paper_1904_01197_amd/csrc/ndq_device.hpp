@@ -17,11 +17,20 @@ constexpr int kBlock = kWave * kWavesPerBlock;
 #ifndef NDQ_ENC_ROWS
 #define NDQ_ENC_ROWS 8
 #endif
-#ifndef NDQ_DEC_ROWS
-#define NDQ_DEC_ROWS 8
+#ifndef NDQ_DEC_ROWS_STREAM
+#define NDQ_DEC_ROWS_STREAM 8
+#endif
+#ifndef NDQ_DEC_ROWS_UPDATE
+#define NDQ_DEC_ROWS_UPDATE 1
 #endif
 constexpr int kEncRows = NDQ_ENC_ROWS;   // 16-byte loads in flight per lane and encoder tile
-constexpr int kDecRows = NDQ_DEC_ROWS;   // 16-byte stores per lane and decoder tile
+// 16-byte stores per lane and decoder tile.  A decoder that only writes values
+// (DQSG, no accumulate) is bound by load latency per wave and wants long tiles;
+// one that also reads values (side information, running sum) moves twice the
+// bytes per element and measures fastest when a wave covers 1 KB at a time, so
+// that the reads and writes in flight on the chip stay within a few MB of HBM.
+constexpr int kDecRowsStream = NDQ_DEC_ROWS_STREAM;
+constexpr int kDecRowsUpdate = NDQ_DEC_ROWS_UPDATE;
 
 // ---------------------------------------------------------------------------
 // Dither (Sec. 2.1 Remark 1: the receiver regenerates the dither from the same
@@ -35,6 +44,12 @@ struct DitherStream {
     uint32_t worker;       // worker index p
 };
 
+__device__ __forceinline__ uint32_t xor3(uint32_t a, uint32_t b, uint32_t c)
+{
+    // gfx950 three-input bitwise op; truth table 0x96 = a ^ b ^ c
+    return __builtin_amdgcn_bitop3_b32(a, b, c, 0x96);
+}
+
 __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
                                               uint32_t k0, uint32_t k1, uint32_t (&out)[4])
 {
@@ -42,8 +57,8 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
     for (int round = 0; round < 10; ++round) {
         const uint64_t p0 = (uint64_t)0xD2511F53u * c0;
         const uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
-        const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
-        const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        const uint32_t n0 = xor3((uint32_t)(p1 >> 32), c1, k0);
+        const uint32_t n2 = xor3((uint32_t)(p0 >> 32), c3, k1);
         c1 = (uint32_t)p1;
         c3 = (uint32_t)p0;
         c0 = n0;
@@ -88,10 +103,11 @@ __device__ __forceinline__ float inv_step(float step)
 // ---------------------------------------------------------------------------
 // Quantizer parameters shared by encoder and decoder.
 //   kDq           : DQSG, clipped to `levels` indices            (Algorithm 1)
+//   kDqNarrow     : the same for codes of at most 6 bits (encoder packs in float)
 //   kNestedPow2   : NDQSG, M a power of two (mask / exact scale) (Algorithm 2)
 //   kNestedAnyM   : NDQSG, any M in [2,256]
 // ---------------------------------------------------------------------------
-enum Mode { kDq = 0, kNestedPow2 = 1, kNestedAnyM = 2 };
+enum Mode { kDq = 0, kNestedPow2 = 1, kNestedAnyM = 2, kDqNarrow = 3 };  // kDqNarrow: DQSG, codes of <= 6 bits
 
 struct Quant {
     float q_min_f, q_max_f;  // DQSG index range as floats
@@ -100,14 +116,20 @@ struct Quant {
     uint32_t M;              // nesting ratio Delta_2/Delta_1 (nested modes)
     float M_f, inv_M_f;      // (float)M and, for powers of two, its exact reciprocal
     uint32_t bits;           // code width
+    float pack_bias;         // kDqNarrow: -q_min * sum_k 2^(k*bits), k = 0..3
 };
 
-// Index of eq. (2) / Algorithm 1, as a code in [0, levels).
+// Clipped index of eq. (2) / Algorithm 1, still as a float (an exact small integer).
+__device__ __forceinline__ float dq_index_f(float g, float inv, float v, const Quant& qp)
+{
+    const float r = __builtin_rintf(__builtin_fmaf(g, inv, v));
+    return __builtin_fminf(__builtin_fmaxf(r, qp.q_min_f), qp.q_max_f);
+}
+
+// The same as a code in [0, levels).
 __device__ __forceinline__ uint32_t dq_code(float g, float inv, float v, const Quant& qp)
 {
-    float r = __builtin_rintf(__builtin_fmaf(g, inv, v));
-    r = __builtin_fminf(__builtin_fmaxf(r, qp.q_min_f), qp.q_max_f);
-    return (uint32_t)((int32_t)r - qp.q_min);
+    return (uint32_t)((int32_t)dq_index_f(g, inv, v, qp) - qp.q_min);
 }
 
 // Fine index of eq. (7) reduced modulo M.
@@ -126,28 +148,31 @@ __device__ __forceinline__ uint32_t nested_code(float g, float inv, float v, con
 template <int MODE>
 __device__ __forceinline__ uint32_t encode_one(float g, float inv, float v, const Quant& qp)
 {
-    if (MODE == kDq) return dq_code(g, inv, v, qp);
+    if (MODE == kDq || MODE == kDqNarrow) return dq_code(g, inv, v, qp);
     return nested_code<MODE>(g, inv, v, qp);
 }
 
 // Reconstruction Delta * (q - v) of Algorithm 1's server step.
-__device__ __forceinline__ float index_value(int32_t q, float step, float v)
+__device__ __forceinline__ float index_value(float q, float step, float v)
 {
-    const float centred = (float)q - v;
+    const float centred = q - v;
     return step * centred;
 }
 
-// Coset decoder of eq. (8), alpha = 1: integer congruent to m nearest to y/Delta + v.
+// Coset decoder of eq. (8), alpha = 1: the integer congruent to m (mod M) nearest
+// to y/Delta + v, returned as a float.  m + M*k is formed by one fma: exact while
+// below 2^24 and otherwise rounded once, exactly like converting the integer.
 template <int MODE>
-__device__ __forceinline__ int32_t coset_index(uint32_t m, float y, float inv, float v,
+__device__ __forceinline__ float coset_index_f(uint32_t m, float y, float inv, float v,
                                                const Quant& qp)
 {
+    const float m_f = (float)m;
     const float c = __builtin_fmaf(y, inv, v);
-    const float diff = c - (float)m;
+    const float diff = c - m_f;
     float k = (MODE == kNestedPow2) ? diff * qp.inv_M_f : diff / qp.M_f;
     k = __builtin_rintf(k);
     k = __builtin_fminf(__builtin_fmaxf(k, -4194304.0f), 4194304.0f);
-    return (int32_t)m + (int32_t)qp.M * (int32_t)k;
+    return __builtin_fmaf(k, qp.M_f, m_f);
 }
 
 // ---------------------------------------------------------------------------
@@ -166,6 +191,17 @@ template <> struct Elem<0> {               // binary32
     {
         return ((const uint32_t*)p)[i];
     }
+    // running max of |x| over the 16 bytes; the carrier is a float
+    using maxacc = float;
+    __device__ static __forceinline__ float max_init() { return 0.0f; }
+    __device__ static __forceinline__ float max_update(float m, const uint4& raw)
+    {
+        m = __builtin_fmaxf(m, __builtin_fmaxf(__builtin_fabsf(__uint_as_float(raw.x)),
+                                               __builtin_fabsf(__uint_as_float(raw.y))));
+        return __builtin_fmaxf(m, __builtin_fmaxf(__builtin_fabsf(__uint_as_float(raw.z)),
+                                                  __builtin_fabsf(__uint_as_float(raw.w))));
+    }
+    __device__ static __forceinline__ float max_final(float m) { return m; }
 };
 template <> struct Elem<1> {               // bfloat16, widened exactly
     static constexpr int E = 8;
@@ -179,6 +215,28 @@ template <> struct Elem<1> {               // bfloat16, widened exactly
     __device__ static __forceinline__ uint32_t bits_of(const void* p, size_t i)
     {
         return ((const uint16_t*)p)[i];
+    }
+    // |x| of a bfloat16 orders like its low 15 bits, so the running max is kept
+    // as two 16-bit integers per word and widened once at the end
+    using maxacc = uint32_t;
+    __device__ static __forceinline__ uint32_t max_init() { return 0u; }
+    __device__ static __forceinline__ uint32_t pk_max(uint32_t a, uint32_t b)
+    {
+        typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
+        const u16x2 x = __builtin_bit_cast(u16x2, a), y = __builtin_bit_cast(u16x2, b);
+        return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(x, y));
+    }
+    __device__ static __forceinline__ uint32_t max_update(uint32_t m, const uint4& raw)
+    {
+        m = pk_max(m, raw.x & 0x7FFF7FFFu);
+        m = pk_max(m, raw.y & 0x7FFF7FFFu);
+        m = pk_max(m, raw.z & 0x7FFF7FFFu);
+        return pk_max(m, raw.w & 0x7FFF7FFFu);
+    }
+    __device__ static __forceinline__ float max_final(uint32_t m)
+    {
+        const uint32_t hi = m >> 16, lo = m & 0xFFFFu;
+        return __uint_as_float((hi > lo ? hi : lo) << 16);
     }
 };
 

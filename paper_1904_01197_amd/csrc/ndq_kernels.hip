@@ -48,12 +48,10 @@ __device__ __forceinline__ void encode_tile(const EncodeArgs& a, const TileRef& 
     float step;
     if (FUSED) {
         // the bucket is this tile: kappa = max|g| in registers (Sec. 3.1 eq. (2))
-        float m = 0.0f;
+        typename T::maxacc m = T::max_init();
 #pragma unroll
-        for (int r = 0; r < kEncRows; ++r)
-#pragma unroll
-            for (int k = 0; k < E; ++k) m = __builtin_fmaxf(m, __builtin_fabsf(T::get(raw[r], k)));
-        step = step_from_kappa(wave_max(m), a.qp.levels);
+        for (int r = 0; r < kEncRows; ++r) m = T::max_update(m, raw[r]);
+        step = step_from_kappa(wave_max(T::max_final(m)), a.qp.levels);
         if (lane == 0) a.steps[t.bucket] = step;
     } else if (a.preset_step > 0.0f) {
         step = a.preset_step;
@@ -73,11 +71,23 @@ __device__ __forceinline__ void encode_tile(const EncodeArgs& a, const TileRef& 
             float v[4];
             dither4(a.ds, block0 + (o >> 2) + h, v);
             uint32_t chunk = 0;
+            if (MODE == kDqNarrow) {
+                // codes of <= 6 bits: sum (q_k - q_min) 2^(k b) stays an exact float below 2^24
+                float acc = a.qp.pack_bias;
 #pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                uint32_t c = encode_one<MODE>(T::get(raw[r], 4 * h + k), inv, v[k], a.qp);
-                if (!FULL && o + 4 * h + k >= t.len) c = 0;
-                chunk |= c << (k * bits);
+                for (int k = 0; k < 4; ++k) {
+                    float q = dq_index_f(T::get(raw[r], 4 * h + k), inv, v[k], a.qp);
+                    if (!FULL && o + 4 * h + k >= t.len) q = a.qp.q_min_f;
+                    acc = __builtin_fmaf(q, __uint_as_float((127u + k * bits) << 23), acc);
+                }
+                chunk = (uint32_t)acc;
+            } else {
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    uint32_t c = encode_one<MODE>(T::get(raw[r], 4 * h + k), inv, v[k], a.qp);
+                    if (!FULL && o + 4 * h + k >= t.len) c = 0;
+                    chunk |= c << (k * bits);
+                }
             }
             quad[h] = chunk;
         }
@@ -115,7 +125,7 @@ __global__ __launch_bounds__(kBlock) void encode_kernel(EncodeArgs a)
     constexpr uint32_t TILE = EncTile<DT>::N;
     __shared__ __align__(16) unsigned char stage_all[kWavesPerBlock][TILE + 8];
     const int lane = threadIdx.x & (kWave - 1);
-    const int wave = threadIdx.x / kWave;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);   // wave-uniform
     unsigned char* stage = stage_all[wave];
 
     const uint32_t tile_id = blockIdx.x * kWavesPerBlock + wave;
@@ -150,7 +160,8 @@ __global__ __launch_bounds__(kBlock) void absmax_kernel(const void* g, Tiling tl
     using T = Elem<DT>;
     constexpr uint32_t TILE = EncTile<DT>::N;
     const int lane = threadIdx.x & (kWave - 1);
-    const uint32_t tile_id = blockIdx.x * kWavesPerBlock + threadIdx.x / kWave;
+    const uint32_t tile_id =
+        blockIdx.x * kWavesPerBlock + __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     const TileRef t = locate_tile(tl, tile_id, TILE);
     if (t.len == 0) return;
     const typename T::scalar* tile = (const typename T::scalar*)g + t.start;
@@ -164,12 +175,10 @@ __global__ __launch_bounds__(kBlock) void absmax_kernel(const void* g, Tiling tl
         for (int r = 0; r < kEncRows; ++r)
             raw[r] = load_row<DT, false>(tile, (uint32_t)r * kWave * T::E + (uint32_t)lane * T::E, t.len);
     }
-    float m = 0.0f;
+    typename T::maxacc acc = T::max_init();
 #pragma unroll
-    for (int r = 0; r < kEncRows; ++r)
-#pragma unroll
-        for (int k = 0; k < T::E; ++k) m = __builtin_fmaxf(m, __builtin_fabsf(T::get(raw[r], k)));
-    m = wave_max(m);
+    for (int r = 0; r < kEncRows; ++r) acc = T::max_update(acc, raw[r]);
+    const float m = wave_max(T::max_final(acc));
     // non-negative floats order like their bit patterns
     if (lane == 0) atomicMax(kappa_bits + t.bucket, __float_as_uint(m));
 }
@@ -195,7 +204,10 @@ struct DecodeArgs {
     float side_scale;
 };
 
-constexpr uint32_t kDecTile = kWave * 4 * kDecRows;   // outputs per wave
+template <int ROWS> struct DecTile { static constexpr uint32_t N = kWave * 4 * ROWS; };  // outputs per wave
+template <int MODE, int ACC> struct DecRows {
+    static constexpr int R = (MODE == kDq && ACC == 0) ? kDecRowsStream : kDecRowsUpdate;
+};
 
 enum Acc { kStore = 0, kAccumulate = 1, kAccumulateInPlace = 2 };  // in place: out == side
 
@@ -213,6 +225,7 @@ __device__ __forceinline__ void decode_tile(const DecodeArgs& a, const TileRef& 
     const float inv = inv_step(step);
     const uint64_t block0 = (a.index0 + t.start) >> 2;
 
+    constexpr int kDecRows = DecRows<MODE, ACC>::R;
     uint32_t packed[kDecRows];
     float4 y[kDecRows], prev[kDecRows];
 #pragma unroll
@@ -259,12 +272,12 @@ __device__ __forceinline__ void decode_tile(const DecodeArgs& a, const TileRef& 
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
             const uint32_t c = (packed[r] >> (k * bits)) & mask;
-            int32_t q;
+            float q;
             if (MODE == kDq) {
-                q = (int32_t)c + a.qp.q_min;
+                q = (float)((int32_t)c + a.qp.q_min);
             } else {
                 const float yk = ys[k] * a.side_scale;
-                q = coset_index<MODE>(c, yk, inv, v[k], a.qp);
+                q = coset_index_f<MODE>(c, yk, inv, v[k], a.qp);
             }
             const float val = index_value(q, step, v[k]);
             if (ACC == kStore) res[k] = val;
@@ -285,9 +298,11 @@ template <int MODE, int ACC, bool STRADDLE>
 __global__ __launch_bounds__(kBlock) void decode_kernel(DecodeArgs a)
 {
     const int lane = threadIdx.x & (kWave - 1);
-    const uint32_t tile_id = blockIdx.x * kWavesPerBlock + threadIdx.x / kWave;
-    const TileRef t = locate_tile(a.tl, tile_id, kDecTile);
-    if (t.len == kDecTile) decode_tile<MODE, ACC, true, STRADDLE>(a, t, lane);
+    const uint32_t tile_id =
+        blockIdx.x * kWavesPerBlock + __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    constexpr uint32_t TILE = DecTile<DecRows<MODE, ACC>::R>::N;
+    const TileRef t = locate_tile(a.tl, tile_id, TILE);
+    if (t.len == TILE) decode_tile<MODE, ACC, true, STRADDLE>(a, t, lane);
     else if (t.len != 0) decode_tile<MODE, ACC, false, STRADDLE>(a, t, lane);
 }
 
@@ -380,6 +395,9 @@ static int make_quant(uint32_t levels, uint32_t M, bool nested, Quant* qp)
     qp->M_f = (float)qp->M;
     qp->inv_M_f = 1.0f / qp->M_f;   // exact when M is a power of two, unused otherwise
     qp->bits = code_bits(nested ? M : levels);
+    float weights = 0.0f;
+    for (uint32_t k = 0; k < 4; ++k) weights += (float)(1u << (k * qp->bits < 31u ? k * qp->bits : 31u));
+    qp->pack_bias = -qp->q_min_f * weights;   // exact for bits <= 6, the only user
     return NDQ_OK;
 }
 
@@ -458,33 +476,45 @@ static int encode_common(const void* g, ndq_dtype dt, size_t n, float delta, uin
                            s, steps_out, K, levels);
         if (launched() != NDQ_OK) return NDQ_ELAUNCH;
     }
-    const int mode = !nested ? kDq : (is_pow2(M) ? kNestedPow2 : kNestedAnyM);
+    const int mode = !nested ? (a.qp.bits <= 6u ? kDqNarrow : kDq)
+                             : (is_pow2(M) ? kNestedPow2 : kNestedAnyM);
     if (dt == NDQ_F32) {
+        if (mode == kDqNarrow) return run_encode<0, kDqNarrow>(a, fused, s);
         if (mode == kDq) return run_encode<0, kDq>(a, fused, s);
         if (mode == kNestedPow2) return run_encode<0, kNestedPow2>(a, fused, s);
         return run_encode<0, kNestedAnyM>(a, fused, s);
     }
+    if (mode == kDqNarrow) return run_encode<1, kDqNarrow>(a, fused, s);
     if (mode == kDq) return run_encode<1, kDq>(a, fused, s);
     if (mode == kNestedPow2) return run_encode<1, kNestedPow2>(a, fused, s);
     return run_encode<1, kNestedAnyM>(a, fused, s);
 }
 
-template <int MODE, bool STRADDLE>
-static int run_decode2(const DecodeArgs& a, int acc, hipStream_t s)
+template <int MODE, int ACC, bool STRADDLE>
+static int run_decode3(DecodeArgs a, uint64_t n, uint32_t bucket, hipStream_t s)
 {
-    const dim3 grid(blocks_for(a.tl.total_tiles)), block(kBlock);
-    if (acc == kStore) hipLaunchKernelGGL((decode_kernel<MODE, kStore, STRADDLE>), grid, block, 0, s, a);
-    else if (acc == kAccumulate) hipLaunchKernelGGL((decode_kernel<MODE, kAccumulate, STRADDLE>), grid, block, 0, s, a);
-    else hipLaunchKernelGGL((decode_kernel<MODE, kAccumulateInPlace, STRADDLE>), grid, block, 0, s, a);
+    const int rc = make_tiling(n, bucket, DecTile<DecRows<MODE, ACC>::R>::N, &a.tl);
+    if (rc != NDQ_OK) return rc;
+    hipLaunchKernelGGL((decode_kernel<MODE, ACC, STRADDLE>), dim3(blocks_for(a.tl.total_tiles)),
+                       dim3(kBlock), 0, s, a);
     return launched();
 }
 
+template <int MODE, bool STRADDLE>
+static int run_decode2(const DecodeArgs& a, uint64_t n, uint32_t bucket, int acc, hipStream_t s)
+{
+    if (acc == kStore) return run_decode3<MODE, kStore, STRADDLE>(a, n, bucket, s);
+    if (acc == kAccumulate) return run_decode3<MODE, kAccumulate, STRADDLE>(a, n, bucket, s);
+    return run_decode3<MODE, kAccumulateInPlace, STRADDLE>(a, n, bucket, s);
+}
+
 template <int MODE>
-static int run_decode(const DecodeArgs& a, int acc, hipStream_t s)
+static int run_decode(const DecodeArgs& a, uint64_t n, uint32_t bucket, int acc, hipStream_t s)
 {
     // four b-bit codes sit inside one 32-bit word exactly when 4b divides 32
     const bool straddle = (32u % (4u * a.qp.bits)) != 0u;
-    return straddle ? run_decode2<MODE, true>(a, acc, s) : run_decode2<MODE, false>(a, acc, s);
+    return straddle ? run_decode2<MODE, true>(a, n, bucket, acc, s)
+                    : run_decode2<MODE, false>(a, n, bucket, acc, s);
 }
 
 static int decode_common(const void* codes, size_t n, uint32_t levels, uint32_t M, bool nested,
@@ -507,8 +537,6 @@ static int decode_common(const void* codes, size_t n, uint32_t levels, uint32_t 
         const uintptr_t s0 = (uintptr_t)side, o0 = (uintptr_t)out, len = (uintptr_t)n * 4u;
         if (s0 < o0 + len && o0 < s0 + len) return NDQ_EINVAL;
     }
-    rc = make_tiling(n, bucket, kDecTile, &a.tl);
-    if (rc != NDQ_OK) return rc;
     a.codes = (const unsigned char*)codes;
     a.steps = steps;
     a.side = nested ? side : out;
@@ -519,9 +547,9 @@ static int decode_common(const void* codes, size_t n, uint32_t levels, uint32_t 
     hipStream_t s = (hipStream_t)stream;
     int acc = accumulate ? kAccumulate : kStore;
     if (nested && accumulate && side == out) acc = kAccumulateInPlace;
-    if (!nested) return run_decode<kDq>(a, acc, s);
-    if (is_pow2(M)) return run_decode<kNestedPow2>(a, acc, s);
-    return run_decode<kNestedAnyM>(a, acc, s);
+    if (!nested) return run_decode<kDq>(a, n, bucket, acc, s);
+    if (is_pow2(M)) return run_decode<kNestedPow2>(a, n, bucket, acc, s);
+    return run_decode<kNestedAnyM>(a, n, bucket, acc, s);
 }
 
 }  // namespace ndq

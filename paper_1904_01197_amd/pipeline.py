@@ -94,6 +94,52 @@ def step(wl: Workload, grads, bufs: Buffers, ds, preset_step: float = 0.0):
     return decode_chain(wl, n, bufs, ds)
 
 
+class TwoStreams:
+    """Two HIP streams (default priority) and one event per worker, so that the
+    compute-bound encoders overlap the bandwidth-bound decoders."""
+
+    def __init__(self, W: int):
+        self.enc = torch.cuda.Stream()
+        self.dec = torch.cuda.Stream()
+        self.encoded = [torch.cuda.Event() for _ in range(W)]
+
+
+def step_overlapped(wl: Workload, grads, bufs: Buffers, ds, ts: TwoStreams,
+                    preset_step: float = 0.0):
+    """The same work as step(), enqueued on two streams: worker w's decode waits
+    only for worker w's encode (and the decode before it), so encode w+1 runs
+    beside decode w.  Results are identical to step()."""
+    assert not (wl.shared_step and preset_step == 0.0), "shared step must be preset"
+    n = grads[0].numel()
+    main = torch.cuda.current_stream()
+    ts.enc.wait_stream(main)
+    ts.dec.wait_stream(main)
+    with torch.cuda.stream(ts.enc):
+        for w, (kind, arg) in enumerate(wl.plan):
+            if kind == "dq":
+                ndq.ndq_dq_encode(grads[w], preset_step, arg, wl.bucket, ds[w], bufs.codes[w],
+                                  bufs.steps[w])
+            else:
+                ndq.ndq_nested_encode(grads[w], preset_step, wl.fine_levels, arg, wl.bucket,
+                                      ds[w], bufs.codes[w], bufs.steps[w])
+            ts.encoded[w].record(ts.enc)
+    S = bufs.total
+    with torch.cuda.stream(ts.dec):
+        for w, (kind, arg) in enumerate(wl.plan):
+            ts.dec.wait_event(ts.encoded[w])
+            if kind == "dq":
+                ndq.ndq_dq_decode(bufs.codes[w], n, arg, wl.bucket, bufs.steps[w], ds[w], S,
+                                  accumulate=w > 0)
+            else:
+                ndq.ndq_nested_decode(bufs.codes[w], n, arg, wl.bucket, bufs.steps[w], ds[w], S,
+                                      1.0 / w, S, accumulate=True)
+        if wl.out_scale != 1.0:
+            ndq.ndq_aggregate([S], wl.out_scale, S)
+    main.wait_stream(ts.enc)
+    main.wait_stream(ts.dec)
+    return S
+
+
 def to_device(wl: Workload, host_grads, device="cuda"):
     out = []
     for g in host_grads:

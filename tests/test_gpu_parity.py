@@ -397,3 +397,22 @@ def test_runs_are_deterministic():
     ds2 = pipeline.dithers(wl, step=1)
     pipeline.step(wl, dev, b2, ds2)
     assert not torch.equal(b1.codes[0], b2.codes[0])
+
+
+def test_two_stream_schedule_gives_identical_results():
+    """Encoders and decoders on two streams (encode w+1 beside decode w) must
+    produce exactly what the single-stream schedule does."""
+    wl = workloads.CONFIGS[5]
+    n = (1 << 22) + 4096 * 3
+    dev = pipeline.to_device(wl, workloads.gradients(wl, n))
+    ds = pipeline.dithers(wl)
+    b1, b2 = pipeline.allocate(wl, n), pipeline.allocate(wl, n)
+    ref = pipeline.step(wl, dev, b1, ds).clone()
+    ts = pipeline.TwoStreams(wl.W)
+    for _ in range(3):
+        b2.total.zero_()
+        out = pipeline.step_overlapped(wl, dev, b2, ds, ts)
+        torch.cuda.synchronize()
+        assert torch.equal(out, ref)
+    for w in range(wl.W):
+        assert torch.equal(b1.codes[w], b2.codes[w]) and torch.equal(b1.steps[w], b2.steps[w])
