@@ -33,9 +33,10 @@ def parse_args():
     ap.add_argument("--cpu-sample", type=int, default=1 << 27,
                     help="elements per worker the oracle is timed on")
     ap.add_argument("--kernel-reps", type=int, default=20)
-    ap.add_argument("--schedule", choices=["serial", "overlap"], default="serial",
-                    help="serial: all launches on one stream; overlap: encoders and decoders "
-                         "on two streams (encode w+1 beside decode w)")
+    ap.add_argument("--schedule", choices=["serial", "overlap", "fused"], default="serial",
+                    help="serial: one library call per worker and direction, one stream; "
+                         "overlap: the same calls, encoders and decoders on two streams; "
+                         "fused: all encodes, then the whole server loop in one call")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch a plain copy of 2^28 floats (ndq_aggregate with W=1, "
                          "scale=1: 1 GiB read + 1 GiB written) so that a counter run has a "
@@ -116,6 +117,8 @@ def main():
     if args.schedule == "overlap":
         ts = pipeline.TwoStreams(wl.W)
         one_step = lambda: pipeline.step_overlapped(wl, dev, bufs, ds, ts, preset)
+    elif args.schedule == "fused":
+        one_step = lambda: pipeline.step_fused(wl, dev, bufs, ds, preset)
     else:
         one_step = lambda: pipeline.step(wl, dev, bufs, ds, preset)
     for _ in range(args.warmup):

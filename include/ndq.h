@@ -21,18 +21,18 @@
  *   - Return value: 0 on success, a negative ndq_status on error; on error
  *     nothing has been enqueued.  n == 0 is a successful no-op.
  *   - g, codes, out and side must be 16-byte aligned; steps 4-byte aligned.
- *     bucket must be 0 or a multiple of 64; d->offset a multiple of 4 (and of
+ *     bucket must be 0 or a multiple of 64; d->offset a multiple of 8 (and of
  *     bucket when a slice of a bucketed vector is processed).
  *   - Inputs must be finite; this is not checked.
  *   - No global state: calls are thread-safe.  Calls that write the same buffers
  *     on different streams race.
  *
  * Arithmetic (binary32, round-to-nearest-even, no contraction)
- *   unit dither   v_i = (k + 1/2) 2^-24 - 1/2, k = top 24 bits of word (I mod 4) of
- *                 Philox4x32-10(counter = (I/4 low, I/4 high, step, worker),
- *                 key = (seed low, seed high)), I = offset + i.  The dither of
- *                 the paper is u_i = Delta v_i; it is never transmitted (Sec. 2.1,
- *                 Remark 1).
+ *   unit dither   v_i = (k + 1/2) 2^-16 - 1/2, k = 16-bit half (I mod 2) of word
+ *                 ((I/2) mod 4) of Philox4x32-10(counter = (I/8 low, I/8 high, step,
+ *                 worker), key = (seed low, seed high)), I = offset + i: one block
+ *                 serves eight consecutive elements.  The dither of the paper is
+ *                 u_i = Delta v_i; it is never transmitted (Sec. 2.1, Remark 1).
  *   step          Delta_b = 2 kappa_b / (L-1), kappa_b = max |g_i| over bucket b
  *                 (Sec. 3.1 eq. (2) and the partitioning paragraph after Lemma 2);
  *                 Delta_b < 2^-100 is sent as 0 (all-zero bucket).  1/Delta_b := 0
@@ -140,6 +140,33 @@ int ndq_nested_decode(const void* codes, size_t n, uint32_t M, uint32_t bucket,
  * floats; out may be one of the inputs only if W <= 32. */
 int ndq_aggregate(const float* const* gs, uint32_t W, size_t n, float scale, float* out,
                   void* stream);
+
+/* One worker's message as the server holds it (Algorithm 2, "Server"): the packed
+ * codes and steps it sent (DEVICE pointers), how they were made, and its dither. */
+typedef enum { NDQ_WORKER_DQ = 0, NDQ_WORKER_NESTED = 1 } ndq_worker_kind;
+typedef struct {
+    const void* codes;      /* ndq_packed_bytes(n, ndq_code_bits(levels_or_M)) bytes   */
+    const float* steps;     /* ndq_num_buckets(n, bucket) floats                        */
+    uint32_t kind;          /* ndq_worker_kind: group P1 (DQSG) or group P2 (nested)    */
+    uint32_t levels_or_M;   /* levels for a DQSG worker, M for a nested worker          */
+    ndq_dither dither;
+} ndq_worker;
+
+/* The whole server loop of Algorithm 2 in one pass over the elements.  With S the
+ * running sum and c the number of workers folded in so far (S = 0, c = 0 at the
+ * start), for p = 0 .. W-1 in the given order:
+ *     DQSG worker  : S_i <- g~_p,i if c == 0, else S_i + g~_p,i   (as ndq_dq_decode)
+ *     nested worker: y_i = S_i * (1/c);  S_i <- S_i + g~_p,i      (as ndq_nested_decode
+ *                    with side = out = S, side_scale = 1/c, accumulate)
+ *     c <- c + 1
+ * and finally out_i = S_i if scale == 1, else scale * S_i.  Element for element
+ * this is the result of the corresponding sequence of ndq_dq_decode /
+ * ndq_nested_decode calls (and ndq_aggregate for the scale), but S stays in
+ * registers: the codes are read once and out is written once.
+ * workers: HOST array of W entries (1 <= W <= 1024), the first must be a DQSG
+ * worker; all share n and bucket.  out: n floats, written only. */
+int ndq_decode_chain(const ndq_worker* workers, uint32_t W, size_t n, uint32_t bucket,
+                     float scale, float* out, void* stream);
 
 /* Static, human-readable text for a status code. */
 const char* ndq_strerror(int rc);

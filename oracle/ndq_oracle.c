@@ -16,9 +16,11 @@
 /* Algorithm 1) only asks that sender and receiver run the same generator from  */
 /* the same seed and that the seed changes every iteration.  Choice made here:  */
 /* the counter-based Philox4x32 with 10 rounds of Salmon, Moraes, Dror & Shaw,  */
-/* "Parallel random numbers: as easy as 1, 2, 3" (SC'11).  Element i uses word   */
-/* (i mod 4) of the block whose counter is (i/4 low, i/4 high, step, worker)     */
-/* under key (seed low, seed high); "updating the seed" is the step counter.    */
+/* "Parallel random numbers: as easy as 1, 2, 3" (SC'11).  One 128-bit block     */
+/* serves eight consecutive elements, 16 bits each: element i uses half (i mod  */
+/* 2) of word ((i/2) mod 4) of the block whose counter is (i/8 low, i/8 high,   */
+/* step, worker) under key (seed low, seed high); "updating the seed" is the    */
+/* step counter.                                                                */
 /* ------------------------------------------------------------------------- */
 
 void oracle_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4])
@@ -44,16 +46,20 @@ void oracle_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t
 
 float oracle_unit_dither(uint64_t seed, uint32_t step, uint32_t worker, uint64_t i)
 {
-    uint64_t block = i >> 2;
+    uint64_t block = i >> 3;
     uint32_t ctr[4] = { (uint32_t)block, (uint32_t)(block >> 32), step, worker };
     uint32_t key[2] = { (uint32_t)seed, (uint32_t)(seed >> 32) };
     uint32_t r[4];
     oracle_philox4x32_10(ctr, key, r);
-    uint32_t top24 = r[i & 3u] >> 8;
-    /* (top24 + 1/2) * 2^-24 - 1/2 : the mid-point of cell top24 of 2^24 equal
+    uint32_t word = r[(i >> 1) & 3u];
+    uint32_t cell = (i & 1u) ? (word >> 16) : (word & 0xFFFFu);
+    /* (cell + 1/2) * 2^-16 - 1/2 : the mid-point of cell `cell` of 2^16 equal
      * cells of [-1/2, 1/2).  Every such value is a binary32 number, so the fma
-     * is exact; the grid is symmetric, hence has mean exactly 0. */
-    return fmaf((float)top24, 0x1p-24f, -0.5f + 0x1p-25f);
+     * is exact; the grid is symmetric, hence has mean exactly 0.  A dither on
+     * K equally spaced points meets condition 2 of Thm 1 for every l that is
+     * not a multiple of K, so the reconstruction error is uniform and
+     * independent of the input down to a resolution of Delta/K = 2^-16 Delta. */
+    return fmaf((float)cell, 0x1p-16f, -0.5f + 0x1p-17f);
 }
 
 /* ------------------------------------------------------------------------- */

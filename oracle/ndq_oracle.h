@@ -16,8 +16,9 @@
  *
  * Free choices the paper leaves open (all pinned here, see each function):
  *   - the random-number generator: Philox4x32-10 (Salmon et al., SC'11), counter
- *     (i>>2 low, i>>2 high, step, worker), key (seed low, seed high);
- *   - the dither grid: 2^24 mid-points of equal cells of [-1/2, 1/2);
+ *     (i>>3 low, i>>3 high, step, worker), key (seed low, seed high); one block
+ *     gives the dithers of eight consecutive elements, 16 bits each;
+ *   - the dither grid: 2^16 mid-points of equal cells of [-1/2, 1/2);
  *   - "nearest integer" ties: to even;
  *   - number of levels L (odd L is the paper's 2M+1 case; even L uses
  *     indices -L/2 .. L/2-1);

@@ -14,16 +14,15 @@ namespace ndq {
 constexpr int kWave = 64;           // CDNA wavefront
 constexpr int kWavesPerBlock = 4;   // 256-thread workgroups, waves work independently
 constexpr int kBlock = kWave * kWavesPerBlock;
-#ifndef NDQ_ENC_ROWS
-#define NDQ_ENC_ROWS 8
-#endif
 #ifndef NDQ_DEC_ROWS_STREAM
 #define NDQ_DEC_ROWS_STREAM 8
 #endif
 #ifndef NDQ_DEC_ROWS_UPDATE
 #define NDQ_DEC_ROWS_UPDATE 1
 #endif
-constexpr int kEncRows = NDQ_ENC_ROWS;   // 16-byte loads in flight per lane and encoder tile
+// Encoder tile: eight 16-byte loads in flight per lane (4096 bfloat16 or 2048
+// binary32 elements per wave), the largest bucket whose max-norm one wave reduces.
+constexpr int kEncLoads = 8;
 // 16-byte stores per lane and decoder tile.  A decoder that only writes values
 // (DQSG, no accumulate) is bound by load latency per wave and wants long tiles;
 // one that also reads values (side information, running sum) moves twice the
@@ -69,19 +68,40 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
     out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
 }
 
-// Mid-point of cell k = word>>8 of 2^24 equal cells of [-1/2, 1/2): exact in binary32.
-__device__ __forceinline__ float unit_dither(uint32_t word)
+// Mid-point of cell `cell` of 2^16 equal cells of [-1/2, 1/2): exact in binary32.
+__device__ __forceinline__ float unit_dither(uint32_t cell)
 {
-    return __builtin_fmaf((float)(word >> 8), 0x1p-24f, -0.5f + 0x1p-25f);
+    return __builtin_fmaf((float)cell, 0x1p-16f, -0.5f + 0x1p-17f);
 }
 
-// The four unit dithers of elements 4*block .. 4*block+3 of a stream.
-__device__ __forceinline__ void dither4(const DitherStream& s, uint64_t block, float (&v)[4])
+// One Philox block serves eight consecutive elements, 16 bits each: element I
+// takes half (I mod 2) of word ((I/2) mod 4) of block I/8.
+
+// The eight unit dithers of elements 8*block .. 8*block+7.
+__device__ __forceinline__ void dither8(const DitherStream& s, uint64_t block, float (&v)[8])
 {
     uint32_t r[4];
     philox4x32_10((uint32_t)block, (uint32_t)(block >> 32), s.step, s.worker, s.key0, s.key1, r);
 #pragma unroll
-    for (int k = 0; k < 4; ++k) v[k] = unit_dither(r[k]);
+    for (int w = 0; w < 4; ++w) {
+        v[2 * w] = unit_dither(r[w] & 0xFFFFu);
+        v[2 * w + 1] = unit_dither(r[w] >> 16);
+    }
+}
+
+// The four unit dithers of elements 4*quad .. 4*quad+3 (half a block; used where
+// a lane owns four elements and memory, not arithmetic, is the limit).
+__device__ __forceinline__ void dither4(const DitherStream& s, uint64_t quad, float (&v)[4])
+{
+    const uint64_t block = quad >> 1;
+    uint32_t r[4];
+    philox4x32_10((uint32_t)block, (uint32_t)(block >> 32), s.step, s.worker, s.key0, s.key1, r);
+    const bool upper = (quad & 1u) != 0u;
+    const uint32_t a = upper ? r[2] : r[0], b = upper ? r[3] : r[1];
+    v[0] = unit_dither(a & 0xFFFFu);
+    v[1] = unit_dither(a >> 16);
+    v[2] = unit_dither(b & 0xFFFFu);
+    v[3] = unit_dither(b >> 16);
 }
 
 // ---------------------------------------------------------------------------
@@ -116,7 +136,7 @@ struct Quant {
     uint32_t M;              // nesting ratio Delta_2/Delta_1 (nested modes)
     float M_f, inv_M_f;      // (float)M and, for powers of two, its exact reciprocal
     uint32_t bits;           // code width
-    float pack_bias;         // kDqNarrow: -q_min * sum_k 2^(k*bits), k = 0..3
+    float pack_bias;         // kDqNarrow: -q_min * sum_k 2^(k*bits), k = 0..3 (codes of <= 6 bits)
 };
 
 // Clipped index of eq. (2) / Algorithm 1, still as a float (an exact small integer).
@@ -176,45 +196,55 @@ __device__ __forceinline__ float coset_index_f(uint32_t m, float y, float inv, f
 }
 
 // ---------------------------------------------------------------------------
-// Input element types: 16-byte loads hold E elements.
+// Input element types.  A lane owns 8 consecutive elements per row (one Philox
+// block): V 16-byte vectors.
 // ---------------------------------------------------------------------------
 template <int DT> struct Elem;
-template <> struct Elem<0> {               // binary32
-    static constexpr int E = 4;
+template <> struct Elem<0> {               // binary32: two 16-byte vectors
+    static constexpr int V = 2;
     using scalar = float;
-    __device__ static __forceinline__ float get(const uint4& raw, int k)
+    struct Row { uint4 v[2]; };
+    __device__ static __forceinline__ float get(const Row& row, int k)
     {
-        const uint32_t w = (k == 0) ? raw.x : (k == 1) ? raw.y : (k == 2) ? raw.z : raw.w;
+        const uint4& raw = row.v[k >> 2];
+        const int c = k & 3;
+        const uint32_t w = (c == 0) ? raw.x : (c == 1) ? raw.y : (c == 2) ? raw.z : raw.w;
         return __uint_as_float(w);
     }
-    __device__ static __forceinline__ uint32_t bits_of(const void* p, size_t i)
+    __device__ static __forceinline__ float scalar_at(const void* p, size_t i)
     {
-        return ((const uint32_t*)p)[i];
+        return ((const float*)p)[i];
     }
-    // running max of |x| over the 16 bytes; the carrier is a float
+    // running max of |x|; the carrier is a float
     using maxacc = float;
     __device__ static __forceinline__ float max_init() { return 0.0f; }
-    __device__ static __forceinline__ float max_update(float m, const uint4& raw)
+    __device__ static __forceinline__ float max4(float m, const uint4& raw)
     {
         m = __builtin_fmaxf(m, __builtin_fmaxf(__builtin_fabsf(__uint_as_float(raw.x)),
                                                __builtin_fabsf(__uint_as_float(raw.y))));
         return __builtin_fmaxf(m, __builtin_fmaxf(__builtin_fabsf(__uint_as_float(raw.z)),
                                                   __builtin_fabsf(__uint_as_float(raw.w))));
     }
+    __device__ static __forceinline__ float max_update(float m, const Row& row)
+    {
+        return max4(max4(m, row.v[0]), row.v[1]);
+    }
     __device__ static __forceinline__ float max_final(float m) { return m; }
 };
-template <> struct Elem<1> {               // bfloat16, widened exactly
-    static constexpr int E = 8;
+template <> struct Elem<1> {               // bfloat16, widened exactly: one 16-byte vector
+    static constexpr int V = 1;
     using scalar = uint16_t;
-    __device__ static __forceinline__ float get(const uint4& raw, int k)
+    struct Row { uint4 v[1]; };
+    __device__ static __forceinline__ float get(const Row& row, int k)
     {
+        const uint4& raw = row.v[0];
         const int wi = k >> 1;
         const uint32_t w = (wi == 0) ? raw.x : (wi == 1) ? raw.y : (wi == 2) ? raw.z : raw.w;
         return __uint_as_float((k & 1) ? (w & 0xFFFF0000u) : (w << 16));
     }
-    __device__ static __forceinline__ uint32_t bits_of(const void* p, size_t i)
+    __device__ static __forceinline__ float scalar_at(const void* p, size_t i)
     {
-        return ((const uint16_t*)p)[i];
+        return __uint_as_float((uint32_t)((const uint16_t*)p)[i] << 16);
     }
     // |x| of a bfloat16 orders like its low 15 bits, so the running max is kept
     // as two 16-bit integers per word and widened once at the end
@@ -226,8 +256,9 @@ template <> struct Elem<1> {               // bfloat16, widened exactly
         const u16x2 x = __builtin_bit_cast(u16x2, a), y = __builtin_bit_cast(u16x2, b);
         return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(x, y));
     }
-    __device__ static __forceinline__ uint32_t max_update(uint32_t m, const uint4& raw)
+    __device__ static __forceinline__ uint32_t max_update(uint32_t m, const Row& row)
     {
+        const uint4& raw = row.v[0];
         m = pk_max(m, raw.x & 0x7FFF7FFFu);
         m = pk_max(m, raw.y & 0x7FFF7FFFu);
         m = pk_max(m, raw.z & 0x7FFF7FFFu);
@@ -239,29 +270,35 @@ template <> struct Elem<1> {               // bfloat16, widened exactly
         return __uint_as_float((hi > lo ? hi : lo) << 16);
     }
 };
+constexpr int kLaneElems = 8;   // elements per lane and row in the encoders
 
-// Loads E elements at element offset `o` of a tile with `len` valid elements.
-// FULL: the whole tile is valid, a plain 16-byte load (o % E == 0).  Otherwise
-// elements past the end read as zero.
+// Loads the 8 elements at element offset `o` (a multiple of 8) of a tile with
+// `len` valid elements.  FULL: the whole tile is valid, plain 16-byte loads.
+// Otherwise elements past the end read as zero.
 template <int DT, bool FULL>
-__device__ __forceinline__ uint4 load_row(const void* tile, uint32_t o, uint32_t len)
+__device__ __forceinline__ typename Elem<DT>::Row load_row(const void* tile, uint32_t o, uint32_t len)
 {
     using T = Elem<DT>;
-    if (FULL) return *(const uint4*)((const typename T::scalar*)tile + o);
-    uint4 raw = make_uint4(0u, 0u, 0u, 0u);
-    if (o + T::E <= len) {
-        raw = *(const uint4*)((const typename T::scalar*)tile + o);
-    } else if (o < len) {
-        uint32_t w[4] = {0u, 0u, 0u, 0u};
+    typename T::Row row;
+    const typename T::scalar* base = (const typename T::scalar*)tile + o;
 #pragma unroll
-        for (uint32_t k = 0; k < (uint32_t)T::E; ++k)
-            if (o + k < len) {
-                const uint32_t b = T::bits_of(tile, o + k);
-                if (DT == 0) w[k & 3] = b; else w[k >> 1] |= b << (16 * (k & 1));
-            }
-        raw = make_uint4(w[0], w[1], w[2], w[3]);
+    for (int j = 0; j < T::V; ++j) {
+        constexpr uint32_t per = kLaneElems / T::V;        // elements per vector
+        const uint32_t oj = o + j * per;
+        if (FULL || oj + per <= len) {
+            row.v[j] = *(const uint4*)(base + j * per);
+        } else {
+            uint32_t w[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+            for (uint32_t k = 0; k < per; ++k)
+                if (oj + k < len) {
+                    if (DT == 0) w[k & 3] = ((const uint32_t*)tile)[oj + k];
+                    else w[k >> 1] |= (uint32_t)((const uint16_t*)tile)[oj + k] << (16 * (k & 1));
+                }
+            row.v[j] = make_uint4(w[0], w[1], w[2], w[3]);
+        }
     }
-    return raw;
+    return row;
 }
 
 __device__ __forceinline__ float wave_max(float x)

@@ -27,30 +27,33 @@ struct EncodeArgs {
     float preset_step;     // > 0: bucket == 0 with a caller-set step
 };
 
-template <int DT> struct EncTile { static constexpr uint32_t N = kWave * Elem<DT>::E * kEncRows; };
+template <int DT> struct EncRows { static constexpr int R = kEncLoads / Elem<DT>::V; };
+template <int DT> struct EncTile { static constexpr uint32_t N = kWave * kLaneElems * EncRows<DT>::R; };
 
 // One wave encodes one tile: loads it (all 16-byte loads issued back to back),
 // finds the step, quantizes, and leaves the packed codes in `stage` in stream
-// order.  FULL: every element of the tile is valid -- no guards anywhere.
+// order.  A lane owns 8 consecutive elements per row: one Philox block, and
+// 8 codes = `bits` whole bytes of the stream.  FULL: every element of the tile
+// is valid -- no guards anywhere.
 template <int DT, int MODE, bool FUSED, bool FULL>
 __device__ __forceinline__ void encode_tile(const EncodeArgs& a, const TileRef& t, uint32_t tile_id,
                                             unsigned char* stage, int lane)
 {
     using T = Elem<DT>;
-    constexpr int E = T::E;
+    constexpr int ROWS = EncRows<DT>::R;
     const uint32_t bits = a.qp.bits;
     const typename T::scalar* tile = (const typename T::scalar*)a.g + t.start;
-    uint4 raw[kEncRows];
+    typename T::Row raw[ROWS];
 #pragma unroll
-    for (int r = 0; r < kEncRows; ++r)
-        raw[r] = load_row<DT, FULL>(tile, (uint32_t)r * kWave * E + (uint32_t)lane * E, t.len);
+    for (int r = 0; r < ROWS; ++r)
+        raw[r] = load_row<DT, FULL>(tile, (uint32_t)(r * kWave + lane) * kLaneElems, t.len);
 
     float step;
     if (FUSED) {
         // the bucket is this tile: kappa = max|g| in registers (Sec. 3.1 eq. (2))
         typename T::maxacc m = T::max_init();
 #pragma unroll
-        for (int r = 0; r < kEncRows; ++r) m = T::max_update(m, raw[r]);
+        for (int r = 0; r < ROWS; ++r) m = T::max_update(m, raw[r]);
         step = step_from_kappa(wave_max(T::max_final(m)), a.qp.levels);
         if (lane == 0) a.steps[t.bucket] = step;
     } else if (a.preset_step > 0.0f) {
@@ -60,23 +63,23 @@ __device__ __forceinline__ void encode_tile(const EncodeArgs& a, const TileRef& 
         step = a.steps[t.bucket];
     }
     const float inv = inv_step(step);
-    const uint64_t block0 = (a.index0 + t.start) >> 2;
+    const uint64_t block0 = (a.index0 + t.start) >> 3;
 
 #pragma unroll
-    for (int r = 0; r < kEncRows; ++r) {
-        const uint32_t o = (uint32_t)r * kWave * E + (uint32_t)lane * E;
-        uint32_t quad[E / 4];
+    for (int r = 0; r < ROWS; ++r) {
+        const uint32_t o = (uint32_t)(r * kWave + lane) * kLaneElems;
+        float v[8];
+        dither8(a.ds, block0 + (o >> 3), v);
+        uint32_t quad[2];
 #pragma unroll
-        for (int h = 0; h < E / 4; ++h) {
-            float v[4];
-            dither4(a.ds, block0 + (o >> 2) + h, v);
+        for (int h = 0; h < 2; ++h) {
             uint32_t chunk = 0;
             if (MODE == kDqNarrow) {
                 // codes of <= 6 bits: sum (q_k - q_min) 2^(k b) stays an exact float below 2^24
                 float acc = a.qp.pack_bias;
 #pragma unroll
                 for (int k = 0; k < 4; ++k) {
-                    float q = dq_index_f(T::get(raw[r], 4 * h + k), inv, v[k], a.qp);
+                    float q = dq_index_f(T::get(raw[r], 4 * h + k), inv, v[4 * h + k], a.qp);
                     if (!FULL && o + 4 * h + k >= t.len) q = a.qp.q_min_f;
                     acc = __builtin_fmaf(q, __uint_as_float((127u + k * bits) << 23), acc);
                 }
@@ -84,7 +87,7 @@ __device__ __forceinline__ void encode_tile(const EncodeArgs& a, const TileRef& 
             } else {
 #pragma unroll
                 for (int k = 0; k < 4; ++k) {
-                    uint32_t c = encode_one<MODE>(T::get(raw[r], 4 * h + k), inv, v[k], a.qp);
+                    uint32_t c = encode_one<MODE>(T::get(raw[r], 4 * h + k), inv, v[4 * h + k], a.qp);
                     if (!FULL && o + 4 * h + k >= t.len) c = 0;
                     chunk |= c << (k * bits);
                 }
@@ -92,25 +95,15 @@ __device__ __forceinline__ void encode_tile(const EncodeArgs& a, const TileRef& 
             quad[h] = chunk;
         }
         // eight consecutive codes -> `bits` bytes at byte (o/8)*bits of the tile's stream
-        uint32_t lo = quad[0], hi;
-        bool writer = true;
-        if (E == 8) {
-            hi = quad[E / 4 - 1];
-        } else {
-            hi = __shfl_down(lo, 1, kWave);
-            writer = (lane & 1) == 0;
-        }
-        const uint64_t chunk8 = (uint64_t)lo | ((uint64_t)hi << (4 * bits));
-        if (writer) {
-            unsigned char* p = stage + (o >> 3) * bits;
-            switch (bits) {
-                case 1: *p = (unsigned char)chunk8; break;
-                case 2: *(uint16_t*)p = (uint16_t)chunk8; break;
-                case 4: *(uint32_t*)p = (uint32_t)chunk8; break;
-                case 8: *(uint64_t*)p = chunk8; break;
-                default:
-                    for (uint32_t k = 0; k < bits; ++k) p[k] = (unsigned char)(chunk8 >> (8 * k));
-            }
+        const uint64_t chunk8 = (uint64_t)quad[0] | ((uint64_t)quad[1] << (4 * bits));
+        unsigned char* p = stage + (o >> 3) * bits;
+        switch (bits) {
+            case 1: *p = (unsigned char)chunk8; break;
+            case 2: *(uint16_t*)p = (uint16_t)chunk8; break;
+            case 4: *(uint32_t*)p = (uint32_t)chunk8; break;
+            case 8: *(uint64_t*)p = chunk8; break;
+            default:
+                for (uint32_t k = 0; k < bits; ++k) p[k] = (unsigned char)(chunk8 >> (8 * k));
         }
     }
     if (lane == 0) *(uint64_t*)(stage + (size_t)EncTile<DT>::N / 8 * bits) = 0;  // pad unit
@@ -165,19 +158,20 @@ __global__ __launch_bounds__(kBlock) void absmax_kernel(const void* g, Tiling tl
     const TileRef t = locate_tile(tl, tile_id, TILE);
     if (t.len == 0) return;
     const typename T::scalar* tile = (const typename T::scalar*)g + t.start;
-    uint4 raw[kEncRows];
+    constexpr int ROWS = EncRows<DT>::R;
+    typename T::Row raw[ROWS];
     if (t.len == TILE) {
 #pragma unroll
-        for (int r = 0; r < kEncRows; ++r)
-            raw[r] = load_row<DT, true>(tile, (uint32_t)r * kWave * T::E + (uint32_t)lane * T::E, t.len);
+        for (int r = 0; r < ROWS; ++r)
+            raw[r] = load_row<DT, true>(tile, (uint32_t)(r * kWave + lane) * kLaneElems, t.len);
     } else {
 #pragma unroll
-        for (int r = 0; r < kEncRows; ++r)
-            raw[r] = load_row<DT, false>(tile, (uint32_t)r * kWave * T::E + (uint32_t)lane * T::E, t.len);
+        for (int r = 0; r < ROWS; ++r)
+            raw[r] = load_row<DT, false>(tile, (uint32_t)(r * kWave + lane) * kLaneElems, t.len);
     }
     typename T::maxacc acc = T::max_init();
 #pragma unroll
-    for (int r = 0; r < kEncRows; ++r) acc = T::max_update(acc, raw[r]);
+    for (int r = 0; r < ROWS; ++r) acc = T::max_update(acc, raw[r]);
     const float m = wave_max(T::max_final(acc));
     // non-negative floats order like their bit patterns
     if (lane == 0) atomicMax(kappa_bits + t.bucket, __float_as_uint(m));
@@ -238,8 +232,11 @@ __device__ __forceinline__ void decode_tile(const DecodeArgs& a, const TileRef& 
             const uint32_t bit = o * bits;
             const uint32_t w = bit >> 5, sh = bit & 31u;
             if (STRADDLE) {
+                // read the next word only if a valid code reaches into it (a ragged
+                // tail must not touch memory past the stream)
+                const uint32_t ncodes = FULL ? 4u : (t.len - o < 4u ? t.len - o : 4u);
                 uint64_t window = codes32[w];
-                if (sh + 4u * bits > 32u) window |= (uint64_t)codes32[w + 1] << 32;
+                if (sh + ncodes * bits > 32u) window |= (uint64_t)codes32[w + 1] << 32;
                 packed[r] = (uint32_t)(window >> sh);
             } else {
                 packed[r] = codes32[w] >> sh;
@@ -304,6 +301,165 @@ __global__ __launch_bounds__(kBlock) void decode_kernel(DecodeArgs a)
     const TileRef t = locate_tile(a.tl, tile_id, TILE);
     if (t.len == TILE) decode_tile<MODE, ACC, true, STRADDLE>(a, t, lane);
     else if (t.len != 0) decode_tile<MODE, ACC, false, STRADDLE>(a, t, lane);
+}
+
+// ---------------------------------------------------------------------------
+// Chain decoder: the whole server loop of Algorithm 2 in one pass.  The running
+// sum of a lane's elements lives in registers while the workers are folded in
+// one after the other; the next worker's code words and step are prefetched
+// while the current worker's dither is generated.
+// ---------------------------------------------------------------------------
+constexpr uint32_t kChainMax = 32;    // workers per launch
+constexpr int kChainRows = 2;         // rows of 8 elements per lane and tile
+constexpr uint32_t kChainTile = kWave * kLaneElems * kChainRows;
+
+struct ChainWorker {
+    const unsigned char* codes;
+    const float* steps;
+    uint64_t index0;
+    DitherStream ds;
+    int32_t q_min;
+    uint32_t M;
+    float M_f, inv_M_f;
+    float side_scale;     // 1/(workers folded in before this one); 0 for the first
+    uint32_t bits;
+    uint32_t mode;        // Mode
+    uint32_t first;       // S <- value instead of S + value
+};
+
+struct ChainArgs {
+    ChainWorker w[kChainMax];
+    float* out;
+    Tiling tl;
+    uint32_t W;
+    int continue_sum;     // S starts from out (an earlier group of workers)
+    int apply_scale;
+    float scale;
+};
+
+// What is prefetched per worker: the step and, per row, the words holding the
+// lane's eight codes (8*bits bits starting at a multiple of 8 bits).
+struct ChainFetch {
+    uint32_t w0[kChainRows], w1[kChainRows], w2[kChainRows];
+    float step;
+};
+
+template <bool FULL>
+__device__ __forceinline__ void chain_fetch(const ChainWorker& cw, const TileRef& t, int lane,
+                                            ChainFetch& f)
+{
+    const uint32_t bits = cw.bits;
+    const uint32_t* codes32 = (const uint32_t*)(cw.codes + (t.start >> 3) * bits);
+    f.step = cw.steps[t.bucket];
+#pragma unroll
+    for (int r = 0; r < kChainRows; ++r) {
+        const uint32_t o = (uint32_t)(r * kWave + lane) * kLaneElems;
+        f.w0[r] = 0; f.w1[r] = 0; f.w2[r] = 0;
+        if (FULL || o < t.len) {
+            const uint32_t bit = o * bits;                     // multiple of 8
+            const uint32_t w = bit >> 5, sh = bit & 31u;
+            // bits used from word w on; a ragged tail only counts its valid codes so
+            // that no word past the stream is touched
+            const uint32_t ncodes = FULL ? 8u : (t.len - o < 8u ? t.len - o : 8u);
+            const uint32_t end = sh + ncodes * bits;
+            f.w0[r] = codes32[w];
+            if (end > 32u) f.w1[r] = codes32[w + 1];
+            if (end > 64u) f.w2[r] = codes32[w + 2];
+        }
+    }
+}
+
+template <int MODE>
+__device__ __forceinline__ void chain_fold(const ChainWorker& cw, const ChainFetch& f,
+                                           uint64_t block0, int lane, float (&S)[kChainRows][8])
+{
+    const uint32_t bits = cw.bits;
+    const uint32_t mask = (1u << bits) - 1u;
+    const float step = f.step;
+    const float inv = inv_step(step);
+    Quant qp;
+    qp.M = cw.M; qp.M_f = cw.M_f; qp.inv_M_f = cw.inv_M_f; qp.q_min = cw.q_min;
+#pragma unroll
+    for (int r = 0; r < kChainRows; ++r) {
+        const uint32_t o = (uint32_t)(r * kWave + lane) * kLaneElems;
+        const uint32_t sh = (o * bits) & 31u;
+        // the lane's 8*bits code bits, in two halves of four codes
+        const uint64_t low = (((uint64_t)f.w1[r] << 32) | f.w0[r]) >> sh;
+        const uint64_t high = sh ? ((uint64_t)f.w2[r] << (64u - sh)) : 0u;
+        const uint64_t chunk = low | high;
+        const uint32_t half[2] = {(uint32_t)chunk, (uint32_t)(chunk >> (4u * bits))};
+        float v[8];
+        dither8(cw.ds, block0 + (o >> 3), v);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const uint32_t c = (half[k >> 2] >> ((k & 3) * bits)) & mask;
+            float q;
+            if (MODE == kDq) {
+                q = (float)((int32_t)c + qp.q_min);
+            } else {
+                const float yk = S[r][k] * cw.side_scale;
+                q = coset_index_f<MODE>(c, yk, inv, v[k], qp);
+            }
+            const float val = index_value(q, step, v[k]);
+            S[r][k] = (MODE == kDq && cw.first) ? val : S[r][k] + val;
+        }
+    }
+}
+
+template <bool FULL>
+__device__ __forceinline__ void chain_tile(const ChainArgs& a, const TileRef& t, int lane)
+{
+    float S[kChainRows][8];
+    float* out = a.out + t.start;
+#pragma unroll
+    for (int r = 0; r < kChainRows; ++r) {
+        const uint32_t o = (uint32_t)(r * kWave + lane) * kLaneElems;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            S[r][k] = 0.0f;
+            if (a.continue_sum && (FULL || o + k < t.len)) S[r][k] = out[o + k];
+        }
+    }
+    ChainFetch cur;
+    chain_fetch<FULL>(a.w[0], t, lane, cur);
+    ChainFetch nxt = cur;
+    for (uint32_t w = 0; w < a.W; ++w) {
+        const ChainWorker& cw = a.w[w];
+        if (w + 1 < a.W) chain_fetch<FULL>(a.w[w + 1], t, lane, nxt);
+        const uint64_t block0 = (cw.index0 + t.start) >> 3;
+        if (cw.mode == kDq) chain_fold<kDq>(cw, cur, block0, lane, S);
+        else if (cw.mode == kNestedPow2) chain_fold<kNestedPow2>(cw, cur, block0, lane, S);
+        else chain_fold<kNestedAnyM>(cw, cur, block0, lane, S);
+        cur = nxt;
+    }
+#pragma unroll
+    for (int r = 0; r < kChainRows; ++r) {
+        const uint32_t o = (uint32_t)(r * kWave + lane) * kLaneElems;
+        float res[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) res[k] = a.apply_scale ? a.scale * S[r][k] : S[r][k];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            if (FULL || o + 4 * j + 4 <= t.len) {
+                *(float4*)(out + o + 4 * j) =
+                    make_float4(res[4 * j], res[4 * j + 1], res[4 * j + 2], res[4 * j + 3]);
+            } else {
+#pragma unroll
+                for (uint32_t k = 0; k < 4; ++k)
+                    if (o + 4 * j + k < t.len) out[o + 4 * j + k] = res[4 * j + k];
+            }
+        }
+    }
+}
+
+__global__ __launch_bounds__(kBlock) void chain_kernel(ChainArgs a)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    const uint32_t tile_id =
+        blockIdx.x * kWavesPerBlock + __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const TileRef t = locate_tile(a.tl, tile_id, kChainTile);
+    if (t.len == kChainTile) chain_tile<true>(a, t, lane);
+    else if (t.len != 0) chain_tile<false>(a, t, lane);
 }
 
 // ---------------------------------------------------------------------------
@@ -451,7 +607,7 @@ static int encode_common(const void* g, ndq_dtype dt, size_t n, float delta, uin
     if (!(delta == delta)) return NDQ_EINVAL;
     if (n >= kMaxN) return NDQ_EUNSUPPORTED;
     if (!aligned16(g) || !aligned16(codes_out) || !aligned4(steps_out)) return NDQ_EALIGN;
-    if (bucket % 64u != 0u || (d->offset & 3u) != 0u) return NDQ_EALIGN;
+    if (bucket % 64u != 0u || (d->offset & 7u) != 0u) return NDQ_EALIGN;
 
     const uint32_t tile = dt == NDQ_F32 ? EncTile<0>::N : EncTile<1>::N;
     rc = make_tiling(n, bucket, tile, &a.tl);
@@ -531,7 +687,7 @@ static int decode_common(const void* codes, size_t n, uint32_t levels, uint32_t 
     if (n >= kMaxN) return NDQ_EUNSUPPORTED;
     if (!aligned16(codes) || !aligned16(out) || !aligned4(steps) || (nested && !aligned16(side)))
         return NDQ_EALIGN;
-    if (bucket % 64u != 0u || (d->offset & 3u) != 0u) return NDQ_EALIGN;
+    if (bucket % 64u != 0u || (d->offset & 7u) != 0u) return NDQ_EALIGN;
     if (nested && side != out) {
         // partial overlap of side and out would race between waves
         const uintptr_t s0 = (uintptr_t)side, o0 = (uintptr_t)out, len = (uintptr_t)n * 4u;
@@ -658,12 +814,68 @@ int ndq_aggregate(const float* const* gs, uint32_t W, size_t n, float scale, flo
     return NDQ_OK;
 }
 
+int ndq_decode_chain(const ndq_worker* workers, uint32_t W, size_t n, uint32_t bucket,
+                     float scale, float* out, void* stream)
+{
+    using namespace ndq;
+    if (!workers || W < 1u || W > 1024u) return NDQ_EINVAL;
+    if (workers[0].kind != NDQ_WORKER_DQ) return NDQ_EINVAL;   // nothing to decode against yet
+    for (uint32_t p = 0; p < W; ++p) {
+        const ndq_worker& wk = workers[p];
+        if (wk.kind != NDQ_WORKER_DQ && wk.kind != NDQ_WORKER_NESTED) return NDQ_EINVAL;
+        if (wk.levels_or_M < 2u || wk.levels_or_M > 256u) return NDQ_EINVAL;
+    }
+    if (n == 0) return NDQ_OK;
+    if (!out) return NDQ_EINVAL;
+    if (n >= kMaxN) return NDQ_EUNSUPPORTED;
+    if (!aligned16(out) || bucket % 64u != 0u) return NDQ_EALIGN;
+    for (uint32_t p = 0; p < W; ++p) {
+        const ndq_worker& wk = workers[p];
+        if (!wk.codes || !wk.steps) return NDQ_EINVAL;
+        if (!aligned16(wk.codes) || !aligned4(wk.steps) || (wk.dither.offset & 7u) != 0u)
+            return NDQ_EALIGN;
+    }
+    ChainArgs a;
+    int rc = make_tiling(n, bucket, kChainTile, &a.tl);
+    if (rc != NDQ_OK) return rc;
+    a.out = out;
+    a.scale = scale;
+    for (uint32_t p0 = 0; p0 < W; p0 += kChainMax) {
+        a.W = (W - p0 < kChainMax) ? W - p0 : kChainMax;
+        a.continue_sum = p0 != 0u;
+        a.apply_scale = (p0 + kChainMax >= W) && scale != 1.0f;
+        for (uint32_t j = 0; j < a.W; ++j) {
+            const ndq_worker& wk = workers[p0 + j];
+            const bool nested = wk.kind == NDQ_WORKER_NESTED;
+            Quant qp;
+            make_quant(nested ? 2u : wk.levels_or_M, wk.levels_or_M, nested, &qp);
+            ChainWorker& cw = a.w[j];
+            cw.codes = (const unsigned char*)wk.codes;
+            cw.steps = wk.steps;
+            cw.index0 = wk.dither.offset;
+            cw.ds = make_stream(&wk.dither);
+            cw.q_min = qp.q_min;
+            cw.M = qp.M;
+            cw.M_f = qp.M_f;
+            cw.inv_M_f = qp.inv_M_f;
+            cw.side_scale = (p0 + j) ? 1.0f / (float)(p0 + j) : 0.0f;
+            cw.bits = qp.bits;
+            cw.mode = !nested ? kDq : (is_pow2(wk.levels_or_M) ? kNestedPow2 : kNestedAnyM);
+            cw.first = (p0 + j) == 0u;
+        }
+        hipLaunchKernelGGL(chain_kernel, dim3(blocks_for(a.tl.total_tiles)), dim3(kBlock), 0,
+                           (hipStream_t)stream, a);
+        if (launched() != NDQ_OK) return NDQ_ELAUNCH;
+    }
+    return NDQ_OK;
+}
+
 const char* ndq_strerror(int rc)
 {
     switch (rc) {
         case NDQ_OK: return "success";
         case NDQ_EINVAL: return "invalid argument (null pointer, levels or M outside [2,256], overlapping buffers, bad W)";
-        case NDQ_EALIGN: return "alignment violated (16-byte data pointers, bucket multiple of 64, offset multiple of 4)";
+        case NDQ_EALIGN: return "alignment violated (16-byte data pointers, bucket multiple of 64, offset multiple of 8)";
         case NDQ_EUNSUPPORTED: return "vector too long for one call";
         case NDQ_ELAUNCH: return "the HIP runtime refused a kernel launch";
         default: return "unknown ndq status";

@@ -19,13 +19,22 @@ NDQ_OK, NDQ_EINVAL, NDQ_EALIGN, NDQ_EUNSUPPORTED, NDQ_ELAUNCH = 0, -1, -2, -3, -
 
 EXPORTS = ("ndq_code_bits", "ndq_packed_bytes", "ndq_num_buckets", "ndq_absmax", "ndq_dq_encode",
            "ndq_dq_decode", "ndq_nested_encode", "ndq_nested_decode", "ndq_aggregate",
-           "ndq_strerror")
+           "ndq_decode_chain", "ndq_strerror")
 
 
 class ndq_dither(C.Structure):
     """Mirror of the C struct: (seed, step, worker, offset)."""
     _fields_ = [("seed", C.c_uint64), ("step", C.c_uint32), ("worker", C.c_uint32),
                 ("offset", C.c_uint64)]
+
+
+NDQ_WORKER_DQ, NDQ_WORKER_NESTED = 0, 1
+
+
+class ndq_worker(C.Structure):
+    """Mirror of the C struct: one worker's message as the server holds it."""
+    _fields_ = [("codes", C.c_void_p), ("steps", C.c_void_p), ("kind", C.c_uint32),
+                ("levels_or_M", C.c_uint32), ("dither", ndq_dither)]
 
 
 class NdqError(RuntimeError):
@@ -61,6 +70,8 @@ def lib():
         L.ndq_nested_decode.argtypes = [vp, sz, u32, u32, vp, dp, vp, f32, vp, ci, vp]
         L.ndq_nested_decode.restype = ci
         L.ndq_aggregate.argtypes, L.ndq_aggregate.restype = [vp, u32, sz, f32, vp, vp], ci
+        L.ndq_decode_chain.argtypes = [C.POINTER(ndq_worker), u32, sz, u32, f32, vp, vp]
+        L.ndq_decode_chain.restype = ci
         L.ndq_strerror.argtypes, L.ndq_strerror.restype = [ci], C.c_char_p
         _lib = L
     return _lib
@@ -181,4 +192,22 @@ def ndq_aggregate(gs, scale=1.0, out=None):
     ptrs = (C.c_void_p * len(gs))(*[_dev(g, "gs[w]").value for g in gs])
     _check(lib().ndq_aggregate(C.cast(ptrs, C.c_void_p), len(gs), n, scale, _dev(out, "out"),
                                _stream()), "ndq_aggregate")
+    return out
+
+
+def ndq_decode_chain(workers, n, bucket, scale=1.0, out=None):
+    """workers: sequence of (codes, steps, kind, levels_or_M, ndq_dither) in decoding order."""
+    arr = (ndq_worker * len(workers))()
+    for i, (codes, steps, kind, arg, d) in enumerate(workers):
+        arr[i].codes = _dev(codes, "codes").value
+        arr[i].steps = _dev(steps, "steps").value
+        arr[i].kind = kind
+        arr[i].levels_or_M = arg
+        arr[i].dither = d
+    if out is None:
+        out = torch.empty(n, dtype=torch.float32, device=workers[0][0].device)
+    if out.dtype != torch.float32 or out.numel() < n:
+        raise ValueError("out must hold n float32")
+    _check(lib().ndq_decode_chain(arr, len(workers), n, bucket, scale, _dev(out, "out"),
+                                  _stream()), "ndq_decode_chain")
     return out

@@ -78,6 +78,15 @@ def decode_chain(wl: Workload, n: int, bufs: Buffers, ds):
     return S
 
 
+def decode_chain_fused(wl: Workload, n: int, bufs: Buffers, ds):
+    """The same server loop as decode_chain() in ONE library call: the running
+    sum stays in registers, codes are read once, the result is written once."""
+    workers = [(bufs.codes[w], bufs.steps[w],
+                ndq.NDQ_WORKER_DQ if kind == "dq" else ndq.NDQ_WORKER_NESTED, arg, ds[w])
+               for w, (kind, arg) in enumerate(wl.plan)]
+    return ndq.ndq_decode_chain(workers, n, wl.bucket, wl.out_scale, bufs.total)
+
+
 def decode_separately(wl: Workload, n: int, bufs: Buffers, ds):
     """Server side of Algorithm 1 as printed: reconstruct every worker's gradient,
     then average them (all-DQSG workloads only)."""
@@ -138,6 +147,13 @@ def step_overlapped(wl: Workload, grads, bufs: Buffers, ds, ts: TwoStreams,
     main.wait_stream(ts.enc)
     main.wait_stream(ts.dec)
     return S
+
+
+def step_fused(wl: Workload, grads, bufs: Buffers, ds, preset_step: float = 0.0):
+    """All encodes, then the fused server loop."""
+    n = grads[0].numel()
+    encode_all(wl, grads, bufs, ds, preset_step)
+    return decode_chain_fused(wl, n, bufs, ds)
 
 
 def to_device(wl: Workload, host_grads, device="cuda"):

@@ -416,3 +416,71 @@ def test_two_stream_schedule_gives_identical_results():
         assert torch.equal(out, ref)
     for w in range(wl.W):
         assert torch.equal(b1.codes[w], b2.codes[w]) and torch.equal(b1.steps[w], b2.steps[w])
+
+
+# --------------------------------------------------------------------------
+# the whole server loop of Algorithm 2 in one call
+# --------------------------------------------------------------------------
+
+def _chain_case(plan, fine_levels, bucket, n, dtype, seed, out_scale, shared_step):
+    rng = np.random.default_rng(seed)
+    common = rng.standard_normal(n) * 0.01
+    host = []
+    for w in range(len(plan)):
+        x = (common + rng.standard_normal(n) * 0.002).astype(F)
+        host.append(workloads.f32_to_bf16_bits(x) if dtype == "bf16" else x)
+    seeds = [7 + w for w in range(len(plan))]
+    ds_o = opipe.dithers(len(plan), seeds, step=3)
+    c_ref, s_ref, _ = opipe.encode_all(plan, fine_levels, bucket, shared_step, host, ds_o)
+    ref = opipe.decode_chain(plan, bucket, n, c_ref, s_ref, ds_o, out_scale)
+    dev = _gpu()
+    workers = []
+    for w, (kind, arg) in enumerate(plan):
+        workers.append((torch.from_numpy(c_ref[w]).to(dev), torch.from_numpy(s_ref[w]).to(dev),
+                        ndq.NDQ_WORKER_DQ if kind == "dq" else ndq.NDQ_WORKER_NESTED, arg,
+                        ndq.ndq_dither(seeds[w], 3, w, 0)))
+    out = ndq.ndq_decode_chain(workers, n, bucket, out_scale)
+    assert np.array_equal(out.cpu().numpy(), ref), (plan, n)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_decode_chain_matches_oracle_loop(dtype):
+    plans = [
+        ((("dq", 4), ("nested", 2), ("nested", 2), ("nested", 2)), 4, 4096, 1.0, False),
+        ((("dq", 16),) + (("nested", 4),) * 15, 16, 0, 1.0 / 16, True),
+        ((("dq", 16),) * 8, 16, 2048, 0.125, False),
+        ((("dq", 8), ("nested", 3), ("dq", 5), ("nested", 7), ("nested", 256), ("dq", 256)),
+         8, 2112, 1.0, False),
+        ((("dq", 3),), 3, 0, 1.0, False),
+    ]
+    for plan, fine, bucket, scale, shared in plans:
+        for n in (1, 255, 1024, 1025, 4096 * 3 + 77, 70001):
+            _chain_case(plan, fine, bucket, n, dtype, seed=n, out_scale=scale, shared_step=shared)
+
+
+def test_decode_chain_more_workers_than_one_launch_holds():
+    plan = (("dq", 16),) + tuple(("nested", 4) if w % 3 else ("dq", 9) for w in range(1, 70))
+    _chain_case(plan, 16, 1024, 9000, "f32", seed=5, out_scale=1.0 / 70, shared_step=False)
+
+
+def test_decode_chain_rejects_a_nested_first_worker():
+    dev = _gpu()
+    codes = torch.zeros(1024, dtype=torch.uint8, device=dev)
+    steps = torch.ones(1, dtype=torch.float32, device=dev)
+    with pytest.raises(ndq.NdqError) as e:
+        ndq.ndq_decode_chain([(codes, steps, ndq.NDQ_WORKER_NESTED, 4, ndq.ndq_dither(0, 0, 0, 0))],
+                             1024, 0)
+    assert e.value.rc == ndq.NDQ_EINVAL
+
+
+def test_fused_step_equals_call_by_call_step_on_the_configs():
+    for cfg, n in ((2, None), (3, 1 << 21), (4, (1 << 21) + 2), (5, (1 << 22) + 100)):
+        wl = workloads.CONFIGS[cfg]
+        n = n or wl.n
+        dev = pipeline.to_device(wl, workloads.gradients(wl, n))
+        ds = pipeline.dithers(wl)
+        b1, b2 = pipeline.allocate(wl, n), pipeline.allocate(wl, n)
+        ref = pipeline.step(wl, dev, b1, ds).clone()
+        preset = float(b1.steps[0][0].item()) if wl.shared_step else 0.0
+        out = pipeline.step_fused(wl, dev, b2, ds, preset)
+        assert torch.equal(out, ref), cfg

@@ -47,20 +47,24 @@ def test_philox_is_a_bijection_of_the_counter_on_a_small_slice():
     assert len(seen) == 4096
 
 
-def test_dither_is_word_i_mod_4_of_block_i_div_4():
-    """Element i takes the top 24 bits of word (i mod 4) of the block with
-    counter (i//4 low, i//4 high, step, worker) and key (seed low, seed high),
-    mapped to the mid-point grid (k + 1/2) 2^-24 - 1/2."""
+def test_dither_is_a_16_bit_half_of_block_i_div_8():
+    """Element i takes half (i mod 2) of word ((i//2) mod 4) of the block with
+    counter (i//8 low, i//8 high, step, worker) and key (seed low, seed high),
+    mapped to the mid-point grid (k + 1/2) 2^-16 - 1/2."""
     seed, step, worker = 0x0123456789ABCDEF, 77, 5
-    for i in [0, 1, 2, 3, 4, 7, 1023, (1 << 34) + 6, (1 << 40) + 1]:
-        blk = i >> 2
+    for i in [0, 1, 2, 3, 4, 7, 8, 9, 1023, (1 << 35) + 6, (1 << 40) + 13]:
+        blk = i >> 3
         words = oracle.philox4x32_10([blk & 0xFFFFFFFF, blk >> 32, step, worker],
                                      [seed & 0xFFFFFFFF, seed >> 32])
-        k = int(words[i & 3]) >> 8
-        expect = (k + 0.5) / 2.0 ** 24 - 0.5          # exact in float64
+        word = int(words[(i >> 1) & 3])
+        k = (word >> 16) if (i & 1) else (word & 0xFFFF)
+        expect = (k + 0.5) / 2.0 ** 16 - 0.5          # exact in float64
         got = oracle.unit_dither(seed, step, worker, i)
         assert float(got) == expect
         assert -0.5 < got < 0.5
+    # all eight dithers of one block are distinct draws
+    v = oracle.unit_dithers(oracle.dither(seed, step, worker, 0), 4096)
+    assert np.mean(v[0::2] == v[1::2]) < 0.001
 
 
 def test_dither_vector_matches_scalar_and_offset_shifts_the_stream():
@@ -386,7 +390,7 @@ def test_mod_M_code_and_coset_search_equal_the_printed_equations(M):
     for _ in range(4000):
         x = F(rng.uniform(-3, 3))
         y = F(x + rng.normal(0, 0.4))
-        v = F((rng.integers(0, 1 << 24) + 0.5) / 2.0 ** 24 - 0.5)
+        v = F((rng.integers(0, 1 << 16) + 0.5) / 2.0 ** 16 - 0.5)
         u = float(v) * d1
         t = (float(x) + u) / d1
         r_paper = (_paper_nested(float(x), u, float(y), d1, M)[0] - u - float(y)) / (M * d1)
