@@ -25,15 +25,15 @@ HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=30)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", type=int, default=5, help="configuration number (5 = the metric's)")
     ap.add_argument("--n", type=int, default=0, help="override elements per worker (debugging)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--cpu-sample", type=int, default=1 << 27,
                     help="elements per worker the oracle is timed on")
-    ap.add_argument("--kernel-reps", type=int, default=20)
-    ap.add_argument("--schedule", choices=["serial", "overlap", "fused"], default="serial",
+    ap.add_argument("--kernel-reps", type=int, default=50)
+    ap.add_argument("--schedule", choices=["serial", "overlap", "fused"], default="fused",
                     help="serial: one library call per worker and direction, one stream; "
                          "overlap: the same calls, encoders and decoders on two streams; "
                          "fused: all encodes, then the whole server loop in one call")
@@ -42,6 +42,26 @@ def parse_args():
                          "scale=1: 1 GiB read + 1 GiB written) so that a counter run has a "
                          "kernel of known traffic to scale FETCH_SIZE / WRITE_SIZE by")
     return ap.parse_args()
+
+
+VALU_PEAK_TOPS = 256 * 64 * 2.4e9 / 1e12   # 256 CUs x 64 lanes x 2.4 GHz = 39.3 T lane-ops/s
+
+# Algorithmic 32-bit lane-operations per element, counted from the arithmetic the
+# header states on a machine with a 32x32->64 multiply, a three-input logic op and
+# fma (what gfx950 has); work that is uniform across a wave (key schedule, step,
+# 1/step) is not counted.
+OPS_PHILOX = 5      # 10 rounds x (2 multiplies + 2 three-input xors) per 8 elements
+OPS_DITHER = 3      # take the 16-bit half, convert, fma onto the mid-point grid
+OPS = {
+    # widen (bf16) + |.|max + fma + rint + clip + offset/pack (2)
+    "encode": lambda bf16: OPS_PHILOX + OPS_DITHER + 7 + (1 if bf16 else 0),
+    # extract + offset + convert + subtract dither + scale (+ add when accumulating)
+    "dq_decode_store": lambda bf16: OPS_PHILOX + OPS_DITHER + 5,
+    "dq_decode_accumulate": lambda bf16: OPS_PHILOX + OPS_DITHER + 6,
+    # extract, convert, side scale, fma, subtract, divide by M, rint, clamp, fma,
+    # subtract dither, scale, add to the running sum
+    "nested_decode": lambda bf16: OPS_PHILOX + OPS_DITHER + 12,
+}
 
 
 def algorithmic_bytes(kind, n, bits, K, s_in):
@@ -133,21 +153,13 @@ def main():
     grad_bytes = wl.W * n * s_in
     value = grad_bytes / (ms_per_step * 1e-3) / 1e9
 
-    # ---- per-kernel durations with events on the launch stream ------------------
-    def timed(fn, reps):
-        fn()
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(reps):
-            fn()
-        e1.record()
-        torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / reps   # ms
-
-    kernels = []
-    seen = {}
+    # ---- per-kernel durations, in place: events on the launch stream around
+    # every library call of the step, averaged over --kernel-reps further steps ----
+    bf16 = wl.dtype == "bf16"
+    calls = []   # (kernel key, function, algorithmic bytes, algorithmic lane-ops)
     count = 0
+    chain_bytes, chain_ops = 4 * n, 0
+    decs = []
     for w, (kind, arg) in enumerate(wl.plan):
         bits = ndq.ndq_code_bits(arg)
         if kind == "dq":
@@ -169,29 +181,85 @@ def main():
                     bufs.codes[w], n, arg, wl.bucket, bufs.steps[w], ds[w], bufs.total, 1.0 / c,
                     bufs.total, True))
         count += 1
-        for key, fn, akind in ((enc_key, enc, "encode"), (dec_key, dec, dkind)):
-            if key in seen:
-                seen[key]["launches_per_step"] += 1
-                continue
-            ms = timed(fn, args.kernel_reps)
-            nbytes = algorithmic_bytes(akind, n, bits, K, s_in)
-            rec = {"kernel": key, "launches_per_step": 1, "avg_ms": round(ms, 5),
-                   "algorithmic_bytes": nbytes, "GBps": round(nbytes / (ms * 1e-3) / 1e9, 1)}
+        chain_bytes += (n * bits + 7) // 8 + 4 * K
+        chain_ops += n * OPS[dkind](bf16)
+        calls.append((enc_key, enc, algorithmic_bytes("encode", n, bits, K, s_in),
+                      n * OPS["encode"](bf16)))
+        decs.append((dec_key, dec, algorithmic_bytes(dkind, n, bits, K, s_in),
+                     n * OPS[dkind](bf16)))
+    if args.schedule == "fused":
+        calls.append(("decode_chain_w%d" % wl.W,
+                      lambda: pipeline.decode_chain_fused(wl, n, bufs, ds), chain_bytes, chain_ops))
+    else:
+        calls += decs
+        if wl.out_scale != 1.0:
+            calls.append(("aggregate_scale",
+                          lambda: ndq.ndq_aggregate([bufs.total], wl.out_scale, bufs.total),
+                          8 * n, n))
+    reps = args.kernel_reps
+    marks = [[torch.cuda.Event(enable_timing=True) for _ in range(len(calls) + 1)]
+             for _ in range(reps)]
+    torch.cuda.synchronize()
+    for r in range(reps):
+        for i, (_, fn, _, _) in enumerate(calls):
+            marks[r][i].record()
+            fn()
+        marks[r][len(calls)].record()
+    torch.cuda.synchronize()
+    kernels, seen = [], {}
+    for i, (key, _, nbytes, nops) in enumerate(calls):
+        ms = sum(marks[r][i].elapsed_time(marks[r][i + 1]) for r in range(reps)) / reps
+        if key in seen:
+            rec = seen[key]
+            rec["_ms_sum"] += ms
+            rec["launches_per_step"] += 1
+        else:
+            rec = {"kernel": key, "launches_per_step": 1, "_ms_sum": ms,
+                   "algorithmic_bytes": nbytes, "algorithmic_lane_ops": nops}
             seen[key] = rec
             kernels.append(rec)
-    if wl.out_scale != 1.0:
-        ms = timed(lambda: ndq.ndq_aggregate([bufs.total], wl.out_scale, bufs.total),
-                   args.kernel_reps)
-        kernels.append({"kernel": "aggregate_scale", "launches_per_step": 1, "avg_ms": round(ms, 5),
-                        "algorithmic_bytes": 8 * n, "GBps": round(8 * n / (ms * 1e-3) / 1e9, 1)})
+    for rec in kernels:
+        ms = rec.pop("_ms_sum") / rec["launches_per_step"]
+        rec["avg_ms"] = round(ms, 5)
+        rec["GBps"] = round(rec["algorithmic_bytes"] / (ms * 1e-3) / 1e9, 1)
+        rec["Tops"] = round(rec["algorithmic_lane_ops"] / (ms * 1e-3) / 1e12, 2)
+
+    def timed(fn, reps):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps   # ms
+
     dominant = max(kernels, key=lambda r: r["avg_ms"] * r["launches_per_step"])
-    achieved = dominant["algorithmic_bytes"] / (dominant["avg_ms"] * 1e-3) / 1e9
-    roofline = {"bound": "hbm", "kernel": dominant["kernel"], "achieved": round(achieved, 1),
-                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": measured_traffic(dominant["kernel"]),
-                "algorithmic_bytes_per_launch": dominant["algorithmic_bytes"],
-                "avg_launch_ms": dominant["avg_ms"]}
+    sec = dominant["avg_ms"] * 1e-3
+    hbm_frac = dominant["algorithmic_bytes"] / sec / 1e9 / HBM_PEAK_GBS
+    alu_frac = dominant["algorithmic_lane_ops"] / sec / 1e12 / VALU_PEAK_TOPS
+    if hbm_frac >= alu_frac:
+        roofline = {"bound": "hbm", "kernel": dominant["kernel"],
+                    "achieved": round(hbm_frac * HBM_PEAK_GBS, 1), "peak": HBM_PEAK_GBS,
+                    "unit": "GB/s", "frac": round(hbm_frac, 4)}
+    else:
+        roofline = {"bound": "alu", "kernel": dominant["kernel"],
+                    "achieved": round(alu_frac * VALU_PEAK_TOPS, 2),
+                    "peak": round(VALU_PEAK_TOPS, 2), "unit": "Tlane-op/s",
+                    "frac": round(alu_frac, 4)}
+    roofline.update({"traffic": measured_traffic(dominant["kernel"]),
+                     "algorithmic_bytes_per_launch": dominant["algorithmic_bytes"],
+                     "algorithmic_lane_ops_per_launch": dominant["algorithmic_lane_ops"],
+                     "hbm_frac": round(hbm_frac, 4), "alu_frac": round(alu_frac, 4),
+                     "avg_launch_ms": dominant["avg_ms"]})
     step_bytes = sum(r["algorithmic_bytes"] * r["launches_per_step"] for r in kernels)
+
+    # the other schedule, for context (same inputs, same outputs)
+    other = "serial" if args.schedule == "fused" else "fused"
+    other_fn = (lambda: pipeline.step(wl, dev, bufs, ds, preset)) if other == "serial" else (
+        lambda: pipeline.step_fused(wl, dev, bufs, ds, preset))
+    other_ms = timed(other_fn, max(3, args.steps // 3))
 
     # ---- CPU baseline: the oracle, as it stands, on a bounded sample ------------
     cpu = None
@@ -228,6 +296,7 @@ def main():
         "roofline": roofline,
         "cpu_baseline": cpu,
         "kernels": kernels,
+        "other_schedule": {"schedule": other, "ms_per_step": round(other_ms, 4)},
         "input_generation_s": round(gen_s, 1),
     }
     print(json.dumps(out))
