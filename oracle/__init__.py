@@ -88,6 +88,10 @@ def lib():
         L.oracle_dq_encode.restype = None
         L.oracle_dq_decode.argtypes = [vp, sz, u32, u32, vp, Dither, vp, i32]
         L.oracle_dq_decode.restype = None
+        L.oracle_dq_value_half.argtypes = [u32, f32, u32]
+        L.oracle_dq_value_half.restype = f32
+        L.oracle_dq_decode_half.argtypes = [vp, sz, u32, u32, vp, vp, i32]
+        L.oracle_dq_decode_half.restype = None
         L.oracle_nested_encode.argtypes = [vp, i32, sz, f32, u32, u32, u32, Dither, vp, vp]
         L.oracle_nested_encode.restype = None
         L.oracle_nested_decode.argtypes = [vp, sz, u32, u32, vp, Dither, vp, f32, vp, i32]
@@ -225,6 +229,22 @@ def dq_decode(codes, n, levels, bucket, steps, d, out=None):
         out = np.empty(n, dtype=np.float32)
     assert out.dtype == np.float32 and out.size == n and out.flags.c_contiguous
     lib().oracle_dq_decode(_p(codes), n, levels, bucket, _p(steps), d, _p(out), int(acc))
+    return out
+
+
+def dq_value_half(code, delta, levels):
+    return lib().oracle_dq_value_half(code, delta, levels)
+
+
+def dq_decode_half(codes, n, levels, bucket, steps, out=None):
+    """Half-dithered reconstruction Delta*q (no dither subtraction)."""
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    steps = np.ascontiguousarray(steps, dtype=np.float32)
+    acc = out is not None
+    if out is None:
+        out = np.empty(n, dtype=np.float32)
+    assert out.dtype == np.float32 and out.size == n and out.flags.c_contiguous
+    lib().oracle_dq_decode_half(_p(codes), n, levels, bucket, _p(steps), _p(out), int(acc))
     return out
 
 

@@ -125,6 +125,13 @@ float oracle_dq_value(uint32_t code, float delta, float v, uint32_t levels)
     return oracle_index_value((int32_t)code + q_min, delta, v);
 }
 
+float oracle_dq_value_half(uint32_t code, float delta, uint32_t levels)
+{
+    /* x~_h = Q(x+u) = Delta * q */
+    int32_t q_min = -(int32_t)(levels / 2u);
+    return delta * (float)((int32_t)code + q_min);
+}
+
 double oracle_dq_value_f64(uint32_t code, double delta, double v, uint32_t levels)
 {
     int32_t q_min = -(int32_t)(levels / 2u);
@@ -266,6 +273,19 @@ void oracle_dq_decode(const uint8_t* codes, size_t n, uint32_t levels, uint32_t 
         float step = steps[bucket_of(i, bucket)];
         float v = oracle_unit_dither(d.seed, d.step, d.worker, d.offset + i);
         float value = oracle_dq_value(q[i], step, v, levels);
+        out[i] = accumulate ? out[i] + value : value;
+    }
+    free(q);
+}
+
+void oracle_dq_decode_half(const uint8_t* codes, size_t n, uint32_t levels, uint32_t bucket,
+                           const float* steps, float* out, int accumulate)
+{
+    uint32_t bits = oracle_code_bits(levels);
+    uint32_t* q = (uint32_t*)malloc((n ? n : 1u) * sizeof *q);
+    oracle_unpack(codes, n, bits, q);
+    for (size_t i = 0; i < n; ++i) {
+        float value = oracle_dq_value_half(q[i], steps[bucket_of(i, bucket)], levels);
         out[i] = accumulate ? out[i] + value : value;
     }
     free(q);

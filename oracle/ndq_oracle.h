@@ -66,6 +66,11 @@ uint32_t oracle_dq_code(float g, float inv_delta, float v, uint32_t levels);
 float oracle_dq_value(uint32_t code, float delta, float v, uint32_t levels);
 double oracle_dq_value_f64(uint32_t code, double delta, double v, uint32_t levels);
 
+/* Sec. 2.1, half-dithered quantization x~_h = Q(x+u): the receiver does not
+ * subtract the dither (the reconstruction rule of the stochastic and ternary
+ * quantizers the paper compares with, Lemma 1). */
+float oracle_dq_value_half(uint32_t code, float delta, uint32_t levels);
+
 /* unclipped fine index round(g/Delta + v) (saturated at +-2^24) */
 int32_t oracle_fine_index(float g, float inv_delta, float v);
 
@@ -105,6 +110,10 @@ void oracle_dq_encode(const void* g, int dtype, size_t n, float delta, uint32_t 
 /* Server side of Alg. 1.  accumulate: out += g~ instead of out = g~. */
 void oracle_dq_decode(const uint8_t* codes, size_t n, uint32_t levels, uint32_t bucket,
                       const float* steps, oracle_dither d, float* out, int accumulate);
+
+/* Half-dithered server side: out = Delta * q, no dither regenerated. */
+void oracle_dq_decode_half(const uint8_t* codes, size_t n, uint32_t levels, uint32_t bucket,
+                           const float* steps, float* out, int accumulate);
 
 /* Worker side of Alg. 2 for p in P2.  `levels` only sets the fine step. */
 void oracle_nested_encode(const void* g, int dtype, size_t n, float delta, uint32_t levels,

@@ -296,6 +296,75 @@ def test_slice_with_offset_equals_slice_of_the_whole():
 
 
 # --------------------------------------------------------------------------
+# half-dithered reconstruction: Sec. 2.1 (last paragraph) and Sec. 2.1.1, Lemma 1
+# --------------------------------------------------------------------------
+
+def test_half_dithered_equals_stochastic_quantization():
+    """Lemma 1 and the display after it: Q(x+u) without subtraction is unbiased and
+    its error variance is (|x| - l/M)((l+1)/M - |x|) for |x| in [l/M, (l+1)/M] --
+    signal dependent, unlike the subtractive form.  Here M = 4 (9 levels, step 1/4
+    on [-1, 1])."""
+    M, levels, delta = 4, 9, F(0.25)
+    inv = oracle.inv_step(delta)
+    v = oracle.unit_dithers(oracle.dither(3, 1, 4), 200000)
+    for x in (0.3, -0.3, 0.0625, 0.74, -0.9, 0.5):
+        vals = np.array([oracle.dq_value_half(oracle.dq_code(F(x), inv, vi, levels), delta, levels)
+                         for vi in v[:100000]], dtype=np.float64)
+        l = math.floor(abs(x) * M)
+        var = (abs(x) - l / M) * ((l + 1) / M - abs(x))
+        assert set(np.round(np.unique(vals) * M)) <= {math.copysign(l, x), math.copysign(l + 1, x)}
+        assert abs(vals.mean() - x) < 4.5 * math.sqrt(max(var, 1e-9) / vals.size) + 1e-6
+        assert abs(np.mean((vals - x) ** 2) - var) < 0.02 * max(var, 1e-3)
+
+
+def test_half_dithered_average_variance_is_twice_the_subtractive_one():
+    """Text after Lemma 1: for x uniform on [-1, 1] the average error variance of the
+    stochastic quantizer is 1/(6 M^2), twice that of dithered quantization
+    (Delta^2/12 with Delta = 1/M)."""
+    n, M, levels = 1 << 20, 2, 5
+    rng = np.random.default_rng(9)
+    g = rng.uniform(-1, 1, n).astype(F)
+    g[0], g[1] = 1.0, -1.0                       # kappa = 1 exactly
+    d = oracle.dither(4, 0, 2)
+    codes, steps = oracle.dq_encode(g, 0.0, levels, 0, d)
+    assert steps[0] == F(0.5)
+    full = oracle.dq_decode(codes, n, levels, 0, steps, d)
+    half = oracle.dq_decode_half(codes, n, levels, 0, steps)
+    var_full = np.mean((full.astype(np.float64) - g) ** 2)
+    var_half = np.mean((half.astype(np.float64) - g) ** 2)
+    assert abs(var_full / (1 / (12 * M * M)) - 1) < 0.01
+    assert abs(var_half / (1 / (6 * M * M)) - 1) < 0.01
+    assert abs(np.mean(half.astype(np.float64) - g)) < 4 * math.sqrt(var_half / n)
+    # the half-dithered error is correlated with where g sits in its cell
+    frac = g.astype(np.float64) / 0.5
+    frac = np.abs(frac - np.round(frac))
+    err2 = (half.astype(np.float64) - g) ** 2
+    assert err2[frac > 0.4].mean() > 3 * err2[frac < 0.1].mean()
+    # accumulate adds into an existing buffer; the values are lattice points
+    base = rng.standard_normal(n).astype(F)
+    acc = oracle.dq_decode_half(codes, n, levels, 0, steps, out=base.copy())
+    assert np.array_equal(acc, base + half)
+    assert np.all(np.isin(half, np.array([-1, -0.5, 0, 0.5, 1], dtype=F)))
+
+
+def test_ternary_special_case():
+    """Sec. 2.1.1: the ternary quantizer is the stochastic one with M = 1: three
+    levels, outputs in {-kappa, 0, +kappa}, still unbiased."""
+    n = 1 << 18
+    rng = np.random.default_rng(2)
+    g = (rng.standard_normal(n) * 0.01).astype(F)
+    d = oracle.dither(8, 8, 8)
+    codes, steps = oracle.dq_encode(g, 0.0, 3, 0, d)
+    kappa = F(np.abs(g).max())
+    assert steps[0] == kappa
+    out = oracle.dq_decode_half(codes, n, 3, 0, steps)
+    assert set(np.unique(out)) <= {-kappa, F(0), kappa}
+    # P(nonzero) = |g|/kappa on average
+    assert abs(np.mean(out != 0) - np.mean(np.abs(g)) / kappa) < 0.005
+    assert abs(np.mean(out.astype(np.float64) - g)) < 4 * float(kappa) * math.sqrt(0.1 / n)
+
+
+# --------------------------------------------------------------------------
 # bitstream
 # --------------------------------------------------------------------------
 
