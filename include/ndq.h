@@ -117,6 +117,14 @@ int ndq_dq_decode(const void* codes, size_t n, uint32_t levels, uint32_t bucket,
                   const float* steps, const ndq_dither* d, float* out, int accumulate,
                   void* stream);
 
+/* Half-dithered server side (Sec. 2.1, last paragraph; Sec. 2.1.1, Lemma 1): the
+ * receiver does not regenerate the dither, out_i = Delta_b * q_i (or += with
+ * accumulate).  Applied to the codes of ndq_dq_encode this is the reconstruction
+ * rule of stochastic quantization (levels = 2M+1) and of ternary quantization
+ * (levels = 3): unbiased, but with an error that depends on the signal. */
+int ndq_dq_decode_half(const void* codes, size_t n, uint32_t levels, uint32_t bucket,
+                       const float* steps, float* out, int accumulate, void* stream);
+
 /* Worker side of Algorithm 2 for a worker of group P2 (eq. (7), alpha = 1): the
  * fine index modulo M.  The step is chosen exactly as in ndq_dq_encode
  * (`levels` only fixes the fine step; it does not clip).

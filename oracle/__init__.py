@@ -92,6 +92,10 @@ def lib():
         L.oracle_dq_value_half.restype = f32
         L.oracle_dq_decode_half.argtypes = [vp, sz, u32, u32, vp, vp, i32]
         L.oracle_dq_decode_half.restype = None
+        L.oracle_code_histogram.argtypes = [vp, sz, u32, vp]
+        L.oracle_code_histogram.restype = None
+        L.oracle_entropy_bits.argtypes = [vp, u32]
+        L.oracle_entropy_bits.restype = C.c_double
         L.oracle_nested_encode.argtypes = [vp, i32, sz, f32, u32, u32, u32, Dither, vp, vp]
         L.oracle_nested_encode.restype = None
         L.oracle_nested_decode.argtypes = [vp, sz, u32, u32, vp, Dither, vp, f32, vp, i32]
@@ -246,6 +250,18 @@ def dq_decode_half(codes, n, levels, bucket, steps, out=None):
     assert out.dtype == np.float32 and out.size == n and out.flags.c_contiguous
     lib().oracle_dq_decode_half(_p(codes), n, levels, bucket, _p(steps), _p(out), int(acc))
     return out
+
+
+def code_histogram(codes, n, bits):
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    hist = np.zeros(1 << bits, dtype=np.uint64)
+    lib().oracle_code_histogram(_p(codes), n, bits, _p(hist))
+    return hist
+
+
+def entropy_bits(hist):
+    hist = np.ascontiguousarray(hist, dtype=np.uint64)
+    return lib().oracle_entropy_bits(_p(hist), hist.size)
 
 
 def nested_encode(g, delta, levels, M, bucket, d):

@@ -203,6 +203,36 @@ void oracle_unpack(const uint8_t* in, size_t n, uint32_t bits, uint32_t* codes)
 }
 
 /* ------------------------------------------------------------------------- */
+/* Entropy of the index stream (Sec. 4, paragraph before Table 1: adaptive      */
+/* arithmetic coding gets within a few percent of the entropy, so the entropy  */
+/* of the indices is what is reported).                                         */
+/* ------------------------------------------------------------------------- */
+
+void oracle_code_histogram(const uint8_t* codes, size_t n, uint32_t bits, uint64_t* hist)
+{
+    uint32_t nbins = 1u << bits;
+    for (uint32_t c = 0; c < nbins; ++c) hist[c] = 0u;
+    uint32_t* q = (uint32_t*)malloc((n ? n : 1u) * sizeof *q);
+    oracle_unpack(codes, n, bits, q);
+    for (size_t i = 0; i < n; ++i) hist[q[i]] += 1u;
+    free(q);
+}
+
+double oracle_entropy_bits(const uint64_t* hist, uint32_t nbins)
+{
+    uint64_t total = 0u;
+    for (uint32_t c = 0; c < nbins; ++c) total += hist[c];
+    if (total == 0u) return 0.0;
+    double h = 0.0;
+    for (uint32_t c = 0; c < nbins; ++c)
+        if (hist[c]) {
+            double p = (double)hist[c] / (double)total;
+            h -= p * log2(p);
+        }
+    return h;
+}
+
+/* ------------------------------------------------------------------------- */
 /* Vector calls                                                                */
 /* ------------------------------------------------------------------------- */
 

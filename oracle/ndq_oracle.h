@@ -89,6 +89,13 @@ size_t oracle_num_buckets(size_t n, uint32_t bucket); /* bucket==0 -> 1 */
 void oracle_pack(const uint32_t* codes, size_t n, uint32_t bits, uint8_t* out);
 void oracle_unpack(const uint8_t* in, size_t n, uint32_t bits, uint32_t* codes);
 
+/* ---- entropy of an index stream (Sec. 4: bits after entropy coding are
+ * reported through the entropy of the transmitted indices) ---- */
+/* hist[c] = number of codes equal to c, c in [0, 2^bits) */
+void oracle_code_histogram(const uint8_t* codes, size_t n, uint32_t bits, uint64_t* hist);
+/* -sum_c p_c log2 p_c with p_c = hist[c]/n, in bits per code; 0 for n == 0 */
+double oracle_entropy_bits(const uint64_t* hist, uint32_t nbins);
+
 /* ---- vector calls, mirroring the library's entry points ---- */
 
 /* seed s_p, iteration, worker p, and the index within the worker's whole

@@ -124,10 +124,12 @@ __device__ __forceinline__ float inv_step(float step)
 // Quantizer parameters shared by encoder and decoder.
 //   kDq           : DQSG, clipped to `levels` indices            (Algorithm 1)
 //   kDqNarrow     : the same for codes of at most 6 bits (encoder packs in float)
+//   kDqHalf       : decoder only: half-dithered reconstruction Delta*q, no dither
+//                   regenerated (Sec. 2.1, last paragraph; Lemma 1)
 //   kNestedPow2   : NDQSG, M a power of two (mask / exact scale) (Algorithm 2)
 //   kNestedAnyM   : NDQSG, any M in [2,256]
 // ---------------------------------------------------------------------------
-enum Mode { kDq = 0, kNestedPow2 = 1, kNestedAnyM = 2, kDqNarrow = 3 };  // kDqNarrow: DQSG, codes of <= 6 bits
+enum Mode { kDq = 0, kNestedPow2 = 1, kNestedAnyM = 2, kDqNarrow = 3, kDqHalf = 4 };
 
 struct Quant {
     float q_min_f, q_max_f;  // DQSG index range as floats

@@ -200,7 +200,7 @@ struct DecodeArgs {
 
 template <int ROWS> struct DecTile { static constexpr uint32_t N = kWave * 4 * ROWS; };  // outputs per wave
 template <int MODE, int ACC> struct DecRows {
-    static constexpr int R = (MODE == kDq && ACC == 0) ? kDecRowsStream : kDecRowsUpdate;
+    static constexpr int R = ((MODE == kDq || MODE == kDqHalf) && ACC == 0) ? kDecRowsStream : kDecRowsUpdate;
 };
 
 enum Acc { kStore = 0, kAccumulate = 1, kAccumulateInPlace = 2 };  // in place: out == side
@@ -242,14 +242,14 @@ __device__ __forceinline__ void decode_tile(const DecodeArgs& a, const TileRef& 
                 packed[r] = codes32[w] >> sh;
             }
             if (FULL || o + 4 <= t.len) {
-                if (MODE != kDq) y[r] = *(const float4*)(side + o);
+                if (MODE == kNestedPow2 || MODE == kNestedAnyM) y[r] = *(const float4*)(side + o);
                 if (ACC == kAccumulate) prev[r] = *(const float4*)(out + o);
             } else {
                 float ys[4] = {0.f, 0.f, 0.f, 0.f}, ps[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (uint32_t k = 0; k < 4; ++k)
                     if (o + k < t.len) {
-                        if (MODE != kDq) ys[k] = side[o + k];
+                        if (MODE == kNestedPow2 || MODE == kNestedAnyM) ys[k] = side[o + k];
                         if (ACC == kAccumulate) ps[k] = out[o + k];
                     }
                 y[r] = make_float4(ys[0], ys[1], ys[2], ys[3]);
@@ -261,8 +261,8 @@ __device__ __forceinline__ void decode_tile(const DecodeArgs& a, const TileRef& 
     for (int r = 0; r < kDecRows; ++r) {
         const uint32_t o = (uint32_t)r * kWave * 4 + (uint32_t)lane * 4;
         if (!FULL && o >= t.len) continue;
-        float v[4];
-        dither4(a.ds, block0 + (o >> 2), v);
+        float v[4] = {0.f, 0.f, 0.f, 0.f};
+        if (MODE != kDqHalf) dither4(a.ds, block0 + (o >> 2), v);
         const float ys[4] = {y[r].x, y[r].y, y[r].z, y[r].w};
         const float ps[4] = {prev[r].x, prev[r].y, prev[r].z, prev[r].w};
         float res[4];
@@ -270,13 +270,13 @@ __device__ __forceinline__ void decode_tile(const DecodeArgs& a, const TileRef& 
         for (int k = 0; k < 4; ++k) {
             const uint32_t c = (packed[r] >> (k * bits)) & mask;
             float q;
-            if (MODE == kDq) {
+            if (MODE == kDq || MODE == kDqHalf) {
                 q = (float)((int32_t)c + a.qp.q_min);
             } else {
                 const float yk = ys[k] * a.side_scale;
                 q = coset_index_f<MODE>(c, yk, inv, v[k], a.qp);
             }
-            const float val = index_value(q, step, v[k]);
+            const float val = (MODE == kDqHalf) ? step * q : index_value(q, step, v[k]);
             if (ACC == kStore) res[k] = val;
             else if (ACC == kAccumulate) res[k] = ps[k] + val;
             else res[k] = ys[k] + val;
@@ -674,7 +674,7 @@ static int run_decode(const DecodeArgs& a, uint64_t n, uint32_t bucket, int acc,
 }
 
 static int decode_common(const void* codes, size_t n, uint32_t levels, uint32_t M, bool nested,
-                         uint32_t bucket, const float* steps, const ndq_dither* d,
+                         bool half, uint32_t bucket, const float* steps, const ndq_dither* d,
                          const float* side, float side_scale, float* out, int accumulate,
                          void* stream)
 {
@@ -703,7 +703,8 @@ static int decode_common(const void* codes, size_t n, uint32_t levels, uint32_t 
     hipStream_t s = (hipStream_t)stream;
     int acc = accumulate ? kAccumulate : kStore;
     if (nested && accumulate && side == out) acc = kAccumulateInPlace;
-    if (!nested) return run_decode<kDq>(a, n, bucket, acc, s);
+    if (!nested) return half ? run_decode<kDqHalf>(a, n, bucket, acc, s)
+                             : run_decode<kDq>(a, n, bucket, acc, s);
     if (is_pow2(M)) return run_decode<kNestedPow2>(a, n, bucket, acc, s);
     return run_decode<kNestedAnyM>(a, n, bucket, acc, s);
 }
@@ -768,8 +769,16 @@ int ndq_dq_decode(const void* codes, size_t n, uint32_t levels, uint32_t bucket,
                   const float* steps, const ndq_dither* d, float* out, int accumulate,
                   void* stream)
 {
-    return ndq::decode_common(codes, n, levels, 0u, false, bucket, steps, d, nullptr, 1.0f, out,
-                              accumulate, stream);
+    return ndq::decode_common(codes, n, levels, 0u, false, false, bucket, steps, d, nullptr, 1.0f,
+                              out, accumulate, stream);
+}
+
+int ndq_dq_decode_half(const void* codes, size_t n, uint32_t levels, uint32_t bucket,
+                       const float* steps, float* out, int accumulate, void* stream)
+{
+    const ndq_dither none = {0u, 0u, 0u, 0u};   // no dither is regenerated
+    return ndq::decode_common(codes, n, levels, 0u, false, true, bucket, steps, &none, nullptr,
+                              1.0f, out, accumulate, stream);
 }
 
 int ndq_nested_decode(const void* codes, size_t n, uint32_t M, uint32_t bucket,
@@ -777,8 +786,8 @@ int ndq_nested_decode(const void* codes, size_t n, uint32_t M, uint32_t bucket,
                       float side_scale, float* out, int accumulate, void* stream)
 {
     // `levels` plays no part in decoding: the step travels in `steps`
-    return ndq::decode_common(codes, n, 2u, M, true, bucket, steps, d, side, side_scale, out,
-                              accumulate, stream);
+    return ndq::decode_common(codes, n, 2u, M, true, false, bucket, steps, d, side, side_scale,
+                              out, accumulate, stream);
 }
 
 int ndq_aggregate(const float* const* gs, uint32_t W, size_t n, float scale, float* out,

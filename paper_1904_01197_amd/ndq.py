@@ -18,7 +18,7 @@ NDQ_F32, NDQ_BF16 = 0, 1
 NDQ_OK, NDQ_EINVAL, NDQ_EALIGN, NDQ_EUNSUPPORTED, NDQ_ELAUNCH = 0, -1, -2, -3, -4
 
 EXPORTS = ("ndq_code_bits", "ndq_packed_bytes", "ndq_num_buckets", "ndq_absmax", "ndq_dq_encode",
-           "ndq_dq_decode", "ndq_nested_encode", "ndq_nested_decode", "ndq_aggregate",
+           "ndq_dq_decode", "ndq_dq_decode_half", "ndq_nested_encode", "ndq_nested_decode", "ndq_aggregate",
            "ndq_decode_chain", "ndq_strerror")
 
 
@@ -65,6 +65,8 @@ def lib():
         L.ndq_dq_encode.restype = ci
         L.ndq_dq_decode.argtypes = [vp, sz, u32, u32, vp, dp, vp, ci, vp]
         L.ndq_dq_decode.restype = ci
+        L.ndq_dq_decode_half.argtypes = [vp, sz, u32, u32, vp, vp, ci, vp]
+        L.ndq_dq_decode_half.restype = ci
         L.ndq_nested_encode.argtypes = [vp, ci, sz, f32, u32, u32, u32, dp, vp, vp, vp]
         L.ndq_nested_encode.restype = ci
         L.ndq_nested_decode.argtypes = [vp, sz, u32, u32, vp, dp, vp, f32, vp, ci, vp]
@@ -165,6 +167,19 @@ def ndq_dq_decode(codes, n, levels, bucket, steps, d, out=None, accumulate=False
     _check(lib().ndq_dq_decode(_dev(codes, "codes"), n, levels, bucket, _dev(steps, "steps"),
                                C.byref(d), _dev(out, "out"), int(bool(accumulate)), _stream()),
            "ndq_dq_decode")
+    return out
+
+
+def ndq_dq_decode_half(codes, n, levels, bucket, steps, out=None, accumulate=False):
+    if out is None:
+        if accumulate:
+            raise ValueError("accumulate needs an existing out")
+        out = torch.empty(n, dtype=torch.float32, device=codes.device)
+    if out.dtype != torch.float32 or out.numel() < n:
+        raise ValueError("out must hold n float32")
+    _check(lib().ndq_dq_decode_half(_dev(codes, "codes"), n, levels, bucket, _dev(steps, "steps"),
+                                    _dev(out, "out"), int(bool(accumulate)), _stream()),
+           "ndq_dq_decode_half")
     return out
 
 

@@ -88,6 +88,24 @@ def test_dq_encode_decode_matches_oracle(dtype, levels, bucket, preset):
         assert np.array_equal(acc.cpu().numpy(), ref_acc)
 
 
+@pytest.mark.parametrize("levels,bucket", [(3, 0), (5, 2048), (9, 64), (16, 4096), (256, 2112), (7, 0)])
+def test_half_dithered_decode_matches_oracle(levels, bucket):
+    """Reconstruction without dither subtraction (stochastic / ternary quantizers'
+    rule): out = Delta * q, bit-exact."""
+    for n in SIZES:
+        g = _make(n, "f32", seed=n + levels)
+        d_o, d_g = oracle.dither(2, 3, 4), ndq.ndq_dither(2, 3, 4, 0)
+        c_ref, s_ref = oracle.dq_encode(g, 0.0, levels, bucket, d_o)
+        codes, steps = ndq.ndq_dq_encode(_to_dev(g), 0.0, levels, bucket, d_g)
+        ref = oracle.dq_decode_half(c_ref, n, levels, bucket, s_ref)
+        out = ndq.ndq_dq_decode_half(codes, n, levels, bucket, steps)
+        assert np.array_equal(out.cpu().numpy(), ref), n
+        base = _make(n, "f32", seed=n + 9)
+        ref_acc = oracle.dq_decode_half(c_ref, n, levels, bucket, s_ref, out=base.copy())
+        acc = ndq.ndq_dq_decode_half(codes, n, levels, bucket, steps, _to_dev(base), True)
+        assert np.array_equal(acc.cpu().numpy(), ref_acc), n
+
+
 def test_config1_dqsg_roundtrip():
     """n = 65,536 fp32 N(0, 0.01^2), 3 levels (2-bit codes), Delta = 2 max|g|/(3-1),
     dither (seed 0, step 0): encode -> pack -> unpack -> decode."""

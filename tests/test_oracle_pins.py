@@ -411,6 +411,62 @@ def test_raw_bits_accounting_matches_table_1(golden_dir):
 
 
 # --------------------------------------------------------------------------
+# entropy of the index stream (Sec. 4)
+# --------------------------------------------------------------------------
+
+def test_entropy_closed_forms():
+    for bits in (1, 2, 3, 4, 8):
+        L = 1 << bits
+        codes = np.tile(np.arange(L, dtype=np.uint32), 50)
+        hist = oracle.code_histogram(oracle.pack(codes, bits), codes.size, bits)
+        assert np.all(hist == 50)
+        assert abs(oracle.entropy_bits(hist) - bits) < 1e-12          # uniform: log2 L
+        const = oracle.pack(np.full(1000, L - 1, dtype=np.uint32), bits)
+        hist = oracle.code_histogram(const, 1000, bits)
+        assert hist[L - 1] == 1000 and hist.sum() == 1000
+        assert oracle.entropy_bits(hist) == 0.0                       # one symbol: 0 bits
+    # binary entropy function
+    codes = np.array([1] * 250 + [0] * 750, dtype=np.uint32)
+    hist = oracle.code_histogram(oracle.pack(codes, 1), 1000, 1)
+    assert abs(oracle.entropy_bits(hist) - (-(0.25 * math.log2(0.25) + 0.75 * math.log2(0.75)))) < 1e-12
+    assert oracle.entropy_bits(np.zeros(4, dtype=np.uint64)) == 0.0
+    # padding bits of the stream are not counted
+    hist = oracle.code_histogram(oracle.pack(np.array([3, 3, 3], dtype=np.uint32), 2), 3, 2)
+    assert list(hist) == [0, 0, 0, 3]
+
+
+def test_index_probabilities_of_gaussian_gradients():
+    """For g ~ N(0, sigma^2) and a uniform dither the index law is
+    P(q = l) = E_v[Phi((l + 1/2 - v) D/s) - Phi((l - 1/2 - v) D/s)] (clipped at the
+    ends); the measured histogram and its entropy follow it.  This is the kind of
+    figure Table 2 reports (there on trained gradients)."""
+    n, levels, sigma, delta = 1 << 20, 9, 0.01, F(0.004)
+    rng = np.random.default_rng(31)
+    g = (rng.standard_normal(n) * sigma).astype(F)
+    codes, steps = oracle.dq_encode(g, delta, levels, 0, oracle.dither(6, 2, 1))
+    hist = oracle.code_histogram(codes, n, 4)
+    assert hist.sum() == n and np.all(hist[levels:] == 0)
+    r = float(delta) / sigma
+    edges = lambda l, v: (stats.norm.cdf((l + 0.5 - v) * r), stats.norm.cdf((l - 0.5 - v) * r))
+    probs = []
+    for c in range(levels):
+        l = c - levels // 2
+        if c == 0:
+            f = lambda v: stats.norm.cdf((l + 0.5 - v) * r)
+        elif c == levels - 1:
+            f = lambda v: stats.norm.sf((l - 0.5 - v) * r)
+        else:
+            f = lambda v: stats.norm.cdf((l + 0.5 - v) * r) - stats.norm.cdf((l - 0.5 - v) * r)
+        probs.append(integrate.quad(f, -0.5, 0.5)[0])
+    probs = np.array(probs)
+    assert abs(probs.sum() - 1) < 1e-9
+    assert np.all(np.abs(hist[:levels] / n - probs) < 5 * np.sqrt(probs / n) + 1e-6)
+    h_exact = -np.sum(probs * np.log2(probs))
+    assert abs(oracle.entropy_bits(hist) - h_exact) < 0.01
+    assert oracle.entropy_bits(hist) < math.log2(levels)
+
+
+# --------------------------------------------------------------------------
 # NDQSG: Sec. 3.2 eqs. (7), (8), Fig. 3 example, Thm 4, Algorithm 2
 # --------------------------------------------------------------------------
 
