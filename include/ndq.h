@@ -176,6 +176,16 @@ typedef struct {
 int ndq_decode_chain(const ndq_worker* workers, uint32_t W, size_t n, uint32_t bucket,
                      float scale, float* out, void* stream);
 
+/* Histogram and empirical entropy of a packed code stream (Sec. 4: the bits left
+ * after entropy coding are reported through the entropy of the transmitted
+ * indices).  hist_out: 2^bits uint64 (device, 8-byte aligned), hist_out[c] = number
+ * of the n codes equal to c; padding bits are not counted.  entropy_out: one
+ * double (device) = -sum_c p_c log2 p_c in bits per code, p_c = hist_out[c]/n
+ * (0 when n == 0); may be NULL to get the histogram only.  bits in [1,8].
+ * Unlike the other calls this one also runs for n == 0 (it clears its outputs). */
+int ndq_code_entropy(const void* codes, size_t n, uint32_t bits, uint64_t* hist_out,
+                     double* entropy_out, void* stream);
+
 /* Static, human-readable text for a status code. */
 const char* ndq_strerror(int rc);
 

@@ -507,6 +507,115 @@ __global__ __launch_bounds__(kBlock) void aggregate_kernel(AggArgs a)
 }
 
 // ---------------------------------------------------------------------------
+// Histogram and entropy of an index stream (Sec. 4: the bit rate after entropy
+// coding is reported through the entropy of the transmitted indices).
+// A thread reads units of 32 codes (= `bits` consecutive 32-bit words) with a
+// small bit reader.  Counting: 1-bit and 2-bit streams by population count in
+// registers; up to 16 bins in a private LDS column per thread (no conflicts);
+// wider codes with LDS atomics on one histogram per workgroup.
+// ---------------------------------------------------------------------------
+constexpr int kHistBlock = 256;
+
+__global__ __launch_bounds__(kHistBlock) void histogram_kernel(const uint32_t* __restrict__ words,
+                                                               uint64_t n, uint32_t bits,
+                                                               unsigned long long* hist)
+{
+    __shared__ uint32_t cols[16][kHistBlock];   // bits <= 4: one column per thread
+    __shared__ uint32_t wide[256];              // bits  > 4: shared, atomic
+    const uint32_t tid = threadIdx.x;
+    const uint32_t nbins = 1u << bits;
+    for (uint32_t b = 0; b < 16; ++b) cols[b][tid] = 0u;
+    wide[tid] = 0u;
+    __syncthreads();
+
+    const uint64_t units = (n + 31u) >> 5;
+    const uint32_t mask = nbins - 1u;
+    uint32_t c1 = 0u, c2 = 0u, c3 = 0u, seen = 0u;   // registers for the 1- and 2-bit paths
+    for (uint64_t u = (uint64_t)blockIdx.x * kHistBlock + tid; u < units;
+         u += (uint64_t)gridDim.x * kHistBlock) {
+        const uint32_t valid = (u + 1u == units) ? (uint32_t)(n - (u << 5)) : 32u;
+        const uint32_t* p = words + u * bits;
+        if (bits == 1u) {
+            uint32_t w = p[0];
+            if (valid < 32u) w &= (1u << valid) - 1u;
+            c1 += __builtin_popcount(w);
+            seen += valid;
+        } else if (bits == 2u) {
+#pragma unroll
+            for (uint32_t j = 0; j < 2; ++j) {
+                const uint32_t have = valid > 16u * j ? (valid - 16u * j < 16u ? valid - 16u * j : 16u) : 0u;
+                uint32_t w = have ? p[j] : 0u;
+                uint32_t field = have == 16u ? 0x55555555u : ((1u << (2u * have)) - 1u) & 0x55555555u;
+                const uint32_t lo = w & field, hi = (w >> 1) & field;
+                c1 += __builtin_popcount(lo & ~hi);
+                c2 += __builtin_popcount(hi & ~lo);
+                c3 += __builtin_popcount(lo & hi);
+                seen += have;
+            }
+        } else {
+            uint64_t buf = 0u;
+            uint32_t have = 0u, next = 0u;
+            for (uint32_t j = 0; j < valid; ++j) {
+                if (have < bits) {
+                    buf |= (uint64_t)p[next++] << have;
+                    have += 32u;
+                }
+                const uint32_t code = (uint32_t)buf & mask;
+                buf >>= bits;
+                have -= bits;
+                if (bits <= 4u) cols[code][tid] += 1u;      // private column: no race
+                else atomicAdd(&wide[code], 1u);
+            }
+        }
+    }
+    if (bits == 1u) {
+        cols[1][tid] = c1; cols[0][tid] = seen - c1;
+    } else if (bits == 2u) {
+        cols[1][tid] = c1; cols[2][tid] = c2; cols[3][tid] = c3; cols[0][tid] = seen - c1 - c2 - c3;
+    }
+    __syncthreads();
+    if (bits <= 4u) {
+        // 16 threads per bin add up the bin's 256 columns, then one atomic per bin and block
+        const uint32_t bin = tid >> 4, part = tid & 15u;
+        uint32_t sum = 0u;
+        for (uint32_t k = 0; k < kHistBlock / 16; ++k) sum += cols[bin][part * (kHistBlock / 16) + k];
+#pragma unroll
+        for (int sft = 8; sft >= 1; sft >>= 1) sum += __shfl_xor(sum, sft, 16);
+        if (part == 0u && bin < nbins && sum) atomicAdd(hist + bin, (unsigned long long)sum);
+    } else if (tid < nbins && wide[tid]) {
+        atomicAdd(hist + tid, (unsigned long long)wide[tid]);
+    }
+}
+
+__global__ void fill_zero64_kernel(unsigned long long* p, uint32_t count)
+{
+    if (threadIdx.x < count) p[threadIdx.x] = 0ull;
+}
+
+// -sum p log2 p over at most 256 bins, binary64, fixed reduction order
+__global__ __launch_bounds__(256) void entropy_kernel(const unsigned long long* hist, uint32_t nbins,
+                                                      uint64_t n, double* entropy_out)
+{
+    __shared__ double term[256];
+    const uint32_t tid = threadIdx.x;
+    double t = 0.0;
+    if (tid < nbins && n) {
+        const unsigned long long h = hist[tid];
+        if (h) {
+            const double p = (double)h / (double)n;
+            t = -p * log2(p);
+        }
+    }
+    term[tid] = t;
+    __syncthreads();
+    for (uint32_t s = 128; s >= 1; s >>= 1) {
+        if (tid < s) term[tid] += term[tid + s];
+        __syncthreads();
+    }
+    if (tid == 0) entropy_out[0] = term[0];
+}
+
+// ---------------------------------------------------------------------------
 // Host side: validation and dispatch
 // ---------------------------------------------------------------------------
 static uint32_t code_bits(uint32_t x)
@@ -874,6 +983,35 @@ int ndq_decode_chain(const ndq_worker* workers, uint32_t W, size_t n, uint32_t b
         }
         hipLaunchKernelGGL(chain_kernel, dim3(blocks_for(a.tl.total_tiles)), dim3(kBlock), 0,
                            (hipStream_t)stream, a);
+        if (launched() != NDQ_OK) return NDQ_ELAUNCH;
+    }
+    return NDQ_OK;
+}
+
+int ndq_code_entropy(const void* codes, size_t n, uint32_t bits, uint64_t* hist_out,
+                     double* entropy_out, void* stream)
+{
+    using namespace ndq;
+    if (bits < 1u || bits > 8u || !hist_out) return NDQ_EINVAL;
+    if (n >= kMaxN) return NDQ_EUNSUPPORTED;
+    if (((uintptr_t)hist_out & 7u) != 0u || ((uintptr_t)entropy_out & 7u) != 0u) return NDQ_EALIGN;
+    if (n != 0 && !codes) return NDQ_EINVAL;
+    if (n != 0 && !aligned16(codes)) return NDQ_EALIGN;
+    hipStream_t s = (hipStream_t)stream;
+    const uint32_t nbins = 1u << bits;
+    hipLaunchKernelGGL(fill_zero64_kernel, dim3(1), dim3(256), 0, s, (unsigned long long*)hist_out, nbins);
+    if (launched() != NDQ_OK) return NDQ_ELAUNCH;
+    if (n != 0) {
+        const uint64_t units = (n + 31u) >> 5;
+        uint64_t blocks = (units + kHistBlock - 1) / kHistBlock;
+        if (blocks > 4096u) blocks = 4096u;
+        hipLaunchKernelGGL(histogram_kernel, dim3((uint32_t)blocks), dim3(kHistBlock), 0, s,
+                           (const uint32_t*)codes, (uint64_t)n, bits, (unsigned long long*)hist_out);
+        if (launched() != NDQ_OK) return NDQ_ELAUNCH;
+    }
+    if (entropy_out) {
+        hipLaunchKernelGGL(entropy_kernel, dim3(1), dim3(256), 0, s,
+                           (const unsigned long long*)hist_out, nbins, (uint64_t)n, entropy_out);
         if (launched() != NDQ_OK) return NDQ_ELAUNCH;
     }
     return NDQ_OK;

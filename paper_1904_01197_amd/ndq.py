@@ -19,7 +19,7 @@ NDQ_OK, NDQ_EINVAL, NDQ_EALIGN, NDQ_EUNSUPPORTED, NDQ_ELAUNCH = 0, -1, -2, -3, -
 
 EXPORTS = ("ndq_code_bits", "ndq_packed_bytes", "ndq_num_buckets", "ndq_absmax", "ndq_dq_encode",
            "ndq_dq_decode", "ndq_dq_decode_half", "ndq_nested_encode", "ndq_nested_decode", "ndq_aggregate",
-           "ndq_decode_chain", "ndq_strerror")
+           "ndq_decode_chain", "ndq_code_entropy", "ndq_strerror")
 
 
 class ndq_dither(C.Structure):
@@ -74,6 +74,7 @@ def lib():
         L.ndq_aggregate.argtypes, L.ndq_aggregate.restype = [vp, u32, sz, f32, vp, vp], ci
         L.ndq_decode_chain.argtypes = [C.POINTER(ndq_worker), u32, sz, u32, f32, vp, vp]
         L.ndq_decode_chain.restype = ci
+        L.ndq_code_entropy.argtypes, L.ndq_code_entropy.restype = [vp, sz, u32, vp, vp, vp], ci
         L.ndq_strerror.argtypes, L.ndq_strerror.restype = [ci], C.c_char_p
         _lib = L
     return _lib
@@ -226,3 +227,16 @@ def ndq_decode_chain(workers, n, bucket, scale=1.0, out=None):
     _check(lib().ndq_decode_chain(arr, len(workers), n, bucket, scale, _dev(out, "out"),
                                   _stream()), "ndq_decode_chain")
     return out
+
+
+def ndq_code_entropy(codes, n, bits, hist_out=None, entropy_out=None):
+    """-> (histogram int64 tensor of 2^bits counts, entropy float64 tensor of 1 element)"""
+    dev = codes.device
+    if hist_out is None:
+        hist_out = torch.empty(1 << bits, dtype=torch.int64, device=dev)
+    if entropy_out is None:
+        entropy_out = torch.empty(1, dtype=torch.float64, device=dev)
+    cptr = _dev(codes, "codes") if n else C.c_void_p(0)
+    _check(lib().ndq_code_entropy(cptr, n, bits, _dev(hist_out, "hist_out"),
+                                  _dev(entropy_out, "entropy_out"), _stream()), "ndq_code_entropy")
+    return hist_out, entropy_out

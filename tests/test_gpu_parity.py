@@ -502,3 +502,38 @@ def test_fused_step_equals_call_by_call_step_on_the_configs():
         preset = float(b1.steps[0][0].item()) if wl.shared_step else 0.0
         out = pipeline.step_fused(wl, dev, b2, ds, preset)
         assert torch.equal(out, ref), cfg
+
+
+# --------------------------------------------------------------------------
+# histogram and entropy of the index stream
+# --------------------------------------------------------------------------
+
+@pytest.mark.parametrize("bits", [1, 2, 3, 4, 5, 6, 7, 8])
+def test_code_histogram_and_entropy_match_oracle(bits):
+    dev = _gpu()
+    for n in (0, 1, 31, 32, 33, 1000, 8191, 65536 + 17, 3000001):
+        rng = np.random.default_rng(n + bits)
+        # skewed code distribution, like real index streams
+        p = rng.dirichlet(np.full(1 << bits, 0.3))
+        codes = rng.choice(1 << bits, size=n, p=p).astype(np.uint32)
+        packed = oracle.pack(codes, bits)
+        ref_h = oracle.code_histogram(packed, n, bits)
+        ref_e = oracle.entropy_bits(ref_h)
+        hist, ent = ndq.ndq_code_entropy(torch.from_numpy(packed).to(dev), n, bits)
+        assert np.array_equal(hist.cpu().numpy().astype(np.uint64), ref_h), (bits, n)
+        assert abs(float(ent.item()) - ref_e) <= 1e-9, (bits, n)
+
+
+def test_entropy_of_the_benchmark_code_streams():
+    """Entropy of the actual DQSG / nested index streams of config 5 (reduced size):
+    GPU histogram against the oracle's, bit-exact."""
+    wl = workloads.CONFIGS[5]
+    n = (1 << 21) + 123
+    host, c_ref, s_ref, ds_o, bufs, ds_g = _run_both(wl, n)
+    for w, (kind, arg) in enumerate(wl.plan):
+        bits = oracle.code_bits(arg)
+        ref_h = oracle.code_histogram(c_ref[w], n, bits)
+        hist, ent = ndq.ndq_code_entropy(bufs.codes[w], n, bits)
+        assert np.array_equal(hist.cpu().numpy().astype(np.uint64), ref_h)
+        assert abs(float(ent.item()) - oracle.entropy_bits(ref_h)) <= 1e-9
+        assert float(ent.item()) <= bits
