@@ -176,6 +176,21 @@ typedef struct {
 int ndq_decode_chain(const ndq_worker* workers, uint32_t W, size_t n, uint32_t bucket,
                      float scale, float* out, void* stream);
 
+/* Dense base-L stream.  Table 1 (Sec. 4) counts log2(L) bits per index (1.585 for
+ * three levels); the fixed-width stream spends ceil(log2 L).  The dense stream
+ * stores k = ndq_dense_group(L) = max{k : L^k <= 2^32} indices per 32-bit word as
+ * the number sum_j c_j L^j (first index = lowest digit; the last group is
+ * filled with zero digits; zero words pad the stream to ndq_dense_bytes(n, L), a
+ * multiple of 16): 1.6 bits per index for L = 3.  `levels` is L of a DQSG worker
+ * or M of a nested one; every index must be < levels.
+ * ndq_dense_pack:   codes (fixed-width stream, ndq_packed_bytes(n, ndq_code_bits(
+ *                   levels)) bytes) -> dense_out (ndq_dense_bytes(n, levels) bytes)
+ * ndq_dense_unpack: the inverse; codes_out is fully written, padding zero. */
+uint32_t ndq_dense_group(uint32_t levels);
+size_t ndq_dense_bytes(size_t n, uint32_t levels);
+int ndq_dense_pack(const void* codes, size_t n, uint32_t levels, void* dense_out, void* stream);
+int ndq_dense_unpack(const void* dense, size_t n, uint32_t levels, void* codes_out, void* stream);
+
 /* Histogram and empirical entropy of a packed code stream (Sec. 4: the bits left
  * after entropy coding are reported through the entropy of the transmitted
  * indices).  hist_out: 2^bits uint64 (device, 8-byte aligned), hist_out[c] = number

@@ -92,6 +92,10 @@ def lib():
         L.oracle_dq_value_half.restype = f32
         L.oracle_dq_decode_half.argtypes = [vp, sz, u32, u32, vp, vp, i32]
         L.oracle_dq_decode_half.restype = None
+        L.oracle_dense_group.argtypes, L.oracle_dense_group.restype = [u32], u32
+        L.oracle_dense_bytes.argtypes, L.oracle_dense_bytes.restype = [sz, u32], sz
+        L.oracle_dense_pack.argtypes, L.oracle_dense_pack.restype = [vp, sz, u32, vp], None
+        L.oracle_dense_unpack.argtypes, L.oracle_dense_unpack.restype = [vp, sz, u32, vp], None
         L.oracle_code_histogram.argtypes = [vp, sz, u32, vp]
         L.oracle_code_histogram.restype = None
         L.oracle_entropy_bits.argtypes = [vp, u32]
@@ -250,6 +254,29 @@ def dq_decode_half(codes, n, levels, bucket, steps, out=None):
     assert out.dtype == np.float32 and out.size == n and out.flags.c_contiguous
     lib().oracle_dq_decode_half(_p(codes), n, levels, bucket, _p(steps), _p(out), int(acc))
     return out
+
+
+def dense_group(levels):
+    return lib().oracle_dense_group(levels)
+
+
+def dense_bytes(n, levels):
+    return lib().oracle_dense_bytes(n, levels)
+
+
+def dense_pack(codes, levels):
+    codes = np.ascontiguousarray(codes, dtype=np.uint32)
+    out = np.empty(dense_bytes(codes.size, levels), dtype=np.uint8)
+    lib().oracle_dense_pack(_p(codes), codes.size, levels, _p(out))
+    return out
+
+
+def dense_unpack(dense, n, levels):
+    dense = np.ascontiguousarray(dense, dtype=np.uint8)
+    assert dense.size >= dense_bytes(n, levels)
+    codes = np.empty(n, dtype=np.uint32)
+    lib().oracle_dense_unpack(_p(dense), n, levels, _p(codes))
+    return codes
 
 
 def code_histogram(codes, n, bits):

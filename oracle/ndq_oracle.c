@@ -203,6 +203,57 @@ void oracle_unpack(const uint8_t* in, size_t n, uint32_t bits, uint32_t* codes)
 }
 
 /* ------------------------------------------------------------------------- */
+/* Dense base-L stream.  Table 1 (Sec. 4) counts log2(L) bits per index; k      */
+/* base-L digits in a 32-bit word spend 32/k, e.g. 1.6 bits for L = 3 (k = 20). */
+/* ------------------------------------------------------------------------- */
+
+uint32_t oracle_dense_group(uint32_t levels)
+{
+    if (levels < 2u || levels > 256u) return 0u;
+    uint32_t k = 0u;
+    uint64_t power = 1u;                        /* levels^k */
+    while (power * levels <= ((uint64_t)1 << 32)) { power *= levels; ++k; }
+    return k;
+}
+
+size_t oracle_dense_bytes(size_t n, uint32_t levels)
+{
+    uint32_t k = oracle_dense_group(levels);
+    size_t words = (n + k - 1u) / k;
+    return (words * 4u + 15u) / 16u * 16u;
+}
+
+void oracle_dense_pack(const uint32_t* codes, size_t n, uint32_t levels, uint8_t* out)
+{
+    uint32_t k = oracle_dense_group(levels);
+    size_t bytes = oracle_dense_bytes(n, levels);
+    memset(out, 0, bytes);
+    size_t words = (n + k - 1u) / k;
+    for (size_t w = 0; w < words; ++w) {
+        uint64_t value = 0u, weight = 1u;
+        for (uint32_t j = 0; j < k; ++j) {
+            size_t i = w * k + j;
+            uint32_t digit = i < n ? codes[i] : 0u;
+            value += digit * weight;
+            weight *= levels;
+        }
+        for (uint32_t b = 0; b < 4u; ++b) out[4u * w + b] = (uint8_t)(value >> (8u * b));
+    }
+}
+
+void oracle_dense_unpack(const uint8_t* in, size_t n, uint32_t levels, uint32_t* codes)
+{
+    uint32_t k = oracle_dense_group(levels);
+    for (size_t i = 0; i < n; ++i) {
+        size_t w = i / k;
+        uint32_t value = (uint32_t)in[4u * w] | ((uint32_t)in[4u * w + 1u] << 8) |
+                         ((uint32_t)in[4u * w + 2u] << 16) | ((uint32_t)in[4u * w + 3u] << 24);
+        for (uint32_t j = 0; j < i % k; ++j) value /= levels;
+        codes[i] = value % levels;
+    }
+}
+
+/* ------------------------------------------------------------------------- */
 /* Entropy of the index stream (Sec. 4, paragraph before Table 1: adaptive      */
 /* arithmetic coding gets within a few percent of the entropy, so the entropy  */
 /* of the indices is what is reported).                                         */

@@ -89,6 +89,18 @@ size_t oracle_num_buckets(size_t n, uint32_t bucket); /* bucket==0 -> 1 */
 void oracle_pack(const uint32_t* codes, size_t n, uint32_t bits, uint8_t* out);
 void oracle_unpack(const uint8_t* in, size_t n, uint32_t bits, uint32_t* codes);
 
+/* ---- dense base-L stream (Sec. 4 Table 1 counts log2(L) bits per index, e.g.
+ * 1.585 for three levels; fixed-width codes spend ceil(log2 L)) ----
+ * k = oracle_dense_group(L) is the largest k with L^k <= 2^32; codes are taken in
+ * groups of k and each group is stored as the 32-bit number sum_j c_j L^j
+ * (little-endian words, first code = lowest digit); the last group is filled
+ * with zero digits and the stream is padded with zero words to a multiple of 16
+ * bytes. */
+uint32_t oracle_dense_group(uint32_t levels);
+size_t oracle_dense_bytes(size_t n, uint32_t levels);
+void oracle_dense_pack(const uint32_t* codes, size_t n, uint32_t levels, uint8_t* out);
+void oracle_dense_unpack(const uint8_t* in, size_t n, uint32_t levels, uint32_t* codes);
+
 /* ---- entropy of an index stream (Sec. 4: bits after entropy coding are
  * reported through the entropy of the transmitted indices) ---- */
 /* hist[c] = number of codes equal to c, c in [0, 2^bits) */

@@ -616,6 +616,80 @@ __global__ __launch_bounds__(256) void entropy_kernel(const unsigned long long* 
 }
 
 // ---------------------------------------------------------------------------
+// Dense base-L stream (Sec. 4 Table 1 counts log2 L bits per index): k indices
+// per 32-bit word as the number sum_j c_j L^j.  Transcoders between the
+// fixed-width stream and the dense one.  A thread owns 8 dense words = 8k
+// indices = k*bits whole bytes of the fixed-width stream, so no two threads
+// touch the same byte.
+// ---------------------------------------------------------------------------
+struct DenseArgs {
+    unsigned char* fixed;     // fixed-width stream (read by pack, written by unpack)
+    uint32_t* dense;          // dense stream (written by pack, read by unpack)
+    uint64_t n;               // indices
+    uint64_t fixed_valid;     // ceil(n*bits/8): bytes of the fixed stream that hold indices
+    uint64_t fixed_total;     // its padded size
+    uint64_t dense_valid;     // ceil(n/k) words that hold indices
+    uint64_t dense_total;     // padded size in words
+    uint32_t levels, k, bits;
+};
+
+__global__ __launch_bounds__(256) void dense_pack_kernel(DenseArgs a)
+{
+    const uint64_t t = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const uint64_t w0 = t * 8u;
+    if (w0 >= a.dense_total) return;
+    uint64_t byte = t * a.k * a.bits;
+    const uint32_t mask = (1u << a.bits) - 1u;
+    uint32_t buf = 0u, have = 0u;
+    for (uint32_t j = 0; j < 8u; ++j) {
+        const uint64_t w = w0 + j;
+        if (w >= a.dense_total) break;
+        uint64_t value = 0u, weight = 1u;
+        for (uint32_t d = 0; d < a.k; ++d) {
+            if (have < a.bits) {
+                const uint32_t b = byte < a.fixed_valid ? a.fixed[byte] : 0u;
+                ++byte;
+                buf |= b << have;
+                have += 8u;
+            }
+            uint32_t c = buf & mask;
+            buf >>= a.bits;
+            have -= a.bits;
+            if (w * a.k + d >= a.n) c = 0u;
+            value += c * weight;
+            weight *= a.levels;
+        }
+        a.dense[w] = (uint32_t)value;
+    }
+}
+
+__global__ __launch_bounds__(256) void dense_unpack_kernel(DenseArgs a)
+{
+    const uint64_t t = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    uint64_t byte = t * a.k * a.bits;
+    if (byte >= a.fixed_total) return;
+    const uint64_t w0 = t * 8u;
+    uint32_t buf = 0u, have = 0u;
+    for (uint32_t j = 0; j < 8u; ++j) {
+        const uint64_t w = w0 + j;
+        uint32_t value = w < a.dense_valid ? a.dense[w] : 0u;
+        for (uint32_t d = 0; d < a.k; ++d) {
+            uint32_t c = value % a.levels;
+            value /= a.levels;
+            if (w * a.k + d >= a.n) c = 0u;
+            buf |= c << have;
+            have += a.bits;
+            if (have >= 8u) {
+                if (byte < a.fixed_total) a.fixed[byte] = (unsigned char)buf;
+                ++byte;
+                buf >>= 8;
+                have -= 8u;
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
 // Host side: validation and dispatch
 // ---------------------------------------------------------------------------
 static uint32_t code_bits(uint32_t x)
@@ -1015,6 +1089,63 @@ int ndq_code_entropy(const void* codes, size_t n, uint32_t bits, uint64_t* hist_
         if (launched() != NDQ_OK) return NDQ_ELAUNCH;
     }
     return NDQ_OK;
+}
+
+uint32_t ndq_dense_group(uint32_t levels)
+{
+    if (levels < 2u || levels > 256u) return 0u;
+    uint32_t k = 0u;
+    uint64_t power = 1u;
+    while (power * levels <= ((uint64_t)1 << 32)) { power *= levels; ++k; }
+    return k;
+}
+
+size_t ndq_dense_bytes(size_t n, uint32_t levels)
+{
+    const uint32_t k = ndq_dense_group(levels);
+    if (!k) return 0u;
+    const size_t words = (n + k - 1u) / k;
+    return (words * 4u + 15u) / 16u * 16u;
+}
+
+static int dense_common(const void* fixed, const void* dense, size_t n, uint32_t levels, bool pack,
+                        void* stream)
+{
+    using namespace ndq;
+    DenseArgs a;
+    a.k = ndq_dense_group(levels);
+    if (!a.k) return NDQ_EINVAL;
+    if (n == 0) return NDQ_OK;
+    if (!fixed || !dense) return NDQ_EINVAL;
+    if (n >= kMaxN) return NDQ_EUNSUPPORTED;
+    if (!aligned16(fixed) || !aligned16(dense)) return NDQ_EALIGN;
+    a.fixed = (unsigned char*)fixed;
+    a.dense = (uint32_t*)dense;
+    a.n = n;
+    a.levels = levels;
+    a.bits = code_bits(levels);
+    a.fixed_valid = ((uint64_t)n * a.bits + 7u) / 8u;
+    a.fixed_total = packed_bytes(n, a.bits);
+    a.dense_valid = ((uint64_t)n + a.k - 1u) / a.k;
+    a.dense_total = ndq_dense_bytes(n, levels) / 4u;
+    const uint64_t per_thread_bytes = (uint64_t)a.k * a.bits;
+    const uint64_t threads = pack ? (a.dense_total + 7u) / 8u
+                                  : (a.fixed_total + per_thread_bytes - 1u) / per_thread_bytes;
+    const uint64_t blocks = (threads + 255u) / 256u;
+    if (blocks >= ((uint64_t)1 << 31)) return NDQ_EUNSUPPORTED;
+    if (pack) hipLaunchKernelGGL(dense_pack_kernel, dim3((uint32_t)blocks), dim3(256), 0, (hipStream_t)stream, a);
+    else hipLaunchKernelGGL(dense_unpack_kernel, dim3((uint32_t)blocks), dim3(256), 0, (hipStream_t)stream, a);
+    return launched();
+}
+
+int ndq_dense_pack(const void* codes, size_t n, uint32_t levels, void* dense_out, void* stream)
+{
+    return dense_common(codes, dense_out, n, levels, true, stream);
+}
+
+int ndq_dense_unpack(const void* dense, size_t n, uint32_t levels, void* codes_out, void* stream)
+{
+    return dense_common(codes_out, dense, n, levels, false, stream);
 }
 
 const char* ndq_strerror(int rc)

@@ -19,7 +19,8 @@ NDQ_OK, NDQ_EINVAL, NDQ_EALIGN, NDQ_EUNSUPPORTED, NDQ_ELAUNCH = 0, -1, -2, -3, -
 
 EXPORTS = ("ndq_code_bits", "ndq_packed_bytes", "ndq_num_buckets", "ndq_absmax", "ndq_dq_encode",
            "ndq_dq_decode", "ndq_dq_decode_half", "ndq_nested_encode", "ndq_nested_decode", "ndq_aggregate",
-           "ndq_decode_chain", "ndq_code_entropy", "ndq_strerror")
+           "ndq_decode_chain", "ndq_code_entropy", "ndq_dense_group", "ndq_dense_bytes",
+           "ndq_dense_pack", "ndq_dense_unpack", "ndq_strerror")
 
 
 class ndq_dither(C.Structure):
@@ -74,6 +75,10 @@ def lib():
         L.ndq_aggregate.argtypes, L.ndq_aggregate.restype = [vp, u32, sz, f32, vp, vp], ci
         L.ndq_decode_chain.argtypes = [C.POINTER(ndq_worker), u32, sz, u32, f32, vp, vp]
         L.ndq_decode_chain.restype = ci
+        L.ndq_dense_group.argtypes, L.ndq_dense_group.restype = [u32], u32
+        L.ndq_dense_bytes.argtypes, L.ndq_dense_bytes.restype = [sz, u32], sz
+        L.ndq_dense_pack.argtypes, L.ndq_dense_pack.restype = [vp, sz, u32, vp, vp], ci
+        L.ndq_dense_unpack.argtypes, L.ndq_dense_unpack.restype = [vp, sz, u32, vp, vp], ci
         L.ndq_code_entropy.argtypes, L.ndq_code_entropy.restype = [vp, sz, u32, vp, vp, vp], ci
         L.ndq_strerror.argtypes, L.ndq_strerror.restype = [ci], C.c_char_p
         _lib = L
@@ -240,3 +245,34 @@ def ndq_code_entropy(codes, n, bits, hist_out=None, entropy_out=None):
     _check(lib().ndq_code_entropy(cptr, n, bits, _dev(hist_out, "hist_out"),
                                   _dev(entropy_out, "entropy_out"), _stream()), "ndq_code_entropy")
     return hist_out, entropy_out
+
+
+def ndq_dense_group(levels):
+    return lib().ndq_dense_group(levels)
+
+
+def ndq_dense_bytes(n, levels):
+    return lib().ndq_dense_bytes(n, levels)
+
+
+def ndq_dense_pack(codes, n, levels, dense_out=None):
+    if dense_out is None:
+        dense_out = torch.empty(ndq_dense_bytes(n, levels), dtype=torch.uint8, device=codes.device)
+    if dense_out.numel() * dense_out.element_size() < ndq_dense_bytes(n, levels):
+        raise ValueError("dense_out too small")
+    if n:
+        _check(lib().ndq_dense_pack(_dev(codes, "codes"), n, levels, _dev(dense_out, "dense_out"),
+                                    _stream()), "ndq_dense_pack")
+    return dense_out
+
+
+def ndq_dense_unpack(dense, n, levels, codes_out=None):
+    nbytes = ndq_packed_bytes(n, ndq_code_bits(levels))
+    if codes_out is None:
+        codes_out = torch.empty(nbytes, dtype=torch.uint8, device=dense.device)
+    if codes_out.numel() * codes_out.element_size() < nbytes:
+        raise ValueError("codes_out too small")
+    if n:
+        _check(lib().ndq_dense_unpack(_dev(dense, "dense"), n, levels, _dev(codes_out, "codes_out"),
+                                      _stream()), "ndq_dense_unpack")
+    return codes_out

@@ -537,3 +537,42 @@ def test_entropy_of_the_benchmark_code_streams():
         assert np.array_equal(hist.cpu().numpy().astype(np.uint64), ref_h)
         assert abs(float(ent.item()) - oracle.entropy_bits(ref_h)) <= 1e-9
         assert float(ent.item()) <= bits
+
+
+# --------------------------------------------------------------------------
+# dense base-L stream
+# --------------------------------------------------------------------------
+
+@pytest.mark.parametrize("levels", [2, 3, 4, 5, 6, 7, 9, 16, 17, 100, 255, 256])
+def test_dense_stream_matches_oracle(levels):
+    dev = _gpu()
+    bits = oracle.code_bits(levels)
+    k = oracle.dense_group(levels)
+    assert ndq.ndq_dense_group(levels) == k
+    for n in (1, k - 1, k, k + 1, 8 * k, 8 * k + 1, 1000, 65536 + 5, 1000003):
+        rng = np.random.default_rng(n + levels)
+        codes = rng.integers(0, levels, n).astype(np.uint32)
+        codes[:min(n, k)] = levels - 1
+        fixed = oracle.pack(codes, bits)
+        ref = oracle.dense_pack(codes, levels)
+        assert ndq.ndq_dense_bytes(n, levels) == ref.size
+        fixed_d = torch.from_numpy(fixed).to(dev)
+        dense = ndq.ndq_dense_pack(fixed_d, n, levels)
+        assert dense.cpu().numpy().tobytes() == ref.tobytes(), (levels, n)
+        back = torch.full((fixed.size,), 0xAB, dtype=torch.uint8, device=dev)
+        ndq.ndq_dense_unpack(dense, n, levels, back)
+        assert back.cpu().numpy().tobytes() == fixed.tobytes(), (levels, n)
+
+
+def test_three_level_gradient_in_dense_form():
+    """The paper's three-level DQSG message at 1.6 bits per index: encode, make
+    dense, expand, decode -- same reconstruction as without the detour."""
+    n = 266610                       # FC-300-100's parameter count (Table 1)
+    g = _make(n, "f32", seed=1)
+    d = ndq.ndq_dither(1, 0, 0, 0)
+    codes, steps = ndq.ndq_dq_encode(_to_dev(g), 0.0, 3, 0, d)
+    dense = ndq.ndq_dense_pack(codes, n, 3)
+    assert dense.numel() * 8 <= 1.0097 * n * np.log2(3) + 128 and dense.numel() < codes.numel()
+    back = ndq.ndq_dense_unpack(dense, n, 3)
+    assert torch.equal(back, codes)
+    assert torch.equal(ndq.ndq_dq_decode(back, n, 3, 0, steps, d), ndq.ndq_dq_decode(codes, n, 3, 0, steps, d))

@@ -395,6 +395,37 @@ def test_pack_unpack_identity_over_all_small_streams():
             assert np.array_equal(oracle.unpack(packed, n, bits), codes)
 
 
+def test_dense_base_L_stream():
+    """Groups of k = max{k : L^k <= 2^32} indices stored as one base-L number:
+    checked against Python's big integers, round trip for every L, no overflow
+    for the all-(L-1) group, and the bit count against Table 1's log2(L)."""
+    expect_k = {2: 32, 3: 20, 4: 16, 5: 13, 7: 11, 9: 10, 16: 8, 17: 7, 255: 4, 256: 4}
+    for L, k in expect_k.items():
+        assert oracle.dense_group(L) == k
+        assert L ** k <= 2 ** 32 < L ** (k + 1)
+    rng = np.random.default_rng(0)
+    for L in list(range(2, 20)) + [31, 100, 255, 256]:
+        k = oracle.dense_group(L)
+        for n in (0, 1, k - 1, k, k + 1, 5 * k + 3, 1000):
+            codes = rng.integers(0, L, n).astype(np.uint32)
+            if n >= k:
+                codes[:k] = L - 1                           # largest group value L^k - 1
+            dense = oracle.dense_pack(codes, L)
+            assert dense.size == oracle.dense_bytes(n, L) and dense.size % 16 == 0
+            words = np.frombuffer(dense.tobytes(), dtype="<u4")
+            for w in range((n + k - 1) // k):
+                group = [int(c) for c in codes[w * k:(w + 1) * k]]
+                assert int(words[w]) == sum(c * L ** j for j, c in enumerate(group))
+            assert np.all(words[(n + k - 1) // k:] == 0)
+            assert np.array_equal(oracle.dense_unpack(dense, n, L), codes)
+    # Table 1: 3 levels cost log2(3) = 1.585 bits per index; the dense stream spends
+    # 32/20 = 1.6 (1 % more), the fixed-width stream 2
+    n = 266610
+    dense_bits = 32 * ((n + 19) // 20)
+    assert n * math.log2(3) <= dense_bits <= 1.0096 * n * math.log2(3)
+    assert abs((dense_bits + 32 * 6) / 1000 - 422.8) < 4.1
+
+
 def test_raw_bits_accounting_matches_table_1(golden_dir):
     """Table 1 and the NDQSG paragraph of Sec. 4: bits = n log2(L) + 32 per
     scale factor (a 32-bit kappa per tensor); the fixed-width stream of this
