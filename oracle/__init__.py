@@ -74,6 +74,16 @@ def lib():
         L.oracle_coset_index.restype = C.c_int32
         L.oracle_index_value.argtypes = [C.c_int32, f32, f32]
         L.oracle_index_value.restype = f32
+        L.oracle_nested_code_alpha.argtypes = [f32, f32, f32, f32, u32]
+        L.oracle_nested_code_alpha.restype = u32
+        L.oracle_nested_value_alpha.argtypes = [u32, f32, f32, f32, f32, u32]
+        L.oracle_nested_value_alpha.restype = f32
+        L.oracle_alpha_for_equal_variance.argtypes = [C.c_double, C.c_double]
+        L.oracle_alpha_for_equal_variance.restype = C.c_double
+        L.oracle_decode_error_bound.argtypes = [C.c_double, u32, C.c_double, C.c_double]
+        L.oracle_decode_error_bound.restype = C.c_double
+        L.oracle_sqdiff_sum.argtypes = [vp, vp, sz]
+        L.oracle_sqdiff_sum.restype = C.c_double
         L.oracle_packed_bytes.argtypes = [sz, u32]
         L.oracle_packed_bytes.restype = sz
         L.oracle_num_buckets.argtypes = [sz, u32]
@@ -100,9 +110,9 @@ def lib():
         L.oracle_code_histogram.restype = None
         L.oracle_entropy_bits.argtypes = [vp, u32]
         L.oracle_entropy_bits.restype = C.c_double
-        L.oracle_nested_encode.argtypes = [vp, i32, sz, f32, u32, u32, u32, Dither, vp, vp]
+        L.oracle_nested_encode.argtypes = [vp, i32, sz, f32, u32, u32, f32, u32, Dither, vp, vp]
         L.oracle_nested_encode.restype = None
-        L.oracle_nested_decode.argtypes = [vp, sz, u32, u32, vp, Dither, vp, f32, vp, i32]
+        L.oracle_nested_decode.argtypes = [vp, sz, u32, f32, u32, vp, Dither, vp, f32, vp, i32]
         L.oracle_nested_decode.restype = None
         L.oracle_aggregate.argtypes = [vp, u32, sz, f32, vp]
         L.oracle_aggregate.restype = None
@@ -184,6 +194,29 @@ def coset_index(m, y, inv_delta, v, M):
 
 def index_value(q, delta, v):
     return lib().oracle_index_value(q, delta, v)
+
+
+def nested_code_alpha(g, inv_delta, alpha, v, M):
+    return lib().oracle_nested_code_alpha(g, inv_delta, alpha, v, M)
+
+
+def nested_value_alpha(m, y, delta, alpha, v, M):
+    return lib().oracle_nested_value_alpha(m, y, delta, alpha, v, M)
+
+
+def alpha_for_equal_variance(delta1, sigma_z2):
+    return lib().oracle_alpha_for_equal_variance(delta1, sigma_z2)
+
+
+def decode_error_bound(delta1, M, alpha, sigma_z2):
+    return lib().oracle_decode_error_bound(delta1, M, alpha, sigma_z2)
+
+
+def sqdiff_sum(a, b):
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    b = np.ascontiguousarray(b, dtype=np.float32)
+    assert a.size == b.size
+    return lib().oracle_sqdiff_sum(_p(a), _p(b), a.size)
 
 
 def packed_bytes(n, bits):
@@ -291,16 +324,16 @@ def entropy_bits(hist):
     return lib().oracle_entropy_bits(_p(hist), hist.size)
 
 
-def nested_encode(g, delta, levels, M, bucket, d):
+def nested_encode(g, delta, levels, M, bucket, d, alpha=1.0):
     g = np.ascontiguousarray(g)
     codes = np.empty(packed_bytes(g.size, code_bits(M)), dtype=np.uint8)
     steps = np.empty(num_buckets(g.size, bucket), dtype=np.float32)
-    lib().oracle_nested_encode(_p(g), _dtype_of(g), g.size, delta, levels, M, bucket, d,
-                               _p(codes), _p(steps))
+    lib().oracle_nested_encode(_p(g), _dtype_of(g), g.size, delta, levels, M, np.float32(alpha),
+                               bucket, d, _p(codes), _p(steps))
     return codes, steps
 
 
-def nested_decode(codes, n, M, bucket, steps, d, side, side_scale=1.0, out=None):
+def nested_decode(codes, n, M, bucket, steps, d, side, side_scale=1.0, out=None, alpha=1.0):
     codes = np.ascontiguousarray(codes, dtype=np.uint8)
     steps = np.ascontiguousarray(steps, dtype=np.float32)
     side = np.ascontiguousarray(side, dtype=np.float32)
@@ -308,7 +341,7 @@ def nested_decode(codes, n, M, bucket, steps, d, side, side_scale=1.0, out=None)
     if out is None:
         out = np.empty(n, dtype=np.float32)
     assert out.dtype == np.float32 and out.size == n and out.flags.c_contiguous
-    lib().oracle_nested_decode(_p(codes), n, M, bucket, _p(steps), d, _p(side),
+    lib().oracle_nested_decode(_p(codes), n, M, np.float32(alpha), bucket, _p(steps), d, _p(side),
                                np.float32(side_scale), _p(out), int(acc))
     return out
 

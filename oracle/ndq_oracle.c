@@ -165,6 +165,53 @@ int32_t oracle_coset_index(uint32_t m, float y, float inv_delta, float v, uint32
 }
 
 /* ------------------------------------------------------------------------- */
+/* Shrinkage factor alpha (Sec. 3.2 eqs. (7)-(8), Thm 4)                        */
+/* ------------------------------------------------------------------------- */
+
+uint32_t oracle_nested_code_alpha(float g, float inv_delta, float alpha, float v, uint32_t M)
+{
+    /* t = alpha*x + u in units of Delta_1: g * (alpha/Delta_1) + v.  The factor
+     * alpha/Delta_1 is formed once (one rounding); with alpha = 1 it is 1/Delta_1. */
+    float a = alpha * inv_delta;
+    return oracle_nested_code(g, a, v, M);
+}
+
+float oracle_nested_value_alpha(uint32_t m, float y, float delta, float alpha, float v, uint32_t M)
+{
+    /* r - Q2(r) = Delta_1*(q^ - v) - alpha*y with q^ = m + M*k the coset point
+     * nearest to alpha*y/Delta_1 + v, hence
+     *   x^ = y + alpha*(r - Q2(r)) = (1 - alpha^2)*y + alpha*Delta_1*(q^ - v). */
+    float a = alpha * oracle_inv_step(delta);
+    int32_t q = oracle_coset_index(m, y, a, v, M);
+    float lattice = oracle_index_value(q, delta, v);
+    float beta = (float)(1.0 - (double)alpha * (double)alpha);
+    float scaled = alpha * lattice;
+    return fmaf(beta, y, scaled);
+}
+
+double oracle_alpha_for_equal_variance(double delta1, double sigma_z2)
+{
+    double arg = 1.0 - delta1 * delta1 / (12.0 * sigma_z2);
+    return arg > 0.0 ? sqrt(arg) : 0.0;
+}
+
+double oracle_decode_error_bound(double delta1, uint32_t M, double alpha, double sigma_z2)
+{
+    double delta2 = (double)M * delta1;
+    return delta1 * delta1 / (3.0 * delta2 * delta2) + 4.0 * alpha * alpha * sigma_z2 / (delta2 * delta2);
+}
+
+double oracle_sqdiff_sum(const float* a, const float* b, size_t n)
+{
+    double acc = 0.0;
+    for (size_t i = 0; i < n; ++i) {
+        double d = (double)a[i] - (double)b[i];
+        acc += d * d;
+    }
+    return acc;
+}
+
+/* ------------------------------------------------------------------------- */
 /* Bitstream: fixed-width codes, least-significant bit first.                  */
 /* ------------------------------------------------------------------------- */
 
@@ -373,8 +420,8 @@ void oracle_dq_decode_half(const uint8_t* codes, size_t n, uint32_t levels, uint
 }
 
 void oracle_nested_encode(const void* g, int dtype, size_t n, float delta, uint32_t levels,
-                          uint32_t M, uint32_t bucket, oracle_dither d, uint8_t* codes_out,
-                          float* steps_out)
+                          uint32_t M, float alpha, uint32_t bucket, oracle_dither d,
+                          uint8_t* codes_out, float* steps_out)
 {
     uint32_t bits = oracle_code_bits(M);
     make_steps(g, dtype, n, delta, levels, bucket, steps_out);
@@ -382,14 +429,14 @@ void oracle_nested_encode(const void* g, int dtype, size_t n, float delta, uint3
     for (size_t i = 0; i < n; ++i) {
         float inv = oracle_inv_step(steps_out[bucket_of(i, bucket)]);
         float v = oracle_unit_dither(d.seed, d.step, d.worker, d.offset + i);
-        m[i] = oracle_nested_code(load_elem(g, dtype, i), inv, v, M);
+        m[i] = oracle_nested_code_alpha(load_elem(g, dtype, i), inv, alpha, v, M);
     }
     oracle_pack(m, n, bits, codes_out);
     free(m);
 }
 
-void oracle_nested_decode(const uint8_t* codes, size_t n, uint32_t M, uint32_t bucket,
-                          const float* steps, oracle_dither d, const float* side,
+void oracle_nested_decode(const uint8_t* codes, size_t n, uint32_t M, float alpha,
+                          uint32_t bucket, const float* steps, oracle_dither d, const float* side,
                           float side_scale, float* out, int accumulate)
 {
     uint32_t bits = oracle_code_bits(M);
@@ -397,11 +444,9 @@ void oracle_nested_decode(const uint8_t* codes, size_t n, uint32_t M, uint32_t b
     oracle_unpack(codes, n, bits, m);
     for (size_t i = 0; i < n; ++i) {
         float step = steps[bucket_of(i, bucket)];
-        float inv = oracle_inv_step(step);
         float v = oracle_unit_dither(d.seed, d.step, d.worker, d.offset + i);
         float y = side[i] * side_scale; /* running sum times 1/count = running mean */
-        int32_t q = oracle_coset_index(m[i], y, inv, v, M);
-        float value = oracle_index_value(q, step, v);
+        float value = oracle_nested_value_alpha(m[i], y, step, alpha, v, M);
         out[i] = accumulate ? out[i] + value : value;
     }
     free(m);

@@ -82,6 +82,25 @@ uint32_t oracle_nested_code(float g, float inv_delta, float v, uint32_t M);
 int32_t oracle_coset_index(uint32_t m, float y, float inv_delta, float v, uint32_t M);
 float oracle_index_value(int32_t q, float delta, float v);
 
+/* eqs. (7)-(8) with a shrinkage factor 0 < alpha <= 1 (Sec. 3.2; Thm 4):
+ *   encoder  t = alpha*x + u, transmitted residue = round(t/Delta_1) mod M
+ *   decoder  r = s - u - alpha*y,  x^ = y + alpha*(r - Q2(r))
+ *            = (1 - alpha^2)*y + alpha*Delta_1*(q^ - v),
+ *   q^ the integer congruent to the residue nearest to alpha*y/Delta_1 + v.
+ * alpha = 1 gives oracle_nested_code / oracle_coset_index / oracle_index_value
+ * bit for bit. */
+uint32_t oracle_nested_code_alpha(float g, float inv_delta, float alpha, float v, uint32_t M);
+float oracle_nested_value_alpha(uint32_t m, float y, float delta, float alpha, float v, uint32_t M);
+
+/* Thm 4 / last paragraph of Sec. 3.2: the shrinkage that gives NDQSG the
+ * variance Delta_1^2/12 of DQSG, alpha = sqrt(1 - Delta_1^2/(12 sigma_z^2))
+ * (0 if the argument is not positive), and the bound on the probability of a
+ * coset decode error, Delta_1^2/(3 Delta_2^2) + 4 alpha^2 sigma_z^2/Delta_2^2. */
+double oracle_alpha_for_equal_variance(double delta1, double sigma_z2);
+double oracle_decode_error_bound(double delta1, uint32_t M, double alpha, double sigma_z2);
+/* sigma_z^2 estimate: sum_i (a_i - b_i)^2 in binary64 (divide by n for the mean) */
+double oracle_sqdiff_sum(const float* a, const float* b, size_t n);
+
 /* ---- bitstream ---- */
 size_t oracle_packed_bytes(size_t n, uint32_t bits); /* ceil(n*bits/8) rounded up to 16 */
 size_t oracle_num_buckets(size_t n, uint32_t bucket); /* bucket==0 -> 1 */
@@ -136,12 +155,12 @@ void oracle_dq_decode_half(const uint8_t* codes, size_t n, uint32_t levels, uint
 
 /* Worker side of Alg. 2 for p in P2.  `levels` only sets the fine step. */
 void oracle_nested_encode(const void* g, int dtype, size_t n, float delta, uint32_t levels,
-                          uint32_t M, uint32_t bucket, oracle_dither d, uint8_t* codes_out,
-                          float* steps_out);
+                          uint32_t M, float alpha, uint32_t bucket, oracle_dither d,
+                          uint8_t* codes_out, float* steps_out);
 
 /* Server side of Alg. 2 for p in P2; side information y_i = side[i]*side_scale. */
-void oracle_nested_decode(const uint8_t* codes, size_t n, uint32_t M, uint32_t bucket,
-                          const float* steps, oracle_dither d, const float* side,
+void oracle_nested_decode(const uint8_t* codes, size_t n, uint32_t M, float alpha,
+                          uint32_t bucket, const float* steps, oracle_dither d, const float* side,
                           float side_scale, float* out, int accumulate);
 
 /* Alg. 1 server: out_i = scale * sum_w gs[w][i], w ascending. */

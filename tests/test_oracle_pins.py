@@ -641,6 +641,117 @@ def test_decode_error_rate_matches_theorem_4(M, sigma_over_delta):
     assert np.all(jumps != 0) and np.all(np.abs(err[wrong] - jumps * M) <= 0.5 + 1e-4)
 
 
+def _paper_nested_alpha(x, u, y, d1, M, alpha):
+    """eqs. (7)-(8) as printed, with the shrinkage factor, in binary64."""
+    d2 = M * d1
+    q1 = lambda t: d1 * np.round(t / d1)
+    q2 = lambda t: d2 * np.round(t / d2)
+    t = alpha * x + u
+    s = q1(t) - q2(t)
+    r = s - u - alpha * y
+    return s, y + alpha * (r - q2(r))
+
+
+@pytest.mark.parametrize("M,alpha", [(3, 0.9), (4, 0.75), (2, 0.97), (5, 0.5)])
+def test_shrinkage_form_equals_the_printed_equations(M, alpha):
+    """(1 - alpha^2) y + alpha Delta_1 (q^ - v) with q^ found by the coset search on
+    alpha*y/Delta_1 + v is eq. (8) applied to eq. (7)'s message, for alpha < 1."""
+    rng = np.random.default_rng(M)
+    d1 = 0.25
+    inv = oracle.inv_step(F(d1))
+    checked = 0
+    for _ in range(3000):
+        x = F(rng.uniform(-3, 3))
+        y = F(x + rng.normal(0, 0.3))
+        v = F((rng.integers(0, 1 << 16) + 0.5) / 2.0 ** 16 - 0.5)
+        u = float(v) * d1
+        t = (alpha * float(x) + u) / d1
+        s, xhat = _paper_nested_alpha(float(x), u, float(y), d1, M, alpha)
+        r_over = (s - u - alpha * float(y)) / (M * d1)
+        if min(abs(t - math.floor(t) - 0.5), abs(t / M - math.floor(t / M) - 0.5),
+               abs(r_over - math.floor(r_over) - 0.5)) < 1e-4:
+            continue
+        m = oracle.nested_code_alpha(x, inv, F(alpha), v, M)
+        assert (round(s / d1) - m) % M == 0
+        got = oracle.nested_value_alpha(m, y, F(d1), F(alpha), v, M)
+        assert abs(got - xhat) < 2e-5
+        checked += 1
+    assert checked > 2500
+
+
+def test_alpha_one_is_the_plain_nested_quantizer_bit_for_bit():
+    rng = np.random.default_rng(1)
+    delta = F(0.37)
+    inv = oracle.inv_step(delta)
+    for _ in range(2000):
+        x, y = F(rng.normal(0, 2)), F(rng.normal(0, 2))
+        v = F((rng.integers(0, 1 << 16) + 0.5) / 2.0 ** 16 - 0.5)
+        for M in (2, 3, 4):
+            m = oracle.nested_code(x, inv, v, M)
+            assert oracle.nested_code_alpha(x, inv, F(1.0), v, M) == m
+            plain = oracle.index_value(oracle.coset_index(m, y, inv, v, M), delta, v)
+            assert oracle.nested_value_alpha(m, y, delta, F(1.0), v, M) == plain
+
+
+@pytest.mark.parametrize("alpha_kind", ["equal_variance", "half"])
+def test_theorem_4_mse_with_shrinkage(alpha_kind):
+    """Thm 4: without decode errors E(g~ - g)^2 = alpha^2 Delta_1^2/12 + (1 - alpha^2)^2
+    sigma_z^2; with alpha = sqrt(1 - Delta_1^2/(12 sigma_z^2)) this is Delta_1^2/12,
+    the variance of DQSG with the same step (last paragraph of Sec. 3.2)."""
+    n, M = 1 << 20, 64                         # M large: no decode errors
+    rng = np.random.default_rng(23)
+    delta = 0.01
+    sigma_z = 0.8 * delta
+    y = (rng.standard_normal(n) * 0.05).astype(F)
+    z = rng.standard_normal(n) * sigma_z
+    g = (y + z).astype(F)
+    alpha = oracle.alpha_for_equal_variance(delta, sigma_z ** 2) if alpha_kind == "equal_variance" else 0.5
+    if alpha_kind == "equal_variance":
+        assert abs(alpha - math.sqrt(1 - delta ** 2 / (12 * sigma_z ** 2))) < 1e-15
+    d = oracle.dither(4, 4, 1)
+    codes, steps = oracle.nested_encode(g, F(delta), 16, M, 0, d, alpha=alpha)
+    ghat = oracle.nested_decode(codes, n, M, 0, steps, d, y, 1.0, alpha=alpha)
+    mse = np.mean((ghat.astype(np.float64) - g) ** 2)
+    zvar = np.mean((g.astype(np.float64) - y) ** 2)
+    expect = alpha ** 2 * float(steps[0]) ** 2 / 12 + (1 - alpha ** 2) ** 2 * zvar
+    assert abs(mse / expect - 1) < 0.01
+    if alpha_kind == "equal_variance":
+        assert abs(mse / (float(steps[0]) ** 2 / 12) - 1) < 0.01
+    assert abs(oracle.sqdiff_sum(g, y) / n - zvar) < 1e-12 * zvar + 1e-18
+
+
+def test_shrinkage_lowers_the_decode_error_rate_as_theorem_4_says():
+    """Thm 4: p = Pr(|alpha z + u| > Delta_2/2) <= Delta_1^2/(3 Delta_2^2) + 4 alpha^2
+    sigma_z^2/Delta_2^2: a smaller alpha makes coset errors rarer."""
+    n, M = 1 << 19, 3
+    rng = np.random.default_rng(3)
+    delta = 0.01
+    sigma = 0.9 * delta
+    y = (rng.standard_normal(n) * 0.05).astype(F)
+    g = (y + rng.standard_normal(n) * sigma).astype(F)
+    d = oracle.dither(9, 1, 2)
+    rates = []
+    for alpha in (1.0, 0.7):
+        codes, steps = oracle.nested_encode(g, F(delta), 16, M, 0, d, alpha=alpha)
+        ghat = oracle.nested_decode(codes, n, M, 0, steps, d, y, 1.0, alpha=alpha)
+        # without a decode error |g~ - g| <= alpha Delta/2 + (1 - alpha^2)|z|; an error adds
+        # a multiple of alpha * Delta_2
+        resid = (ghat.astype(np.float64) - g) - (1 - alpha ** 2) * (y.astype(np.float64) - g)
+        wrong = np.abs(resid) > alpha * float(steps[0]) * (0.5 + 1e-3)
+        d1, d2 = float(steps[0]), M * float(steps[0])
+        p_exact = integrate.quad(
+            lambda u: (stats.norm.sf((d2 / 2 - u) / (alpha * sigma))
+                       + stats.norm.sf((d2 / 2 + u) / (alpha * sigma))) / d1, -d1 / 2, d1 / 2)[0]
+        assert wrong.mean() <= oracle.decode_error_bound(d1, M, alpha, sigma ** 2)
+        assert abs(wrong.mean() - p_exact) < 5 * math.sqrt(p_exact / n) + 2e-5
+        jumps = resid[wrong] / (alpha * d2)
+        assert np.all(np.abs(jumps - np.round(jumps)) < 0.5 / M + 1e-3) and np.all(np.round(jumps) != 0)
+        rates.append(wrong.mean())
+    assert rates[1] < 0.5 * rates[0]
+    assert abs(oracle.decode_error_bound(0.01, 3, 1.0, 0.0) - 1 / 27) < 1e-15
+    assert abs(oracle.decode_error_bound(1.0, 2, 0.5, 0.25) - (1 / 12 + 0.0625)) < 1e-15
+
+
 def test_nested_side_scale_and_accumulate_implement_the_running_mean():
     """Algorithm 2 server loop: the side information is the mean of the
     gradients decoded so far; keeping their running sum S and passing
