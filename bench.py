@@ -173,12 +173,12 @@ def main():
         else:
             enc_key, enc = "nested_encode_%s_b%d" % (wl.dtype, bits), (
                 lambda w=w, arg=arg: ndq.ndq_nested_encode(dev[w], preset, wl.fine_levels, arg,
-                                                           wl.bucket, ds[w], bufs.codes[w],
+                                                           1.0, wl.bucket, ds[w], bufs.codes[w],
                                                            bufs.steps[w]))
             dkind = "nested_decode"
             dec_key, dec = "nested_decode_inplace_b%d" % bits, (
                 lambda w=w, arg=arg, c=count: ndq.ndq_nested_decode(
-                    bufs.codes[w], n, arg, wl.bucket, bufs.steps[w], ds[w], bufs.total, 1.0 / c,
+                    bufs.codes[w], n, arg, 1.0, wl.bucket, bufs.steps[w], ds[w], bufs.total, 1.0 / c,
                     bufs.total, True))
         count += 1
         chain_bytes += (n * bits + 7) // 8 + 4 * K

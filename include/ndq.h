@@ -41,11 +41,12 @@
  *                 code c_i = q_i + L/2 (integer division).
  *   DQSG value    g~_i = Delta_b * ((float)q_i - v_i)         (Algorithm 1, server)
  *   nested code   m_i = rint(fma(g_i, 1/Delta_b, v_i)) mod M, in [0, M)
- *                 (eq. (7) with alpha = 1 and Delta_2 = M Delta_1: the position of
- *                 the fine bin relative to the coarse one)
+ *                 (eq. (7) with Delta_2 = M Delta_1: the position of the fine bin
+ *                 relative to the coarse one; shown for alpha = 1)
  *   nested value  y_i = side_i * side_scale; k = rint((fma(y_i, 1/Delta_b, v_i) - m_i)/M);
  *                 q^_i = m_i + M k; g~_i = Delta_b * ((float)q^_i - v_i)
- *                 (eq. (8) with alpha = 1: the point of the coset nearest to y_i)
+ *                 (eq. (8): the point of the coset nearest to y_i; shown for alpha = 1,
+ *                 see ndq_nested_decode for a shrinkage factor alpha < 1)
  *   bitstream     code i occupies stream bits [i b, (i+1) b), b = ndq_code_bits(L or M);
  *                 stream bit k is bit (k mod 8) of byte k/8; the stream is padded
  *                 with zero bits to ndq_packed_bytes(n, b) bytes.
@@ -125,23 +126,48 @@ int ndq_dq_decode(const void* codes, size_t n, uint32_t levels, uint32_t bucket,
 int ndq_dq_decode_half(const void* codes, size_t n, uint32_t levels, uint32_t bucket,
                        const float* steps, float* out, int accumulate, void* stream);
 
-/* Worker side of Algorithm 2 for a worker of group P2 (eq. (7), alpha = 1): the
- * fine index modulo M.  The step is chosen exactly as in ndq_dq_encode
- * (`levels` only fixes the fine step; it does not clip).
+/* Worker side of Algorithm 2 for a worker of group P2 (eq. (7)): the fine index of
+ * t = alpha*g + u, modulo M.  The step is chosen exactly as in ndq_dq_encode
+ * (`levels` only fixes the fine step; it does not clip).  alpha in (0, 1] is the
+ * shrinkage factor of Sec. 3.2 (1 = plain nested quantization); the index is
+ * rint(fma(g_i, a, v_i)) with a = alpha * (1/Delta_b) formed once per bucket.
  * codes_out: ndq_packed_bytes(n, ndq_code_bits(M)) bytes. */
 int ndq_nested_encode(const void* g, ndq_dtype dt, size_t n, float delta, uint32_t levels,
-                      uint32_t M, uint32_t bucket, const ndq_dither* d, void* codes_out,
-                      float* steps_out, void* stream);
+                      uint32_t M, float alpha, uint32_t bucket, const ndq_dither* d,
+                      void* codes_out, float* steps_out, void* stream);
 
-/* Server side of Algorithm 2 for a worker of group P2 (eq. (8), alpha = 1).
+/* Server side of Algorithm 2 for a worker of group P2 (eq. (8)).
  * The side information is y_i = side[i] * side_scale, so `side` may be the
  * running SUM of the gradients decoded so far and side_scale = 1/count (the
- * "update the mean" step of Algorithm 2).  accumulate as in ndq_dq_decode; out
- * may be the same buffer as side (in-place update of the running sum), but
- * must not overlap it otherwise. */
-int ndq_nested_decode(const void* codes, size_t n, uint32_t M, uint32_t bucket,
+ * "update the mean" step of Algorithm 2).  With the encoder's alpha:
+ *   q^_i = m_i + M rint((fma(y_i, a, v_i) - m_i)/M),  a = alpha * (1/Delta_b)
+ *   g~_i = Delta_b ((float)q^_i - v_i)                                 if alpha == 1
+ *   g~_i = fma(1 - alpha^2, y_i, alpha * (Delta_b ((float)q^_i - v_i)))  otherwise
+ * (eq. (8): y + alpha (r - Q2(r)); 1 - alpha^2 is formed in binary64 and rounded).
+ * accumulate as in ndq_dq_decode; out may be the same buffer as side (in-place
+ * update of the running sum), but must not overlap it otherwise. */
+int ndq_nested_decode(const void* codes, size_t n, uint32_t M, float alpha, uint32_t bucket,
                       const float* steps, const ndq_dither* d, const float* side,
                       float side_scale, float* out, int accumulate, void* stream);
+
+/* Parameter selection for nested workers (Thm 4 and the last paragraph of Sec. 3.2);
+ * plain host arithmetic.  ndq_alpha_for_equal_variance: alpha = sqrt(1 -
+ * Delta_1^2/(12 sigma_z^2)), the shrinkage that gives NDQSG the variance
+ * Delta_1^2/12 of DQSG (0 when the argument is not positive: the side
+ * information alone is already better).  ndq_decode_error_bound: Thm 4's bound
+ * Delta_1^2/(3 Delta_2^2) + 4 alpha^2 sigma_z^2/Delta_2^2 on the probability of a
+ * coset decode error, Delta_2 = M Delta_1. */
+double ndq_alpha_for_equal_variance(double delta1, double sigma_z2);
+double ndq_decode_error_bound(double delta1, uint32_t M, double alpha, double sigma_z2);
+
+/* Estimate of n*sigma_z^2 for that selection (Thm 4's model g = y + z): out[0] =
+ * sum_i (a_i - b_i)^2 in binary64, with a fixed reduction order (the same inputs
+ * give the same bits).  a, b: n floats each (device, 16-byte aligned); workspace:
+ * ndq_sqdiff_workspace() bytes of device memory (8-byte aligned) the call may
+ * overwrite; out: one double (device). */
+size_t ndq_sqdiff_workspace(void);
+int ndq_sqdiff(const float* a, const float* b, size_t n, double* workspace, double* out,
+               void* stream);
 
 /* Server side of Algorithm 1, last step: out_i = scale * sum_w gs[w][i], summed
  * in ascending w.  gs: HOST array of W device pointers (1 <= W <= 1024), each n
@@ -157,6 +183,7 @@ typedef struct {
     const float* steps;     /* ndq_num_buckets(n, bucket) floats                        */
     uint32_t kind;          /* ndq_worker_kind: group P1 (DQSG) or group P2 (nested)    */
     uint32_t levels_or_M;   /* levels for a DQSG worker, M for a nested worker          */
+    float alpha;            /* nested worker: its shrinkage factor in (0,1]; else unused */
     ndq_dither dither;
 } ndq_worker;
 
@@ -165,7 +192,7 @@ typedef struct {
  * start), for p = 0 .. W-1 in the given order:
  *     DQSG worker  : S_i <- g~_p,i if c == 0, else S_i + g~_p,i   (as ndq_dq_decode)
  *     nested worker: y_i = S_i * (1/c);  S_i <- S_i + g~_p,i      (as ndq_nested_decode
- *                    with side = out = S, side_scale = 1/c, accumulate)
+ *                    with side = out = S, side_scale = 1/c, its alpha, accumulate)
  *     c <- c + 1
  * and finally out_i = S_i if scale == 1, else scale * S_i.  Element for element
  * this is the result of the corresponding sequence of ndq_dq_decode /

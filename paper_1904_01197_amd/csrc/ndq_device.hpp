@@ -126,8 +126,8 @@ __device__ __forceinline__ float inv_step(float step)
 //   kDqNarrow     : the same for codes of at most 6 bits (encoder packs in float)
 //   kDqHalf       : decoder only: half-dithered reconstruction Delta*q, no dither
 //                   regenerated (Sec. 2.1, last paragraph; Lemma 1)
-//   kNestedPow2   : NDQSG, M a power of two (mask / exact scale) (Algorithm 2)
-//   kNestedAnyM   : NDQSG, any M in [2,256]
+//   kNestedPow2   : NDQSG, M a power of two and alpha = 1 (mask / exact scale)
+//   kNestedAnyM   : NDQSG, any M in [2,256], any shrinkage factor alpha in (0,1]
 // ---------------------------------------------------------------------------
 enum Mode { kDq = 0, kNestedPow2 = 1, kNestedAnyM = 2, kDqNarrow = 3, kDqHalf = 4 };
 
@@ -139,6 +139,7 @@ struct Quant {
     float M_f, inv_M_f;      // (float)M and, for powers of two, its exact reciprocal
     uint32_t bits;           // code width
     float pack_bias;         // kDqNarrow: -q_min * sum_k 2^(k*bits), k = 0..3 (codes of <= 6 bits)
+    float alpha, beta;       // nested: shrinkage factor and 1 - alpha^2 (kNestedAnyM when alpha < 1)
 };
 
 // Clipped index of eq. (2) / Algorithm 1, still as a float (an exact small integer).
@@ -172,6 +173,15 @@ __device__ __forceinline__ uint32_t encode_one(float g, float inv, float v, cons
 {
     if (MODE == kDq || MODE == kDqNarrow) return dq_code(g, inv, v, qp);
     return nested_code<MODE>(g, inv, v, qp);
+}
+
+// eq. (8) with a shrinkage factor: y + alpha (r - Q2(r)) = (1 - alpha^2) y + alpha * lattice
+template <int MODE>
+__device__ __forceinline__ float shrink(float lattice, float y, const Quant& qp)
+{
+    if (MODE != kNestedAnyM) return lattice;
+    const float scaled = qp.alpha * lattice;
+    return __builtin_fmaf(qp.beta, y, scaled);
 }
 
 // Reconstruction Delta * (q - v) of Algorithm 1's server step.

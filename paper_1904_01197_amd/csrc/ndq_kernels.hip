@@ -7,6 +7,8 @@
 // LDS is used only to transpose the small packed codes into stream order.
 #include <hip/hip_runtime.h>
 
+#include <math.h>
+
 #include "ndq.h"
 #include "ndq_device.hpp"
 
@@ -62,7 +64,7 @@ __device__ __forceinline__ void encode_tile(const EncodeArgs& a, const TileRef& 
     } else {
         step = a.steps[t.bucket];
     }
-    const float inv = inv_step(step);
+    const float inv = a.qp.alpha * inv_step(step);   // alpha = 1 unless a nested worker shrinks
     const uint64_t block0 = (a.index0 + t.start) >> 3;
 
 #pragma unroll
@@ -216,7 +218,7 @@ __device__ __forceinline__ void decode_tile(const DecodeArgs& a, const TileRef& 
     const float* side = a.side + t.start;
     float* out = a.out + t.start;
     const float step = a.steps[t.bucket];
-    const float inv = inv_step(step);
+    const float inv = a.qp.alpha * inv_step(step);
     const uint64_t block0 = (a.index0 + t.start) >> 2;
 
     constexpr int kDecRows = DecRows<MODE, ACC>::R;
@@ -269,14 +271,15 @@ __device__ __forceinline__ void decode_tile(const DecodeArgs& a, const TileRef& 
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
             const uint32_t c = (packed[r] >> (k * bits)) & mask;
-            float q;
+            float q, yk = 0.0f;
             if (MODE == kDq || MODE == kDqHalf) {
                 q = (float)((int32_t)c + a.qp.q_min);
             } else {
-                const float yk = ys[k] * a.side_scale;
+                yk = ys[k] * a.side_scale;
                 q = coset_index_f<MODE>(c, yk, inv, v[k], a.qp);
             }
-            const float val = (MODE == kDqHalf) ? step * q : index_value(q, step, v[k]);
+            const float val = (MODE == kDqHalf) ? step * q
+                                                : shrink<MODE>(index_value(q, step, v[k]), yk, a.qp);
             if (ACC == kStore) res[k] = val;
             else if (ACC == kAccumulate) res[k] = ps[k] + val;
             else res[k] = ys[k] + val;
@@ -321,6 +324,7 @@ struct ChainWorker {
     int32_t q_min;
     uint32_t M;
     float M_f, inv_M_f;
+    float alpha, beta;    // nested: shrinkage factor and 1 - alpha^2
     float side_scale;     // 1/(workers folded in before this one); 0 for the first
     uint32_t bits;
     uint32_t mode;        // Mode
@@ -376,9 +380,10 @@ __device__ __forceinline__ void chain_fold(const ChainWorker& cw, const ChainFet
     const uint32_t bits = cw.bits;
     const uint32_t mask = (1u << bits) - 1u;
     const float step = f.step;
-    const float inv = inv_step(step);
+    const float inv = cw.alpha * inv_step(step);
     Quant qp;
     qp.M = cw.M; qp.M_f = cw.M_f; qp.inv_M_f = cw.inv_M_f; qp.q_min = cw.q_min;
+    qp.alpha = cw.alpha; qp.beta = cw.beta;
 #pragma unroll
     for (int r = 0; r < kChainRows; ++r) {
         const uint32_t o = (uint32_t)(r * kWave + lane) * kLaneElems;
@@ -393,14 +398,14 @@ __device__ __forceinline__ void chain_fold(const ChainWorker& cw, const ChainFet
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
             const uint32_t c = (half[k >> 2] >> ((k & 3) * bits)) & mask;
-            float q;
+            float q, yk = 0.0f;
             if (MODE == kDq) {
                 q = (float)((int32_t)c + qp.q_min);
             } else {
-                const float yk = S[r][k] * cw.side_scale;
+                yk = S[r][k] * cw.side_scale;
                 q = coset_index_f<MODE>(c, yk, inv, v[k], qp);
             }
-            const float val = index_value(q, step, v[k]);
+            const float val = shrink<MODE>(index_value(q, step, v[k]), yk, qp);
             S[r][k] = (MODE == kDq && cw.first) ? val : S[r][k] + val;
         }
     }
@@ -690,6 +695,56 @@ __global__ __launch_bounds__(256) void dense_unpack_kernel(DenseArgs a)
 }
 
 // ---------------------------------------------------------------------------
+// sum_i (a_i - b_i)^2 in binary64 (the sigma_z^2 estimate behind Thm 4's parameter
+// choice).  Two passes over a fixed grid so that the reduction order, and hence
+// the result, does not depend on scheduling.
+// ---------------------------------------------------------------------------
+constexpr uint32_t kSqBlocks = 1024;
+
+__device__ __forceinline__ double block_sum_256(double x, double* sh)
+{
+    const uint32_t tid = threadIdx.x;
+    sh[tid] = x;
+    __syncthreads();
+    for (uint32_t s = 128; s >= 1; s >>= 1) {
+        if (tid < s) sh[tid] += sh[tid + s];
+        __syncthreads();
+    }
+    return sh[0];
+}
+
+__global__ __launch_bounds__(256) void sqdiff_partial_kernel(const float* __restrict__ a,
+                                                             const float* __restrict__ b, uint64_t n,
+                                                             double* partial)
+{
+    __shared__ double sh[256];
+    const uint64_t n4 = n >> 2;
+    double acc = 0.0;
+    for (uint64_t i = (uint64_t)blockIdx.x * 256u + threadIdx.x; i < n4; i += (uint64_t)kSqBlocks * 256u) {
+        const float4 x = ((const float4*)a)[i], y = ((const float4*)b)[i];
+        const double d0 = (double)x.x - (double)y.x, d1 = (double)x.y - (double)y.y;
+        const double d2 = (double)x.z - (double)y.z, d3 = (double)x.w - (double)y.w;
+        acc += d0 * d0; acc += d1 * d1; acc += d2 * d2; acc += d3 * d3;
+    }
+    if (blockIdx.x == 0 && threadIdx.x < (n & 3u)) {       // the last n mod 4 elements
+        const uint64_t i = (n4 << 2) + threadIdx.x;
+        const double d = (double)a[i] - (double)b[i];
+        acc += d * d;
+    }
+    const double total = block_sum_256(acc, sh);
+    if (threadIdx.x == 0) partial[blockIdx.x] = total;
+}
+
+__global__ __launch_bounds__(256) void sqdiff_final_kernel(const double* partial, double* out)
+{
+    __shared__ double sh[256];
+    double acc = 0.0;
+    for (uint32_t j = 0; j < kSqBlocks / 256u; ++j) acc += partial[j * 256u + threadIdx.x];
+    const double total = block_sum_256(acc, sh);
+    if (threadIdx.x == 0) out[0] = total;
+}
+
+// ---------------------------------------------------------------------------
 // Host side: validation and dispatch
 // ---------------------------------------------------------------------------
 static uint32_t code_bits(uint32_t x)
@@ -722,10 +777,13 @@ static int make_tiling(uint64_t n, uint32_t bucket, uint32_t tile, Tiling* tl)
     return NDQ_OK;
 }
 
-static int make_quant(uint32_t levels, uint32_t M, bool nested, Quant* qp)
+static int make_quant(uint32_t levels, uint32_t M, bool nested, float alpha, Quant* qp)
 {
     if (levels < 2u || levels > 256u) return NDQ_EINVAL;
     if (nested && (M < 2u || M > 256u)) return NDQ_EINVAL;
+    if (nested && !(alpha > 0.0f && alpha <= 1.0f)) return NDQ_EINVAL;
+    qp->alpha = nested ? alpha : 1.0f;
+    qp->beta = (float)(1.0 - (double)qp->alpha * (double)qp->alpha);
     qp->levels = levels;
     qp->q_min = -(int32_t)(levels / 2u);
     qp->q_min_f = (float)qp->q_min;
@@ -777,11 +835,11 @@ static int run_encode(const EncodeArgs& a, bool fused, hipStream_t s)
 }
 
 static int encode_common(const void* g, ndq_dtype dt, size_t n, float delta, uint32_t levels,
-                         uint32_t M, bool nested, uint32_t bucket, const ndq_dither* d,
+                         uint32_t M, bool nested, float alpha, uint32_t bucket, const ndq_dither* d,
                          void* codes_out, float* steps_out, void* stream)
 {
     EncodeArgs a;
-    int rc = make_quant(levels, M, nested, &a.qp);
+    int rc = make_quant(levels, M, nested, alpha, &a.qp);
     if (rc != NDQ_OK) return rc;
     if (dt != NDQ_F32 && dt != NDQ_BF16) return NDQ_EINVAL;
     if (!d) return NDQ_EINVAL;
@@ -816,7 +874,7 @@ static int encode_common(const void* g, ndq_dtype dt, size_t n, float delta, uin
         if (launched() != NDQ_OK) return NDQ_ELAUNCH;
     }
     const int mode = !nested ? (a.qp.bits <= 6u ? kDqNarrow : kDq)
-                             : (is_pow2(M) ? kNestedPow2 : kNestedAnyM);
+                             : (is_pow2(M) && alpha == 1.0f ? kNestedPow2 : kNestedAnyM);
     if (dt == NDQ_F32) {
         if (mode == kDqNarrow) return run_encode<0, kDqNarrow>(a, fused, s);
         if (mode == kDq) return run_encode<0, kDq>(a, fused, s);
@@ -857,12 +915,13 @@ static int run_decode(const DecodeArgs& a, uint64_t n, uint32_t bucket, int acc,
 }
 
 static int decode_common(const void* codes, size_t n, uint32_t levels, uint32_t M, bool nested,
-                         bool half, uint32_t bucket, const float* steps, const ndq_dither* d,
+                         bool half, float alpha, uint32_t bucket, const float* steps,
+                         const ndq_dither* d,
                          const float* side, float side_scale, float* out, int accumulate,
                          void* stream)
 {
     DecodeArgs a;
-    int rc = make_quant(levels, M, nested, &a.qp);
+    int rc = make_quant(levels, M, nested, alpha, &a.qp);
     if (rc != NDQ_OK) return rc;
     if (!d) return NDQ_EINVAL;
     if (n == 0) return NDQ_OK;
@@ -888,7 +947,7 @@ static int decode_common(const void* codes, size_t n, uint32_t levels, uint32_t 
     if (nested && accumulate && side == out) acc = kAccumulateInPlace;
     if (!nested) return half ? run_decode<kDqHalf>(a, n, bucket, acc, s)
                              : run_decode<kDq>(a, n, bucket, acc, s);
-    if (is_pow2(M)) return run_decode<kNestedPow2>(a, n, bucket, acc, s);
+    if (is_pow2(M) && alpha == 1.0f) return run_decode<kNestedPow2>(a, n, bucket, acc, s);
     return run_decode<kNestedAnyM>(a, n, bucket, acc, s);
 }
 
@@ -936,41 +995,41 @@ int ndq_dq_encode(const void* g, ndq_dtype dt, size_t n, float delta, uint32_t l
                   uint32_t bucket, const ndq_dither* d, void* codes_out, float* steps_out,
                   void* stream)
 {
-    return ndq::encode_common(g, dt, n, delta, levels, 0u, false, bucket, d, codes_out, steps_out,
-                              stream);
+    return ndq::encode_common(g, dt, n, delta, levels, 0u, false, 1.0f, bucket, d, codes_out,
+                              steps_out, stream);
 }
 
 int ndq_nested_encode(const void* g, ndq_dtype dt, size_t n, float delta, uint32_t levels,
-                      uint32_t M, uint32_t bucket, const ndq_dither* d, void* codes_out,
-                      float* steps_out, void* stream)
+                      uint32_t M, float alpha, uint32_t bucket, const ndq_dither* d,
+                      void* codes_out, float* steps_out, void* stream)
 {
-    return ndq::encode_common(g, dt, n, delta, levels, M, true, bucket, d, codes_out, steps_out,
-                              stream);
+    return ndq::encode_common(g, dt, n, delta, levels, M, true, alpha, bucket, d, codes_out,
+                              steps_out, stream);
 }
 
 int ndq_dq_decode(const void* codes, size_t n, uint32_t levels, uint32_t bucket,
                   const float* steps, const ndq_dither* d, float* out, int accumulate,
                   void* stream)
 {
-    return ndq::decode_common(codes, n, levels, 0u, false, false, bucket, steps, d, nullptr, 1.0f,
-                              out, accumulate, stream);
+    return ndq::decode_common(codes, n, levels, 0u, false, false, 1.0f, bucket, steps, d, nullptr,
+                              1.0f, out, accumulate, stream);
 }
 
 int ndq_dq_decode_half(const void* codes, size_t n, uint32_t levels, uint32_t bucket,
                        const float* steps, float* out, int accumulate, void* stream)
 {
     const ndq_dither none = {0u, 0u, 0u, 0u};   // no dither is regenerated
-    return ndq::decode_common(codes, n, levels, 0u, false, true, bucket, steps, &none, nullptr,
-                              1.0f, out, accumulate, stream);
+    return ndq::decode_common(codes, n, levels, 0u, false, true, 1.0f, bucket, steps, &none,
+                              nullptr, 1.0f, out, accumulate, stream);
 }
 
-int ndq_nested_decode(const void* codes, size_t n, uint32_t M, uint32_t bucket,
+int ndq_nested_decode(const void* codes, size_t n, uint32_t M, float alpha, uint32_t bucket,
                       const float* steps, const ndq_dither* d, const float* side,
                       float side_scale, float* out, int accumulate, void* stream)
 {
     // `levels` plays no part in decoding: the step travels in `steps`
-    return ndq::decode_common(codes, n, 2u, M, true, false, bucket, steps, d, side, side_scale,
-                              out, accumulate, stream);
+    return ndq::decode_common(codes, n, 2u, M, true, false, alpha, bucket, steps, d, side,
+                              side_scale, out, accumulate, stream);
 }
 
 int ndq_aggregate(const float* const* gs, uint32_t W, size_t n, float scale, float* out,
@@ -1016,6 +1075,7 @@ int ndq_decode_chain(const ndq_worker* workers, uint32_t W, size_t n, uint32_t b
         const ndq_worker& wk = workers[p];
         if (wk.kind != NDQ_WORKER_DQ && wk.kind != NDQ_WORKER_NESTED) return NDQ_EINVAL;
         if (wk.levels_or_M < 2u || wk.levels_or_M > 256u) return NDQ_EINVAL;
+        if (wk.kind == NDQ_WORKER_NESTED && !(wk.alpha > 0.0f && wk.alpha <= 1.0f)) return NDQ_EINVAL;
     }
     if (n == 0) return NDQ_OK;
     if (!out) return NDQ_EINVAL;
@@ -1040,7 +1100,7 @@ int ndq_decode_chain(const ndq_worker* workers, uint32_t W, size_t n, uint32_t b
             const ndq_worker& wk = workers[p0 + j];
             const bool nested = wk.kind == NDQ_WORKER_NESTED;
             Quant qp;
-            make_quant(nested ? 2u : wk.levels_or_M, wk.levels_or_M, nested, &qp);
+            make_quant(nested ? 2u : wk.levels_or_M, wk.levels_or_M, nested, wk.alpha, &qp);
             ChainWorker& cw = a.w[j];
             cw.codes = (const unsigned char*)wk.codes;
             cw.steps = wk.steps;
@@ -1050,9 +1110,12 @@ int ndq_decode_chain(const ndq_worker* workers, uint32_t W, size_t n, uint32_t b
             cw.M = qp.M;
             cw.M_f = qp.M_f;
             cw.inv_M_f = qp.inv_M_f;
+            cw.alpha = qp.alpha;
+            cw.beta = qp.beta;
             cw.side_scale = (p0 + j) ? 1.0f / (float)(p0 + j) : 0.0f;
             cw.bits = qp.bits;
-            cw.mode = !nested ? kDq : (is_pow2(wk.levels_or_M) ? kNestedPow2 : kNestedAnyM);
+            cw.mode = !nested ? kDq
+                              : (is_pow2(wk.levels_or_M) && wk.alpha == 1.0f ? kNestedPow2 : kNestedAnyM);
             cw.first = (p0 + j) == 0u;
         }
         hipLaunchKernelGGL(chain_kernel, dim3(blocks_for(a.tl.total_tiles)), dim3(kBlock), 0,
@@ -1146,6 +1209,37 @@ int ndq_dense_pack(const void* codes, size_t n, uint32_t levels, void* dense_out
 int ndq_dense_unpack(const void* dense, size_t n, uint32_t levels, void* codes_out, void* stream)
 {
     return dense_common(codes_out, dense, n, levels, false, stream);
+}
+
+double ndq_alpha_for_equal_variance(double delta1, double sigma_z2)
+{
+    const double arg = 1.0 - delta1 * delta1 / (12.0 * sigma_z2);
+    return arg > 0.0 ? sqrt(arg) : 0.0;
+}
+
+double ndq_decode_error_bound(double delta1, uint32_t M, double alpha, double sigma_z2)
+{
+    const double delta2 = (double)M * delta1;
+    return delta1 * delta1 / (3.0 * delta2 * delta2) + 4.0 * alpha * alpha * sigma_z2 / (delta2 * delta2);
+}
+
+size_t ndq_sqdiff_workspace(void) { return ndq::kSqBlocks * sizeof(double); }
+
+int ndq_sqdiff(const float* a, const float* b, size_t n, double* workspace, double* out,
+               void* stream)
+{
+    using namespace ndq;
+    if (!workspace || !out) return NDQ_EINVAL;
+    if (n != 0 && (!a || !b)) return NDQ_EINVAL;
+    if (n >= kMaxN) return NDQ_EUNSUPPORTED;
+    if (((uintptr_t)workspace & 7u) || ((uintptr_t)out & 7u)) return NDQ_EALIGN;
+    if (n != 0 && (!aligned16(a) || !aligned16(b))) return NDQ_EALIGN;
+    hipStream_t s = (hipStream_t)stream;
+    hipLaunchKernelGGL(sqdiff_partial_kernel, dim3(kSqBlocks), dim3(256), 0, s, a, b, (uint64_t)n,
+                       workspace);
+    if (launched() != NDQ_OK) return NDQ_ELAUNCH;
+    hipLaunchKernelGGL(sqdiff_final_kernel, dim3(1), dim3(256), 0, s, (const double*)workspace, out);
+    return launched();
 }
 
 const char* ndq_strerror(int rc)

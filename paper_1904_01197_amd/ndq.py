@@ -20,7 +20,8 @@ NDQ_OK, NDQ_EINVAL, NDQ_EALIGN, NDQ_EUNSUPPORTED, NDQ_ELAUNCH = 0, -1, -2, -3, -
 EXPORTS = ("ndq_code_bits", "ndq_packed_bytes", "ndq_num_buckets", "ndq_absmax", "ndq_dq_encode",
            "ndq_dq_decode", "ndq_dq_decode_half", "ndq_nested_encode", "ndq_nested_decode", "ndq_aggregate",
            "ndq_decode_chain", "ndq_code_entropy", "ndq_dense_group", "ndq_dense_bytes",
-           "ndq_dense_pack", "ndq_dense_unpack", "ndq_strerror")
+           "ndq_dense_pack", "ndq_dense_unpack", "ndq_alpha_for_equal_variance",
+           "ndq_decode_error_bound", "ndq_sqdiff_workspace", "ndq_sqdiff", "ndq_strerror")
 
 
 class ndq_dither(C.Structure):
@@ -35,7 +36,7 @@ NDQ_WORKER_DQ, NDQ_WORKER_NESTED = 0, 1
 class ndq_worker(C.Structure):
     """Mirror of the C struct: one worker's message as the server holds it."""
     _fields_ = [("codes", C.c_void_p), ("steps", C.c_void_p), ("kind", C.c_uint32),
-                ("levels_or_M", C.c_uint32), ("dither", ndq_dither)]
+                ("levels_or_M", C.c_uint32), ("alpha", C.c_float), ("dither", ndq_dither)]
 
 
 class NdqError(RuntimeError):
@@ -68,13 +69,19 @@ def lib():
         L.ndq_dq_decode.restype = ci
         L.ndq_dq_decode_half.argtypes = [vp, sz, u32, u32, vp, vp, ci, vp]
         L.ndq_dq_decode_half.restype = ci
-        L.ndq_nested_encode.argtypes = [vp, ci, sz, f32, u32, u32, u32, dp, vp, vp, vp]
+        L.ndq_nested_encode.argtypes = [vp, ci, sz, f32, u32, u32, f32, u32, dp, vp, vp, vp]
         L.ndq_nested_encode.restype = ci
-        L.ndq_nested_decode.argtypes = [vp, sz, u32, u32, vp, dp, vp, f32, vp, ci, vp]
+        L.ndq_nested_decode.argtypes = [vp, sz, u32, f32, u32, vp, dp, vp, f32, vp, ci, vp]
         L.ndq_nested_decode.restype = ci
         L.ndq_aggregate.argtypes, L.ndq_aggregate.restype = [vp, u32, sz, f32, vp, vp], ci
         L.ndq_decode_chain.argtypes = [C.POINTER(ndq_worker), u32, sz, u32, f32, vp, vp]
         L.ndq_decode_chain.restype = ci
+        L.ndq_alpha_for_equal_variance.argtypes = [C.c_double, C.c_double]
+        L.ndq_alpha_for_equal_variance.restype = C.c_double
+        L.ndq_decode_error_bound.argtypes = [C.c_double, u32, C.c_double, C.c_double]
+        L.ndq_decode_error_bound.restype = C.c_double
+        L.ndq_sqdiff_workspace.argtypes, L.ndq_sqdiff_workspace.restype = [], sz
+        L.ndq_sqdiff.argtypes, L.ndq_sqdiff.restype = [vp, vp, sz, vp, vp, vp], ci
         L.ndq_dense_group.argtypes, L.ndq_dense_group.restype = [u32], u32
         L.ndq_dense_bytes.argtypes, L.ndq_dense_bytes.restype = [sz, u32], sz
         L.ndq_dense_pack.argtypes, L.ndq_dense_pack.restype = [vp, sz, u32, vp, vp], ci
@@ -155,9 +162,9 @@ def ndq_dq_encode(g, delta, levels, bucket, d, codes_out=None, steps_out=None):
     return codes_out, steps_out
 
 
-def ndq_nested_encode(g, delta, levels, M, bucket, d, codes_out=None, steps_out=None):
+def ndq_nested_encode(g, delta, levels, M, alpha, bucket, d, codes_out=None, steps_out=None):
     codes_out, steps_out = _enc_outputs(g, ndq_code_bits(M), bucket, codes_out, steps_out)
-    _check(lib().ndq_nested_encode(_dev(g, "g"), _dt(g), g.numel(), delta, levels, M, bucket,
+    _check(lib().ndq_nested_encode(_dev(g, "g"), _dt(g), g.numel(), delta, levels, M, alpha, bucket,
                                    C.byref(d), _dev(codes_out, "codes_out"),
                                    _dev(steps_out, "steps_out"), _stream()), "ndq_nested_encode")
     return codes_out, steps_out
@@ -189,7 +196,7 @@ def ndq_dq_decode_half(codes, n, levels, bucket, steps, out=None, accumulate=Fal
     return out
 
 
-def ndq_nested_decode(codes, n, M, bucket, steps, d, side, side_scale=1.0, out=None,
+def ndq_nested_decode(codes, n, M, alpha, bucket, steps, d, side, side_scale=1.0, out=None,
                       accumulate=False):
     if out is None:
         if accumulate:
@@ -197,7 +204,7 @@ def ndq_nested_decode(codes, n, M, bucket, steps, d, side, side_scale=1.0, out=N
         out = torch.empty(n, dtype=torch.float32, device=codes.device)
     if out.dtype != torch.float32 or out.numel() < n or side.dtype != torch.float32:
         raise ValueError("out and side must hold n float32")
-    _check(lib().ndq_nested_decode(_dev(codes, "codes"), n, M, bucket, _dev(steps, "steps"),
+    _check(lib().ndq_nested_decode(_dev(codes, "codes"), n, M, alpha, bucket, _dev(steps, "steps"),
                                    C.byref(d), _dev(side, "side"), side_scale, _dev(out, "out"),
                                    int(bool(accumulate)), _stream()), "ndq_nested_decode")
     return out
@@ -217,13 +224,16 @@ def ndq_aggregate(gs, scale=1.0, out=None):
 
 
 def ndq_decode_chain(workers, n, bucket, scale=1.0, out=None):
-    """workers: sequence of (codes, steps, kind, levels_or_M, ndq_dither) in decoding order."""
+    """workers: sequence of (codes, steps, kind, levels_or_M, ndq_dither[, alpha]) in decoding
+    order; alpha (nested workers only) defaults to 1."""
     arr = (ndq_worker * len(workers))()
-    for i, (codes, steps, kind, arg, d) in enumerate(workers):
+    for i, wk in enumerate(workers):
+        codes, steps, kind, arg, d = wk[:5]
         arr[i].codes = _dev(codes, "codes").value
         arr[i].steps = _dev(steps, "steps").value
         arr[i].kind = kind
         arr[i].levels_or_M = arg
+        arr[i].alpha = wk[5] if len(wk) > 5 else 1.0
         arr[i].dither = d
     if out is None:
         out = torch.empty(n, dtype=torch.float32, device=workers[0][0].device)
@@ -276,3 +286,28 @@ def ndq_dense_unpack(dense, n, levels, codes_out=None):
         _check(lib().ndq_dense_unpack(_dev(dense, "dense"), n, levels, _dev(codes_out, "codes_out"),
                                       _stream()), "ndq_dense_unpack")
     return codes_out
+
+
+def ndq_alpha_for_equal_variance(delta1, sigma_z2):
+    return lib().ndq_alpha_for_equal_variance(delta1, sigma_z2)
+
+
+def ndq_decode_error_bound(delta1, M, alpha, sigma_z2):
+    return lib().ndq_decode_error_bound(delta1, M, alpha, sigma_z2)
+
+
+def ndq_sqdiff_workspace():
+    return lib().ndq_sqdiff_workspace()
+
+
+def ndq_sqdiff(a, b, workspace=None, out=None):
+    """sum_i (a_i - b_i)^2 in binary64 -> 1-element float64 tensor"""
+    if a.dtype != torch.float32 or b.dtype != torch.float32 or a.numel() != b.numel():
+        raise ValueError("a and b must be float32 of equal length")
+    if workspace is None:
+        workspace = torch.empty(ndq_sqdiff_workspace() // 8, dtype=torch.float64, device=a.device)
+    if out is None:
+        out = torch.empty(1, dtype=torch.float64, device=a.device)
+    _check(lib().ndq_sqdiff(_dev(a, "a"), _dev(b, "b"), a.numel(), _dev(workspace, "workspace"),
+                            _dev(out, "out"), _stream()), "ndq_sqdiff")
+    return out

@@ -53,7 +53,7 @@ def encode_all(wl: Workload, grads, bufs: Buffers, ds, preset_step: float = 0.0)
         if kind == "dq":
             ndq.ndq_dq_encode(grads[w], delta, arg, wl.bucket, ds[w], bufs.codes[w], bufs.steps[w])
         else:
-            ndq.ndq_nested_encode(grads[w], delta, wl.fine_levels, arg, wl.bucket, ds[w],
+            ndq.ndq_nested_encode(grads[w], delta, wl.fine_levels, arg, 1.0, wl.bucket, ds[w],
                                   bufs.codes[w], bufs.steps[w])
         if wl.shared_step and w == 0 and delta == 0.0:
             delta = float(bufs.steps[0][0].item())
@@ -70,7 +70,7 @@ def decode_chain(wl: Workload, n: int, bufs: Buffers, ds):
             ndq.ndq_dq_decode(bufs.codes[w], n, arg, wl.bucket, bufs.steps[w], ds[w], S,
                               accumulate=count > 0)
         else:
-            ndq.ndq_nested_decode(bufs.codes[w], n, arg, wl.bucket, bufs.steps[w], ds[w], S,
+            ndq.ndq_nested_decode(bufs.codes[w], n, arg, 1.0, wl.bucket, bufs.steps[w], ds[w], S,
                                   1.0 / count, S, accumulate=True)
         count += 1
     if wl.out_scale != 1.0:
@@ -129,7 +129,7 @@ def step_overlapped(wl: Workload, grads, bufs: Buffers, ds, ts: TwoStreams,
                 ndq.ndq_dq_encode(grads[w], preset_step, arg, wl.bucket, ds[w], bufs.codes[w],
                                   bufs.steps[w])
             else:
-                ndq.ndq_nested_encode(grads[w], preset_step, wl.fine_levels, arg, wl.bucket,
+                ndq.ndq_nested_encode(grads[w], preset_step, wl.fine_levels, arg, 1.0, wl.bucket,
                                       ds[w], bufs.codes[w], bufs.steps[w])
             ts.encoded[w].record(ts.enc)
     S = bufs.total
@@ -140,7 +140,7 @@ def step_overlapped(wl: Workload, grads, bufs: Buffers, ds, ts: TwoStreams,
                 ndq.ndq_dq_decode(bufs.codes[w], n, arg, wl.bucket, bufs.steps[w], ds[w], S,
                                   accumulate=w > 0)
             else:
-                ndq.ndq_nested_decode(bufs.codes[w], n, arg, wl.bucket, bufs.steps[w], ds[w], S,
+                ndq.ndq_nested_decode(bufs.codes[w], n, arg, 1.0, wl.bucket, bufs.steps[w], ds[w], S,
                                       1.0 / w, S, accumulate=True)
         if wl.out_scale != 1.0:
             ndq.ndq_aggregate([S], wl.out_scale, S)

@@ -65,11 +65,16 @@ def test_validation_rejects_bad_arguments_without_a_gpu():
         == ndq.NDQ_EUNSUPPORTED
     d_bad = ndq.ndq_dither(0, 0, 0, 2)
     assert lib.ndq_dq_encode(p, 0, 64, 0.0, 4, 0, C.byref(d_bad), p, p, null) == ndq.NDQ_EALIGN
-    assert lib.ndq_nested_encode(p, 0, 64, 0.0, 4, 1, 0, C.byref(d), p, p, null) == ndq.NDQ_EINVAL
-    assert lib.ndq_nested_decode(p, 64, 300, 0, p, C.byref(d), p, 1.0, p, 0, null) == ndq.NDQ_EINVAL
-    assert lib.ndq_nested_decode(p, 64, 4, 0, p, C.byref(d), null, 1.0, p, 0, null) == ndq.NDQ_EINVAL
+    assert lib.ndq_nested_encode(p, 0, 64, 0.0, 4, 1, 1.0, 0, C.byref(d), p, p, null) == ndq.NDQ_EINVAL
+    assert lib.ndq_nested_decode(p, 64, 300, 1.0, 0, p, C.byref(d), p, 1.0, p, 0, null) == ndq.NDQ_EINVAL
+    assert lib.ndq_nested_decode(p, 64, 4, 1.0, 0, p, C.byref(d), null, 1.0, p, 0, null) == ndq.NDQ_EINVAL
     q = C.c_void_p(0x1010)           # side and out overlap partially
-    assert lib.ndq_nested_decode(p, 64, 4, 0, p, C.byref(d), p, 1.0, q, 1, null) == ndq.NDQ_EINVAL
+    assert lib.ndq_nested_decode(p, 64, 4, 1.0, 0, p, C.byref(d), p, 1.0, q, 1, null) == ndq.NDQ_EINVAL
+    for bad_alpha in (0.0, -0.5, 1.5, float("nan")):
+        assert lib.ndq_nested_encode(p, 0, 64, 0.0, 4, 4, bad_alpha, 0, C.byref(d), p, p, null) \
+            == ndq.NDQ_EINVAL
+        assert lib.ndq_nested_decode(p, 64, 4, bad_alpha, 0, p, C.byref(d), p, 1.0, p, 0, null) \
+            == ndq.NDQ_EINVAL
     assert lib.ndq_dq_decode(p, 64, 4, 32, p, C.byref(d), p, 0, null) == ndq.NDQ_EALIGN
     assert lib.ndq_aggregate(null, 2, 64, 1.0, p, null) == ndq.NDQ_EINVAL
     ptrs = (C.c_void_p * 2)(0x1000, 0x2000)
@@ -99,3 +104,14 @@ def test_workload_generators_are_seeded_and_chunked():
     assert abs(np.corrcoef(g2[0], g2[1])[0, 1] - 0.9) < 0.005
     g4 = W.gradients(W.CONFIGS[4], n=1 << 18)
     assert abs(np.corrcoef(g4[1], g4[2])[0, 1] - 0.917) < 0.01
+
+
+def test_parameter_selection_helpers_agree_with_oracle():
+    for d1, s2 in ((0.01, 6.4e-5), (0.5, 1.0), (1.0, 0.05), (0.004, 1e-6)):
+        assert ndq.ndq_alpha_for_equal_variance(d1, s2) == oracle.alpha_for_equal_variance(d1, s2)
+        for M in (2, 3, 4, 16):
+            for alpha in (1.0, 0.7):
+                assert ndq.ndq_decode_error_bound(d1, M, alpha, s2) == \
+                    oracle.decode_error_bound(d1, M, alpha, s2)
+    assert ndq.ndq_alpha_for_equal_variance(1.0, 0.05) == 0.0
+    assert ndq.ndq_sqdiff_workspace() % 8 == 0 and ndq.ndq_sqdiff_workspace() >= 8

@@ -187,8 +187,9 @@ def test_argument_errors_are_reported_not_launched():
     d = ndq.ndq_dither(0, 0, 0, 0)
     for bad in (lambda: ndq.ndq_dq_encode(g, 0.0, 1, 0, d),
                 lambda: ndq.ndq_dq_encode(g, 0.0, 257, 0, d),
-                lambda: ndq.ndq_nested_encode(g, 0.0, 4, 1, 0, d),
-                lambda: ndq.ndq_nested_encode(g, 0.0, 4, 300, 0, d)):
+                lambda: ndq.ndq_nested_encode(g, 0.0, 4, 1, 1.0, 0, d),
+                lambda: ndq.ndq_nested_encode(g, 0.0, 4, 300, 1.0, 0, d),
+                lambda: ndq.ndq_nested_encode(g, 0.0, 4, 4, 1.5, 0, d)):
         with pytest.raises(ndq.NdqError) as e:
             bad()
         assert e.value.rc == ndq.NDQ_EINVAL
@@ -201,10 +202,10 @@ def test_argument_errors_are_reported_not_launched():
     with pytest.raises(ndq.NdqError) as e:
         ndq.ndq_dq_encode(g, 0.0, 4, 0, ndq.ndq_dither(0, 0, 0, 2))
     assert e.value.rc == ndq.NDQ_EALIGN
-    codes, steps = ndq.ndq_nested_encode(g, 1.0, 4, 4, 0, d)
+    codes, steps = ndq.ndq_nested_encode(g, 1.0, 4, 4, 1.0, 0, d)
     buf = torch.zeros(4096 + 8, dtype=torch.float32, device=dev)
     with pytest.raises(ndq.NdqError) as e:                   # partially overlapping side / out
-        ndq.ndq_nested_decode(codes, 4096, 4, 0, steps, d, buf[:4096], 1.0, buf[4:4100], True)
+        ndq.ndq_nested_decode(codes, 4096, 4, 1.0, 0, steps, d, buf[:4096], 1.0, buf[4:4100], True)
     assert e.value.rc == ndq.NDQ_EINVAL
     torch.cuda.synchronize()
 
@@ -225,24 +226,24 @@ def test_nested_encode_decode_matches_oracle(dtype, M, levels, bucket):
         side = (gf + rng.standard_normal(n).astype(F) * F(0.3 * np.abs(gf).max() / levels)).astype(F)
         d_o, d_g = oracle.dither(3, 2, 9), ndq.ndq_dither(3, 2, 9, 0)
         c_ref, s_ref = oracle.nested_encode(g, 0.0, levels, M, bucket, d_o)
-        codes, steps = ndq.ndq_nested_encode(_to_dev(g), 0.0, levels, M, bucket, d_g)
+        codes, steps = ndq.ndq_nested_encode(_to_dev(g), 0.0, levels, M, 1.0, bucket, d_g)
         assert np.array_equal(steps.cpu().numpy(), s_ref), (n, "steps")
         assert codes.cpu().numpy().tobytes() == c_ref.tobytes(), (n, "codes")
         side_d = _to_dev(side)
         for scale in (1.0, 0.5, 1.0 / 3.0):
             ref = oracle.nested_decode(c_ref, n, M, bucket, s_ref, d_o, side, scale)
-            out = ndq.ndq_nested_decode(codes, n, M, bucket, steps, d_g, side_d, scale)
+            out = ndq.ndq_nested_decode(codes, n, M, 1.0, bucket, steps, d_g, side_d, scale)
             # the coset representative is an integer decision: it must agree exactly
             assert np.array_equal(out.cpu().numpy(), ref), (n, scale)
         # running-sum forms: separate buffer, and in place (out is side)
         base = _make(n, "f32", seed=n + 2)
         ref_acc = oracle.nested_decode(c_ref, n, M, bucket, s_ref, d_o, side, 0.5, out=base.copy())
-        acc = ndq.ndq_nested_decode(codes, n, M, bucket, steps, d_g, side_d, 0.5, _to_dev(base), True)
+        acc = ndq.ndq_nested_decode(codes, n, M, 1.0, bucket, steps, d_g, side_d, 0.5, _to_dev(base), True)
         assert np.array_equal(acc.cpu().numpy(), ref_acc)
         ref_inp = side.copy()
         oracle.nested_decode(c_ref, n, M, bucket, s_ref, d_o, side, 0.5, out=ref_inp)
         s_inp = _to_dev(side)
-        ndq.ndq_nested_decode(codes, n, M, bucket, steps, d_g, s_inp, 0.5, s_inp, True)
+        ndq.ndq_nested_decode(codes, n, M, 1.0, bucket, steps, d_g, s_inp, 0.5, s_inp, True)
         assert np.array_equal(s_inp.cpu().numpy(), ref_inp)
 
 
@@ -258,8 +259,8 @@ def test_nested_equals_dqsg_inside_guaranteed_region_on_gpu():
     gd = _to_dev(g)
     c_dq, s_dq = ndq.ndq_dq_encode(gd, delta, levels + 3, 0, d)
     ref = ndq.ndq_dq_decode(c_dq, n, levels + 3, 0, s_dq, d)
-    c_n, s_n = ndq.ndq_nested_encode(gd, delta, levels, M, 0, d)
-    got = ndq.ndq_nested_decode(c_n, n, M, 0, s_n, d, _to_dev(y), 1.0)
+    c_n, s_n = ndq.ndq_nested_encode(gd, delta, levels, M, 1.0, 0, d)
+    got = ndq.ndq_nested_decode(c_n, n, M, 1.0, 0, s_n, d, _to_dev(y), 1.0)
     assert torch.equal(got, ref)
 
 
@@ -576,3 +577,81 @@ def test_three_level_gradient_in_dense_form():
     back = ndq.ndq_dense_unpack(dense, n, 3)
     assert torch.equal(back, codes)
     assert torch.equal(ndq.ndq_dq_decode(back, n, 3, 0, steps, d), ndq.ndq_dq_decode(codes, n, 3, 0, steps, d))
+
+
+# --------------------------------------------------------------------------
+# shrinkage factor alpha < 1 (eqs. (7)-(8), Thm 4) and its parameter estimate
+# --------------------------------------------------------------------------
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("M,alpha,bucket", [(4, 0.9, 0), (2, 0.75, 4096), (3, 0.5, 2048), (8, 0.97, 2112)])
+def test_nested_with_shrinkage_matches_oracle(dtype, M, alpha, bucket):
+    levels = 16
+    for n in SIZES:
+        g = _make(n, dtype, seed=n + M)
+        gf = workloads.bf16_bits_to_f32(g) if dtype == "bf16" else g
+        rng = np.random.default_rng(n)
+        side = (gf + rng.standard_normal(n).astype(F) * F(0.2 * np.abs(gf).max() / levels)).astype(F)
+        d_o, d_g = oracle.dither(13, 2, 5), ndq.ndq_dither(13, 2, 5, 0)
+        c_ref, s_ref = oracle.nested_encode(g, 0.0, levels, M, bucket, d_o, alpha=alpha)
+        codes, steps = ndq.ndq_nested_encode(_to_dev(g), 0.0, levels, M, alpha, bucket, d_g)
+        assert np.array_equal(steps.cpu().numpy(), s_ref), n
+        assert codes.cpu().numpy().tobytes() == c_ref.tobytes(), n
+        ref = oracle.nested_decode(c_ref, n, M, bucket, s_ref, d_o, side, 0.5, alpha=alpha)
+        out = ndq.ndq_nested_decode(codes, n, M, alpha, bucket, steps, d_g, _to_dev(side), 0.5)
+        assert np.array_equal(out.cpu().numpy(), ref), n
+        ref_inp = side.copy()
+        oracle.nested_decode(c_ref, n, M, bucket, s_ref, d_o, side, 0.5, out=ref_inp, alpha=alpha)
+        s_inp = _to_dev(side)
+        ndq.ndq_nested_decode(codes, n, M, alpha, bucket, steps, d_g, s_inp, 0.5, s_inp, True)
+        assert np.array_equal(s_inp.cpu().numpy(), ref_inp), n
+
+
+def test_chain_with_shrinkage_and_parameter_selection():
+    """Parameter selection of Thm 4 on the device estimate of sigma_z^2, then the
+    fused server loop with per-worker alpha, against the oracle's loop."""
+    n, levels, M, bucket = 300001, 16, 4, 0
+    rng = np.random.default_rng(77)
+    common = (rng.standard_normal(n) * 0.01).astype(F)
+    gs = [(common + rng.standard_normal(n) * 0.002).astype(F) for _ in range(4)]
+    dev = _gpu()
+    gd = [_to_dev(g) for g in gs]
+    # sigma_z^2 between two workers, on the device and in the oracle
+    sq = ndq.ndq_sqdiff(gd[1], gd[0])
+    ref_sq = oracle.sqdiff_sum(gs[1], gs[0])
+    assert abs(float(sq.item()) - ref_sq) <= 1e-12 * ref_sq
+    assert torch.equal(ndq.ndq_sqdiff(gd[1], gd[0]), sq)              # fixed reduction order
+    delta = float(F(2 * np.abs(gs[0]).max() / (levels - 1)))
+    alpha = ndq.ndq_alpha_for_equal_variance(delta, ref_sq / n)
+    assert 0.5 < alpha < 1.0
+    seeds = [0, 0, 0, 0]
+    ds_o = [oracle.dither(seeds[w], 9, w) for w in range(4)]
+    ds_g = [ndq.ndq_dither(seeds[w], 9, w, 0) for w in range(4)]
+    c0, s0 = oracle.dq_encode(gs[0], delta, levels, bucket, ds_o[0])
+    S = oracle.dq_decode(c0, n, levels, bucket, s0, ds_o[0])
+    workers = [(torch.from_numpy(c0).to(dev), torch.from_numpy(s0).to(dev), ndq.NDQ_WORKER_DQ,
+                levels, ds_g[0])]
+    for w in range(1, 4):
+        a_w = alpha if w != 2 else 1.0                                # mixed per-worker alpha
+        c, s = oracle.nested_encode(gs[w], delta, levels, M, bucket, ds_o[w], alpha=a_w)
+        cg, sg = ndq.ndq_nested_encode(gd[w], delta, levels, M, a_w, bucket, ds_g[w])
+        assert cg.cpu().numpy().tobytes() == c.tobytes()
+        S = oracle.nested_decode(c, n, M, bucket, s, ds_o[w], S, F(1.0 / w), out=S, alpha=a_w)
+        workers.append((cg, sg, ndq.NDQ_WORKER_NESTED, M, ds_g[w], a_w))
+    out = ndq.ndq_decode_chain(workers, n, bucket, 0.25)
+    assert np.array_equal(out.cpu().numpy(), oracle.aggregate([S], 0.25))
+
+
+@pytest.mark.parametrize("n", [0, 1, 3, 4, 5, 1023, 262144, 1000003])
+def test_sqdiff_matches_oracle(n):
+    rng = np.random.default_rng(n)
+    a = rng.standard_normal(n).astype(F)
+    b = rng.standard_normal(n).astype(F)
+    ref = oracle.sqdiff_sum(a, b)
+    if n == 0:
+        dev = _gpu()
+        e = torch.empty(0, dtype=torch.float32, device=dev)
+        assert float(ndq.ndq_sqdiff(e, e).item()) == 0.0
+        return
+    got = float(ndq.ndq_sqdiff(_to_dev(a), _to_dev(b)).item())
+    assert abs(got - ref) <= 1e-12 * ref
