@@ -37,6 +37,10 @@ def parse_args():
                     help="serial: one library call per worker and direction, one stream; "
                          "overlap: the same calls, encoders and decoders on two streams; "
                          "fused: all encodes, then the whole server loop in one call")
+    ap.add_argument("--extras", action="store_true",
+                    help="also time the kernels beyond the headline path (half-dithered decode, "
+                         "shrinkage alpha<1, index entropy, dense base-L stream, sigma_z estimate) "
+                         "on worker 0/1 of the same workload; reported under \"extras\"")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch a plain copy of 2^28 floats (ndq_aggregate with W=1, "
                          "scale=1: 1 GiB read + 1 GiB written) so that a counter run has a "
@@ -261,6 +265,58 @@ def main():
         lambda: pipeline.step_fused(wl, dev, bufs, ds, preset))
     other_ms = timed(other_fn, max(3, args.steps // 3))
 
+    extras = None
+    if args.extras:
+        extras = []
+
+        def extra(name, fn, nbytes, note):
+            ms = timed(fn, 10)
+            extras.append({"kernel": name, "avg_ms": round(ms, 5), "algorithmic_bytes": nbytes,
+                           "GBps": round(nbytes / (ms * 1e-3) / 1e9, 1),
+                           "hbm_frac": round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4), "note": note})
+
+        kind0, arg0 = wl.plan[0]
+        b0 = ndq.ndq_code_bits(arg0)
+        pk0 = (n * b0 + 7) // 8
+        scratch = torch.empty(n, dtype=torch.float32, device="cuda")
+        pipeline.encode_all(wl, dev, bufs, ds, preset)
+        extra("dq_decode_half_b%d" % b0,
+              lambda: ndq.ndq_dq_decode_half(bufs.codes[0], n, arg0, wl.bucket, bufs.steps[0], scratch),
+              pk0 + 4 * K + 4 * n, "no dither regenerated; write-bound")
+        hist = torch.empty(1 << b0, dtype=torch.int64, device="cuda")
+        ent = torch.empty(1, dtype=torch.float64, device="cuda")
+        extra("code_entropy_b%d" % b0, lambda: ndq.ndq_code_entropy(bufs.codes[0], n, b0, hist, ent),
+              pk0, "histogram + entropy of worker 0's index stream")
+        entropy0 = float(ent.item())
+        lv = 3
+        c3, s3 = ndq.ndq_dq_encode(dev[0], 0.0, lv, wl.bucket, ds[0])
+        dense = torch.empty(ndq.ndq_dense_bytes(n, lv), dtype=torch.uint8, device="cuda")
+        back = torch.empty_like(c3)
+        extra("dense_pack_L3", lambda: ndq.ndq_dense_pack(c3, n, lv, dense),
+              c3.numel() + dense.numel(), "2-bit stream -> 1.6 bits per index")
+        extra("dense_unpack_L3", lambda: ndq.ndq_dense_unpack(dense, n, lv, back),
+              c3.numel() + dense.numel(), "")
+        ws = torch.empty(ndq.ndq_sqdiff_workspace() // 8, dtype=torch.float64, device="cuda")
+        sq = torch.empty(1, dtype=torch.float64, device="cuda")
+        other_f32 = torch.empty(n, dtype=torch.float32, device="cuda").normal_()
+        extra("sqdiff", lambda: ndq.ndq_sqdiff(scratch, other_f32, ws, sq), 8 * n,
+              "sigma_z^2 estimate, binary64, fixed order")
+        if wl.W > 1 and wl.plan[1][0] == "nested":
+            M1 = wl.plan[1][1]
+            b1 = ndq.ndq_code_bits(M1)
+            pk1 = (n * b1 + 7) // 8
+            ca, sa = ndq.ndq_nested_encode(dev[1], preset, wl.fine_levels, M1, 0.9, wl.bucket, ds[1])
+            extra("nested_encode_alpha0.9_%s_b%d" % (wl.dtype, b1),
+                  lambda: ndq.ndq_nested_encode(dev[1], preset, wl.fine_levels, M1, 0.9, wl.bucket,
+                                                ds[1], ca, sa),
+                  n * s_in + pk1 + 4 * K, "shrinkage alpha = 0.9")
+            extra("nested_decode_alpha0.9_inplace_b%d" % b1,
+                  lambda: ndq.ndq_nested_decode(ca, n, M1, 0.9, wl.bucket, sa, ds[1], scratch, 1.0,
+                                                scratch, True),
+                  pk1 + 4 * K + 8 * n, "shrinkage alpha = 0.9, running sum updated in place")
+        extras.append({"index_entropy_bits_worker0": round(entropy0, 4), "fixed_width_bits": b0})
+        del scratch, other_f32
+
     # ---- CPU baseline: the oracle, as it stands, on a bounded sample ------------
     cpu = None
     if not args.no_cpu:
@@ -298,6 +354,7 @@ def main():
         "kernels": kernels,
         "other_schedule": {"schedule": other, "ms_per_step": round(other_ms, 4)},
         "input_generation_s": round(gen_s, 1),
+        "extras": extras,
     }
     print(json.dumps(out))
 

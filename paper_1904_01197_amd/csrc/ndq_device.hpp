@@ -126,10 +126,11 @@ __device__ __forceinline__ float inv_step(float step)
 //   kDqNarrow     : the same for codes of at most 6 bits (encoder packs in float)
 //   kDqHalf       : decoder only: half-dithered reconstruction Delta*q, no dither
 //                   regenerated (Sec. 2.1, last paragraph; Lemma 1)
-//   kNestedPow2   : NDQSG, M a power of two and alpha = 1 (mask / exact scale)
+//   kNestedPow2   : NDQSG, M a power of two (mask / exact scale); decoder: alpha = 1
+//   kNestedPow2Shrink : decoder only: M a power of two, shrinkage factor alpha < 1
 //   kNestedAnyM   : NDQSG, any M in [2,256], any shrinkage factor alpha in (0,1]
 // ---------------------------------------------------------------------------
-enum Mode { kDq = 0, kNestedPow2 = 1, kNestedAnyM = 2, kDqNarrow = 3, kDqHalf = 4 };
+enum Mode { kDq = 0, kNestedPow2 = 1, kNestedAnyM = 2, kDqNarrow = 3, kDqHalf = 4, kNestedPow2Shrink = 5 };
 
 struct Quant {
     float q_min_f, q_max_f;  // DQSG index range as floats
@@ -162,7 +163,7 @@ __device__ __forceinline__ uint32_t nested_code(float g, float inv, float v, con
     float r = __builtin_rintf(__builtin_fmaf(g, inv, v));
     r = __builtin_fminf(__builtin_fmaxf(r, -16777216.0f), 16777216.0f);
     const int32_t q = (int32_t)r;
-    if (MODE == kNestedPow2) return (uint32_t)q & (qp.M - 1u);
+    if (MODE == kNestedPow2 || MODE == kNestedPow2Shrink) return (uint32_t)q & (qp.M - 1u);
     int32_t m = q % (int32_t)qp.M;
     if (m < 0) m += (int32_t)qp.M;
     return (uint32_t)m;
@@ -179,7 +180,7 @@ __device__ __forceinline__ uint32_t encode_one(float g, float inv, float v, cons
 template <int MODE>
 __device__ __forceinline__ float shrink(float lattice, float y, const Quant& qp)
 {
-    if (MODE != kNestedAnyM) return lattice;
+    if (MODE != kNestedAnyM && MODE != kNestedPow2Shrink) return lattice;
     const float scaled = qp.alpha * lattice;
     return __builtin_fmaf(qp.beta, y, scaled);
 }
@@ -201,7 +202,7 @@ __device__ __forceinline__ float coset_index_f(uint32_t m, float y, float inv, f
     const float m_f = (float)m;
     const float c = __builtin_fmaf(y, inv, v);
     const float diff = c - m_f;
-    float k = (MODE == kNestedPow2) ? diff * qp.inv_M_f : diff / qp.M_f;
+    float k = (MODE == kNestedPow2 || MODE == kNestedPow2Shrink) ? diff * qp.inv_M_f : diff / qp.M_f;
     k = __builtin_rintf(k);
     k = __builtin_fminf(__builtin_fmaxf(k, -4194304.0f), 4194304.0f);
     return __builtin_fmaf(k, qp.M_f, m_f);

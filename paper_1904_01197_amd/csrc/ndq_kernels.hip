@@ -244,14 +244,16 @@ __device__ __forceinline__ void decode_tile(const DecodeArgs& a, const TileRef& 
                 packed[r] = codes32[w] >> sh;
             }
             if (FULL || o + 4 <= t.len) {
-                if (MODE == kNestedPow2 || MODE == kNestedAnyM) y[r] = *(const float4*)(side + o);
+                if (MODE == kNestedPow2 || MODE == kNestedAnyM || MODE == kNestedPow2Shrink)
+                    y[r] = *(const float4*)(side + o);
                 if (ACC == kAccumulate) prev[r] = *(const float4*)(out + o);
             } else {
                 float ys[4] = {0.f, 0.f, 0.f, 0.f}, ps[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (uint32_t k = 0; k < 4; ++k)
                     if (o + k < t.len) {
-                        if (MODE == kNestedPow2 || MODE == kNestedAnyM) ys[k] = side[o + k];
+                        if (MODE == kNestedPow2 || MODE == kNestedAnyM || MODE == kNestedPow2Shrink)
+                            ys[k] = side[o + k];
                         if (ACC == kAccumulate) ps[k] = out[o + k];
                     }
                 y[r] = make_float4(ys[0], ys[1], ys[2], ys[3]);
@@ -434,6 +436,7 @@ __device__ __forceinline__ void chain_tile(const ChainArgs& a, const TileRef& t,
         const uint64_t block0 = (cw.index0 + t.start) >> 3;
         if (cw.mode == kDq) chain_fold<kDq>(cw, cur, block0, lane, S);
         else if (cw.mode == kNestedPow2) chain_fold<kNestedPow2>(cw, cur, block0, lane, S);
+        else if (cw.mode == kNestedPow2Shrink) chain_fold<kNestedPow2Shrink>(cw, cur, block0, lane, S);
         else chain_fold<kNestedAnyM>(cw, cur, block0, lane, S);
         cur = nxt;
     }
@@ -874,7 +877,7 @@ static int encode_common(const void* g, ndq_dtype dt, size_t n, float delta, uin
         if (launched() != NDQ_OK) return NDQ_ELAUNCH;
     }
     const int mode = !nested ? (a.qp.bits <= 6u ? kDqNarrow : kDq)
-                             : (is_pow2(M) && alpha == 1.0f ? kNestedPow2 : kNestedAnyM);
+                             : (is_pow2(M) ? kNestedPow2 : kNestedAnyM);
     if (dt == NDQ_F32) {
         if (mode == kDqNarrow) return run_encode<0, kDqNarrow>(a, fused, s);
         if (mode == kDq) return run_encode<0, kDq>(a, fused, s);
@@ -948,6 +951,7 @@ static int decode_common(const void* codes, size_t n, uint32_t levels, uint32_t 
     if (!nested) return half ? run_decode<kDqHalf>(a, n, bucket, acc, s)
                              : run_decode<kDq>(a, n, bucket, acc, s);
     if (is_pow2(M) && alpha == 1.0f) return run_decode<kNestedPow2>(a, n, bucket, acc, s);
+    if (is_pow2(M)) return run_decode<kNestedPow2Shrink>(a, n, bucket, acc, s);
     return run_decode<kNestedAnyM>(a, n, bucket, acc, s);
 }
 
@@ -1115,7 +1119,8 @@ int ndq_decode_chain(const ndq_worker* workers, uint32_t W, size_t n, uint32_t b
             cw.side_scale = (p0 + j) ? 1.0f / (float)(p0 + j) : 0.0f;
             cw.bits = qp.bits;
             cw.mode = !nested ? kDq
-                              : (is_pow2(wk.levels_or_M) && wk.alpha == 1.0f ? kNestedPow2 : kNestedAnyM);
+                              : (!is_pow2(wk.levels_or_M) ? kNestedAnyM
+                                 : (wk.alpha == 1.0f ? kNestedPow2 : kNestedPow2Shrink));
             cw.first = (p0 + j) == 0u;
         }
         hipLaunchKernelGGL(chain_kernel, dim3(blocks_for(a.tl.total_tiles)), dim3(kBlock), 0,
