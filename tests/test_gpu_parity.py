@@ -367,8 +367,9 @@ def test_config5_heavy_tail_bf16_reduced_size():
 
 
 def test_config5_full_size_sampled_slices():
-    """Config 5 at its full size (n = 2^27 per worker, the benchmark's launch
-    configuration): the GPU processes the whole vectors; the oracle recomputes
+    """Config 5 at its full size (n = 2^27 per worker) in the launch configuration
+    the benchmark times (all encodes, then the fused server loop) and in the
+    call-by-call one: the GPU processes the whole vectors; the oracle recomputes
     bucket-aligned slices (first, last, and a spread of others) from the same
     input bytes with the matching dither offset and must agree bit for bit."""
     wl = workloads.CONFIGS[5]
@@ -377,7 +378,7 @@ def test_config5_full_size_sampled_slices():
     dev = pipeline.to_device(wl, host)
     bufs = pipeline.allocate(wl, n)
     ds_g = pipeline.dithers(wl)
-    out = pipeline.step(wl, dev, bufs, ds_g)
+    out = pipeline.step_fused(wl, dev, bufs, ds_g)
     torch.cuda.synchronize()
     seeds = [workloads.dither_seed(wl, w) for w in range(wl.W)]
     span = 16 * wl.bucket
@@ -396,9 +397,19 @@ def test_config5_full_size_sampled_slices():
             assert np.array_equal(got_s, s_ref[w]), (lo, w)
         ref = opipe.decode_chain(wl.plan, wl.bucket, span, c_ref, s_ref, ds_o, wl.out_scale)
         assert np.array_equal(out[lo:hi].cpu().numpy(), ref), lo
-    # properties that hold at any size: codes use only their b bits' range and the
-    # result is finite
+    # properties that hold at any size
     assert bool(torch.isfinite(out).all())
+    fused = out.clone()
+    # the call-by-call schedule gives the same 2^27 values
+    bufs2 = pipeline.allocate(wl, n)
+    out2 = pipeline.step(wl, dev, bufs2, ds_g)
+    assert torch.equal(out2, fused)
+    for w in range(wl.W):
+        assert torch.equal(bufs.codes[w], bufs2.codes[w]) and torch.equal(bufs.steps[w], bufs2.steps[w])
+    # the fine index never leaves the range the step allows: |q| <= (L-1)/2 + 1/2 for the
+    # worker's own data, so every nested residue is one of M values and the histogram is full
+    hist, _ = ndq.ndq_code_entropy(bufs.codes[1], n, 1)
+    assert int(hist.sum().item()) == n
 
 
 def test_runs_are_deterministic():
