@@ -37,6 +37,8 @@ def parse_args():
                     help="serial: one library call per worker and direction, one stream; "
                          "overlap: the same calls, encoders and decoders on two streams; "
                          "fused: all encodes, then the whole server loop in one call")
+    ap.add_argument("--graph", action="store_true",
+                    help="record the step into a HIP graph once and replay it for the timed steps")
     ap.add_argument("--extras", action="store_true",
                     help="also time the kernels beyond the headline path (half-dithered decode, "
                          "shrinkage alpha<1, index entropy, dense base-L stream, sigma_z estimate) "
@@ -145,6 +147,21 @@ def main():
         one_step = lambda: pipeline.step_fused(wl, dev, bufs, ds, preset)
     else:
         one_step = lambda: pipeline.step(wl, dev, bufs, ds, preset)
+    if args.graph:
+        if args.schedule == "overlap":
+            print("bench.py: --graph records one stream; use it with serial or fused", file=sys.stderr)
+            sys.exit(2)
+        eager_step = one_step
+        cap = torch.cuda.Stream()
+        cap.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(cap):
+            eager_step()
+        torch.cuda.current_stream().wait_stream(cap)
+        torch.cuda.synchronize()
+        hip_graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(hip_graph, stream=cap):
+            eager_step()
+        one_step = hip_graph.replay
     for _ in range(args.warmup):
         one_step()
     torch.cuda.synchronize()
@@ -344,7 +361,7 @@ def main():
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": wl.name, "W": wl.W, "n_per_worker": n, "input_dtype": wl.dtype,
-                   "bucket": wl.bucket, "schedule": args.schedule, "plan": ["%s%d" % p for p in wl.plan],
+                   "bucket": wl.bucket, "schedule": args.schedule, "hip_graph": bool(args.graph), "plan": ["%s%d" % p for p in wl.plan],
                    "launches_per_step": sum(r["launches_per_step"] for r in kernels)},
         "gelem_per_s": round(wl.W * n / (ms_per_step * 1e-3) / 1e9, 3),
         "step_algorithmic_bytes": step_bytes,

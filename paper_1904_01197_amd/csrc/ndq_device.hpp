@@ -12,7 +12,10 @@
 namespace ndq {
 
 constexpr int kWave = 64;           // CDNA wavefront
-constexpr int kWavesPerBlock = 4;   // 256-thread workgroups, waves work independently
+#ifndef NDQ_WAVES_PER_BLOCK
+#define NDQ_WAVES_PER_BLOCK 4
+#endif
+constexpr int kWavesPerBlock = NDQ_WAVES_PER_BLOCK;   // waves of a workgroup work independently
 constexpr int kBlock = kWave * kWavesPerBlock;
 #ifndef NDQ_DEC_ROWS_STREAM
 #define NDQ_DEC_ROWS_STREAM 8
@@ -147,7 +150,7 @@ struct Quant {
 __device__ __forceinline__ float dq_index_f(float g, float inv, float v, const Quant& qp)
 {
     const float r = __builtin_rintf(__builtin_fmaf(g, inv, v));
-    return __builtin_fminf(__builtin_fmaxf(r, qp.q_min_f), qp.q_max_f);
+    return __builtin_amdgcn_fmed3f(r, qp.q_min_f, qp.q_max_f);   // clip: median of (r, lo, hi)
 }
 
 // The same as a code in [0, levels).

@@ -114,8 +114,14 @@ __device__ __forceinline__ void encode_tile(const EncodeArgs& a, const TileRef& 
 // FUSED: the bucket fits one tile; its max-norm is reduced in registers and
 // the step is written.  Otherwise the step is the preset one or read from
 // `steps` (filled by absmax_kernel + steps_from_kappa_kernel).
+// Occupancy target.  The bfloat16 encoder is bound by instruction issue with a
+// burst of loads at the start of every tile; eight waves per SIMD (64 registers)
+// hide that burst better than four (+8 % measured).  The binary32 encoder moves
+// twice the bytes per element and measured best with the registers it asks for.
+template <int DT> struct EncWaves { static constexpr int W = DT == 1 ? 8 : 4; };
 template <int DT, int MODE, bool FUSED>
-__global__ __launch_bounds__(kBlock) void encode_kernel(EncodeArgs a)
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(EncWaves<DT>::W)))
+void encode_kernel(EncodeArgs a)
 {
     constexpr uint32_t TILE = EncTile<DT>::N;
     __shared__ __align__(16) unsigned char stage_all[kWavesPerBlock][TILE + 8];
@@ -213,7 +219,6 @@ template <int MODE, int ACC, bool FULL, bool STRADDLE>
 __device__ __forceinline__ void decode_tile(const DecodeArgs& a, const TileRef& t, int lane)
 {
     const uint32_t bits = a.qp.bits;
-    const uint32_t mask = (1u << bits) - 1u;
     const uint32_t* codes32 = (const uint32_t*)(a.codes + (t.start >> 3) * bits);
     const float* side = a.side + t.start;
     float* out = a.out + t.start;
@@ -272,7 +277,7 @@ __device__ __forceinline__ void decode_tile(const DecodeArgs& a, const TileRef& 
         float res[4];
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
-            const uint32_t c = (packed[r] >> (k * bits)) & mask;
+            const uint32_t c = __builtin_amdgcn_ubfe(packed[r], k * bits, bits);   // bit-field extract
             float q, yk = 0.0f;
             if (MODE == kDq || MODE == kDqHalf) {
                 q = (float)((int32_t)c + a.qp.q_min);
@@ -315,7 +320,10 @@ __global__ __launch_bounds__(kBlock) void decode_kernel(DecodeArgs a)
 // while the current worker's dither is generated.
 // ---------------------------------------------------------------------------
 constexpr uint32_t kChainMax = 32;    // workers per launch
-constexpr int kChainRows = 2;         // rows of 8 elements per lane and tile
+#ifndef NDQ_CHAIN_ROWS
+#define NDQ_CHAIN_ROWS 2
+#endif
+constexpr int kChainRows = NDQ_CHAIN_ROWS;   // rows of 8 elements per lane and tile
 constexpr uint32_t kChainTile = kWave * kLaneElems * kChainRows;
 
 struct ChainWorker {
@@ -380,7 +388,6 @@ __device__ __forceinline__ void chain_fold(const ChainWorker& cw, const ChainFet
                                            uint64_t block0, int lane, float (&S)[kChainRows][8])
 {
     const uint32_t bits = cw.bits;
-    const uint32_t mask = (1u << bits) - 1u;
     const float step = f.step;
     const float inv = cw.alpha * inv_step(step);
     Quant qp;
@@ -399,7 +406,7 @@ __device__ __forceinline__ void chain_fold(const ChainWorker& cw, const ChainFet
         dither8(cw.ds, block0 + (o >> 3), v);
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
-            const uint32_t c = (half[k >> 2] >> ((k & 3) * bits)) & mask;
+            const uint32_t c = __builtin_amdgcn_ubfe(half[k >> 2], (k & 3) * bits, bits);   // bit-field extract
             float q, yk = 0.0f;
             if (MODE == kDq) {
                 q = (float)((int32_t)c + qp.q_min);
@@ -460,7 +467,11 @@ __device__ __forceinline__ void chain_tile(const ChainArgs& a, const TileRef& t,
     }
 }
 
-__global__ __launch_bounds__(kBlock) void chain_kernel(ChainArgs a)
+#ifndef NDQ_CHAIN_WAVES_PER_EU
+#define NDQ_CHAIN_WAVES_PER_EU 6
+#endif
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(NDQ_CHAIN_WAVES_PER_EU)))
+void chain_kernel(ChainArgs a)
 {
     const int lane = threadIdx.x & (kWave - 1);
     const uint32_t tile_id =
@@ -876,7 +887,10 @@ static int encode_common(const void* g, ndq_dtype dt, size_t n, float delta, uin
                            s, steps_out, K, levels);
         if (launched() != NDQ_OK) return NDQ_ELAUNCH;
     }
-    const int mode = !nested ? (a.qp.bits <= 6u ? kDqNarrow : kDq)
+#ifndef NDQ_NARROW_MAX_BITS
+#define NDQ_NARROW_MAX_BITS 6u
+#endif
+    const int mode = !nested ? (a.qp.bits <= NDQ_NARROW_MAX_BITS ? kDqNarrow : kDq)
                              : (is_pow2(M) ? kNestedPow2 : kNestedAnyM);
     if (dt == NDQ_F32) {
         if (mode == kDqNarrow) return run_encode<0, kDqNarrow>(a, fused, s);

@@ -666,3 +666,38 @@ def test_sqdiff_matches_oracle(n):
         return
     got = float(ndq.ndq_sqdiff(_to_dev(a), _to_dev(b)).item())
     assert abs(got - ref) <= 1e-12 * ref
+
+
+def test_step_can_be_captured_in_a_hip_graph_and_replayed():
+    """The library only enqueues kernels on the given stream (no allocation, no
+    memset, no synchronisation), so a whole step can be recorded into a HIP graph;
+    every replay, with eager work and synchronisation in between, must reproduce
+    the eager result."""
+    wl = workloads.CONFIGS[5]
+    n = (1 << 20) + 4096 + 8
+    dev = pipeline.to_device(wl, workloads.gradients(wl, n))
+    ds = pipeline.dithers(wl)
+    eager = pipeline.allocate(wl, n)
+    ref = pipeline.step_fused(wl, dev, eager, ds).clone()
+    torch.cuda.synchronize()
+    bufs = pipeline.allocate(wl, n)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):              # warm-up on the capture stream
+        pipeline.step_fused(wl, dev, bufs, ds)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        pipeline.step_fused(wl, dev, bufs, ds)
+    for rep in range(4):
+        bufs.total.fill_(float(rep))           # eager work between replays
+        for c in bufs.codes:
+            c.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(bufs.total, ref), rep
+        for w in range(wl.W):
+            assert torch.equal(bufs.codes[w], eager.codes[w]), (rep, w)
+            assert torch.equal(bufs.steps[w], eager.steps[w]), (rep, w)
