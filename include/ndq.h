@@ -67,7 +67,7 @@ typedef enum {
     NDQ_OK = 0,
     NDQ_EINVAL = -1,       /* NULL pointer, levels/M outside [2,256], bad bucket, bad W */
     NDQ_EALIGN = -2,       /* pointer, bucket or offset alignment violated             */
-    NDQ_EUNSUPPORTED = -3, /* size beyond what one call supports (n >= 2^40)           */
+    NDQ_EUNSUPPORTED = -3, /* n too large for one call (limits lie between 2^38 and 2^40) */
     NDQ_ELAUNCH = -4       /* the HIP runtime refused a launch                         */
 } ndq_status;
 
