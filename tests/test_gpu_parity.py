@@ -701,3 +701,59 @@ def test_step_can_be_captured_in_a_hip_graph_and_replayed():
         for w in range(wl.W):
             assert torch.equal(bufs.codes[w], eager.codes[w]), (rep, w)
             assert torch.equal(bufs.steps[w], eager.steps[w]), (rep, w)
+
+
+def test_vector_longer_than_2_pow_32_elements():
+    """Largest practical size: n > 2^32 elements per worker (8.6 GB of bf16), so that
+    element indices, bit offsets and Philox counters leave 32 bits.  Inputs are
+    drawn on the device with torch (inputs are just bytes); the oracle recomputes
+    bucket-aligned slices -- the first, the one straddling index 2^32, some beyond
+    it, and the ragged end -- from the same bytes."""
+    dev = _gpu()
+    free, _ = torch.cuda.mem_get_info()
+    if free < 70 * (1 << 30):
+        pytest.skip("needs about 60 GB of free device memory")
+    n = (1 << 32) + (1 << 20) + 8
+    bucket, L, M = 4096, 4, 2
+    gen = torch.Generator(device=dev).manual_seed(20240607)
+    g = [torch.empty(n, dtype=torch.bfloat16, device=dev) for _ in range(2)]
+    step = 1 << 28
+    for a in range(0, n, step):
+        b = min(n, a + step)
+        common = torch.randn(b - a, generator=gen, device=dev) * 1e-3
+        g[0][a:b] = common.to(torch.bfloat16)
+        g[1][a:b] = (0.9 * common + 0.4e-3 * torch.randn(b - a, generator=gen, device=dev)).to(torch.bfloat16)
+        del common
+    d = [ndq.ndq_dither(11, 5, w, 0) for w in range(2)]
+    c0, s0 = ndq.ndq_dq_encode(g[0], 0.0, L, bucket, d[0])
+    c1, s1 = ndq.ndq_nested_encode(g[1], 0.0, L, M, 1.0, bucket, d[1])
+    out = ndq.ndq_decode_chain([(c0, s0, ndq.NDQ_WORKER_DQ, L, d[0]),
+                                (c1, s1, ndq.NDQ_WORKER_NESTED, M, d[1])], n, bucket, 1.0)
+    out2 = ndq.ndq_dq_decode(c0, n, L, bucket, s0, d[0])
+    ndq.ndq_nested_decode(c1, n, M, 1.0, bucket, s1, d[1], out2, 1.0, out2, True)
+    for a in range(0, n, step):
+        assert torch.equal(out[a:min(n, a + step)], out2[a:min(n, a + step)]), a
+    del out2
+    torch.cuda.synchronize()
+    span = 4 * bucket
+    tail = (n // bucket - 3) * bucket
+    starts = [0, (1 << 32) - 2 * bucket, (1 << 32) + 5 * bucket, (1 << 32) + (1 << 19), tail]
+    for lo in starts:
+        hi = min(n, lo + span)
+        m = hi - lo
+        h0 = g[0][lo:hi].view(torch.int16).cpu().numpy().view(np.uint16)
+        h1 = g[1][lo:hi].view(torch.int16).cpu().numpy().view(np.uint16)
+        r0, t0 = oracle.dq_encode(h0, 0.0, L, bucket, oracle.dither(11, 5, 0, lo))
+        r1, t1 = oracle.nested_encode(h1, 0.0, L, M, bucket, oracle.dither(11, 5, 1, lo))
+        nb = (m + bucket - 1) // bucket
+        assert np.array_equal(s0[lo // bucket:lo // bucket + nb].cpu().numpy(), t0), lo
+        assert np.array_equal(s1[lo // bucket:lo // bucket + nb].cpu().numpy(), t1), lo
+        b0, b1 = (m * 2 + 7) // 8, (m + 7) // 8
+        assert c0[lo * 2 // 8:lo * 2 // 8 + b0].cpu().numpy().tobytes() == r0[:b0].tobytes(), lo
+        assert c1[lo // 8:lo // 8 + b1].cpu().numpy().tobytes() == r1[:b1].tobytes(), lo
+        S = oracle.dq_decode(r0, m, L, bucket, t0, oracle.dither(11, 5, 0, lo))
+        S = oracle.nested_decode(r1, m, M, bucket, t1, oracle.dither(11, 5, 1, lo), S, 1.0, out=S)
+        assert np.array_equal(out[lo:hi].cpu().numpy(), S), lo
+    # padding after the last code is zero and within the buffer
+    assert c0.numel() == ndq.ndq_packed_bytes(n, 2) and c1.numel() == ndq.ndq_packed_bytes(n, 1)
+    assert int(c1[(n + 7) // 8:].sum().item()) == 0 and int(c0[(2 * n + 7) // 8:].sum().item()) == 0
