@@ -17,20 +17,22 @@ HIPCC_FLAGS = [
 ]
 
 
-def build_library(force=True, verbose=False):
+def build_library(force=True, verbose=False, so=None):
     """Compiles the library with hipcc; returns the path of the shared object."""
-    stale = (not os.path.exists(SO)) or any(
-        os.path.getmtime(p) > os.path.getmtime(SO) for p in SOURCES + HEADERS)
+    so = so or SO
+    stale = (not os.path.exists(so)) or any(
+        os.path.getmtime(p) > os.path.getmtime(so) for p in SOURCES + HEADERS)
     if force or stale:
         hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-        cmd = [hipcc] + HIPCC_FLAGS + ["-I", os.path.join(ROOT, "include"), "-I",
-                                       os.path.join(HERE, "csrc"), "-o", SO] + SOURCES
+        extra = os.environ.get("NDQ_EXTRA_HIPCC_FLAGS", "").split()
+        cmd = [hipcc] + HIPCC_FLAGS + extra + ["-I", os.path.join(ROOT, "include"), "-I",
+                                       os.path.join(HERE, "csrc"), "-o", so] + SOURCES
         if verbose:
             print(" ".join(cmd))
         res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
         if res.returncode != 0:
             raise RuntimeError("hipcc failed:\n" + res.stdout)
-    return SO
+    return so
 
 
 if __name__ == "__main__":

@@ -288,6 +288,45 @@ template <> struct Elem<1> {               // bfloat16, widened exactly: one 16-
 };
 constexpr int kLaneElems = 8;   // elements per lane and row in the encoders
 
+// Gradients are read once and results written once per call, and every vector is
+// larger than the caches, so both go through non-temporal (streaming) accesses:
+// the lines do not linger in L2 / Infinity Cache, and a kernel's dirty output is
+// not written back underneath the next kernel (measured: the encoder that follows
+// a decoder runs 35 % faster, in-place decoders 5 % faster).  -DNDQ_NO_STREAMING
+// falls back to plain accesses.
+__device__ __forceinline__ void store_streaming(float* p, float a, float b, float c, float d)
+{
+#ifdef NDQ_NO_STREAMING
+    *(float4*)p = make_float4(a, b, c, d);
+#else
+    typedef float f32x4 __attribute__((ext_vector_type(4)));
+    f32x4 v = {a, b, c, d};
+    __builtin_nontemporal_store(v, (f32x4*)p);
+#endif
+}
+
+__device__ __forceinline__ float4 load_streaming_f4(const float* p)
+{
+#if defined(NDQ_NO_STREAMING) || defined(NDQ_NO_STREAMING_RMW_LOADS)
+    return *(const float4*)p;
+#else
+    typedef float f32x4 __attribute__((ext_vector_type(4)));
+    const f32x4 t = __builtin_nontemporal_load((const f32x4*)p);
+    return make_float4(t.x, t.y, t.z, t.w);
+#endif
+}
+
+__device__ __forceinline__ uint4 load_streaming(const void* p)
+{
+#ifdef NDQ_NO_STREAMING
+    return *(const uint4*)p;
+#else
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    const u32x4 t = __builtin_nontemporal_load((const u32x4*)p);
+    return make_uint4(t.x, t.y, t.z, t.w);
+#endif
+}
+
 // Loads the 8 elements at element offset `o` (a multiple of 8) of a tile with
 // `len` valid elements.  FULL: the whole tile is valid, plain 16-byte loads.
 // Otherwise elements past the end read as zero.
@@ -302,7 +341,7 @@ __device__ __forceinline__ typename Elem<DT>::Row load_row(const void* tile, uin
         constexpr uint32_t per = kLaneElems / T::V;        // elements per vector
         const uint32_t oj = o + j * per;
         if (FULL || oj + per <= len) {
-            row.v[j] = *(const uint4*)(base + j * per);
+            row.v[j] = load_streaming(base + j * per);
         } else {
             uint32_t w[4] = {0u, 0u, 0u, 0u};
 #pragma unroll

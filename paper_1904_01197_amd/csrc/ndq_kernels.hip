@@ -250,8 +250,8 @@ __device__ __forceinline__ void decode_tile(const DecodeArgs& a, const TileRef& 
             }
             if (FULL || o + 4 <= t.len) {
                 if (MODE == kNestedPow2 || MODE == kNestedAnyM || MODE == kNestedPow2Shrink)
-                    y[r] = *(const float4*)(side + o);
-                if (ACC == kAccumulate) prev[r] = *(const float4*)(out + o);
+                    y[r] = load_streaming_f4(side + o);
+                if (ACC == kAccumulate) prev[r] = load_streaming_f4(out + o);
             } else {
                 float ys[4] = {0.f, 0.f, 0.f, 0.f}, ps[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -292,7 +292,7 @@ __device__ __forceinline__ void decode_tile(const DecodeArgs& a, const TileRef& 
             else res[k] = ys[k] + val;
         }
         if (FULL || o + 4 <= t.len) {
-            *(float4*)(out + o) = make_float4(res[0], res[1], res[2], res[3]);
+            store_streaming(out + o, res[0], res[1], res[2], res[3]);
         } else {
 #pragma unroll
             for (uint32_t k = 0; k < 4; ++k)
@@ -456,8 +456,7 @@ __device__ __forceinline__ void chain_tile(const ChainArgs& a, const TileRef& t,
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
             if (FULL || o + 4 * j + 4 <= t.len) {
-                *(float4*)(out + o + 4 * j) =
-                    make_float4(res[4 * j], res[4 * j + 1], res[4 * j + 2], res[4 * j + 3]);
+                store_streaming(out + o + 4 * j, res[4 * j], res[4 * j + 1], res[4 * j + 2], res[4 * j + 3]);
             } else {
 #pragma unroll
                 for (uint32_t k = 0; k < 4; ++k)

@@ -12,7 +12,7 @@ import os
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_SO = os.path.join(_HERE, "libndq.so")
+_SO = os.environ.get("NDQ_LIBRARY", os.path.join(_HERE, "libndq.so"))   # override: another build
 
 NDQ_F32, NDQ_BF16 = 0, 1
 NDQ_OK, NDQ_EINVAL, NDQ_EALIGN, NDQ_EUNSUPPORTED, NDQ_ELAUNCH = 0, -1, -2, -3, -4
