@@ -17,20 +17,22 @@ constexpr int kWave = 64;           // CDNA wavefront
 #endif
 constexpr int kWavesPerBlock = NDQ_WAVES_PER_BLOCK;   // waves of a workgroup work independently
 constexpr int kBlock = kWave * kWavesPerBlock;
-#ifndef NDQ_DEC_ROWS_STREAM
-#define NDQ_DEC_ROWS_STREAM 8
-#endif
-#ifndef NDQ_DEC_ROWS_UPDATE
-#define NDQ_DEC_ROWS_UPDATE 1
-#endif
 // Encoder tile: eight 16-byte loads in flight per lane (4096 bfloat16 or 2048
 // binary32 elements per wave), the largest bucket whose max-norm one wave reduces.
 constexpr int kEncLoads = 8;
-// 16-byte stores per lane and decoder tile.  A decoder that only writes values
-// (DQSG, no accumulate) is bound by load latency per wave and wants long tiles;
-// one that also reads values (side information, running sum) moves twice the
-// bytes per element and measures fastest when a wave covers 1 KB at a time, so
-// that the reads and writes in flight on the chip stay within a few MB of HBM.
+#ifndef NDQ_DEC_ROWS_STREAM
+#define NDQ_DEC_ROWS_STREAM 4
+#endif
+#ifndef NDQ_DEC_ROWS_UPDATE
+#define NDQ_DEC_ROWS_UPDATE 4
+#endif
+// 16-byte stores per lane and decoder tile, for decoders that only write values
+// (DQSG, no accumulate) and for those that also read values (side information,
+// running sum).  Measured at n = 2^27 with streaming accesses: 4 rows (4 KB of
+// values per wave) is fastest for both -- 82 us against 106 us with 8 rows for the
+// store-only decoder, 167 us against 171 (2 rows), 174 (8) and 176 (1) for the
+// in-place nested decoder.  Short tiles keep the reads and writes in flight on
+// the chip within a few MB of HBM; very short ones pay per-wave overhead.
 constexpr int kDecRowsStream = NDQ_DEC_ROWS_STREAM;
 constexpr int kDecRowsUpdate = NDQ_DEC_ROWS_UPDATE;
 
