@@ -113,7 +113,9 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     torch.cuda.set_device(0)
-    ndq.lib()   # fail loudly if the HIP library is missing
+    from paper_1904_01197_amd.build import ensure_built
+    ensure_built()   # compiles only when no built library is there
+    ndq.lib()        # fail loudly if the HIP library cannot be loaded
 
     wl = workloads.CONFIGS[args.workload]
     n = args.n or wl.n

@@ -35,5 +35,12 @@ def build_library(force=True, verbose=False, so=None):
     return so
 
 
+def ensure_built():
+    """Builds the library only if no built one is there (a fresh checkout)."""
+    if not os.path.exists(SO):
+        build_library(force=True)
+    return SO
+
+
 if __name__ == "__main__":
     print(build_library(force=True, verbose=True))

@@ -15,3 +15,11 @@ def pytest_configure(config):
 @pytest.fixture(scope="session")
 def golden_dir():
     return os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+
+
+@pytest.fixture(scope="session", autouse=True)
+def _built_library():
+    """A fresh checkout has no libndq.so (it is not under version control): build it
+    once.  A library that is there is used as it is."""
+    from paper_1904_01197_amd.build import ensure_built
+    ensure_built()
