@@ -336,6 +336,13 @@ def main():
         extras.append({"index_entropy_bits_worker0": round(entropy0, 4), "fixed_width_bits": b0})
         del scratch, other_f32
 
+    # ---- practical memory roof: a plain copy (ndq_aggregate, one input, scale 1) ----
+    m = min(n, 1 << 27)
+    spare = torch.empty(m, dtype=torch.float32, device="cuda")
+    copy_ms = timed(lambda: ndq.ndq_aggregate([bufs.total[:m]], 1.0, spare), 10)
+    copy_gbps = 8.0 * m / (copy_ms * 1e-3) / 1e9
+    del spare
+
     # ---- CPU baseline: the oracle, as it stands, on a bounded sample ------------
     cpu = None
     if not args.no_cpu:
@@ -368,6 +375,8 @@ def main():
         "gelem_per_s": round(wl.W * n / (ms_per_step * 1e-3) / 1e9, 3),
         "step_algorithmic_bytes": step_bytes,
         "step_hbm_frac_of_peak": round(step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+        "device_copy_GBps": round(copy_gbps, 1),
+        "step_frac_of_device_copy": round(step_bytes / (ms_per_step * 1e-3) / 1e9 / copy_gbps, 4),
         "roofline": roofline,
         "cpu_baseline": cpu,
         "kernels": kernels,

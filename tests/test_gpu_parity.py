@@ -366,6 +366,31 @@ def test_config5_heavy_tail_bf16_reduced_size():
     assert np.array_equal(out, ref)
 
 
+def test_config5_diagnostics_clip_and_coset_error_fractions():
+    """Untimed diagnostics of the benchmark workload on a 2^22-element sample: how
+    many DQSG indices saturate (even level count: the positive end clips) and how
+    often a nested worker's coarse bin is resolved wrongly (Thm 4's event); wrong
+    decodes are off by exact multiples of M fine steps."""
+    wl = workloads.CONFIGS[5]
+    n = 1 << 22
+    host, c_ref, s_ref, ds_o, bufs, ds_g = _run_both(wl, n)
+    q0 = oracle.fine_indices(host[0], wl.bucket, s_ref[0], ds_o[0])
+    L = wl.plan[0][1]
+    clip = np.mean((q0 < -(L // 2)) | (q0 > -(L // 2) + L - 1))
+    ref, idx = opipe.decode_chain(wl.plan, wl.bucket, n, c_ref, s_ref, ds_o, wl.out_scale, True)
+    rates = []
+    for w in range(1, wl.W):
+        q_true = oracle.fine_indices(host[w], wl.bucket, s_ref[w], ds_o[w])
+        wrong = idx[w] != q_true
+        assert np.all((idx[w] - q_true)[wrong] % wl.plan[w][1] == 0)
+        rates.append(wrong.mean())
+    print("config 5 (n=2^22 sample): clip fraction of worker 0 = %.2e; coset decode error "
+          "fraction per nested worker = %s" % (clip, ["%.2e" % r for r in rates]))
+    assert clip < 0.01 and max(rates) < 0.05
+    out = pipeline.decode_chain_fused(wl, n, bufs, ds_g).cpu().numpy()
+    assert np.array_equal(out, ref)
+
+
 def test_config5_full_size_sampled_slices():
     """Config 5 at its full size (n = 2^27 per worker) in the launch configuration
     the benchmark times (all encodes, then the fused server loop) and in the
