@@ -782,3 +782,40 @@ def test_vector_longer_than_2_pow_32_elements():
     # padding after the last code is zero and within the buffer
     assert c0.numel() == ndq.ndq_packed_bytes(n, 2) and c1.numel() == ndq.ndq_packed_bytes(n, 1)
     assert int(c1[(n + 7) // 8:].sum().item()) == 0 and int(c0[(2 * n + 7) // 8:].sum().item()) == 0
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_extreme_magnitudes_denormals_and_signed_zeros(dtype):
+    """Log-uniform magnitudes over the whole exponent range, denormals, +-0: every
+    rounding on the GPU is the oracle's (no flush to zero, correctly rounded
+    division, no contraction), including indices that saturate and coset searches
+    far outside any sensible range."""
+    n = 3 * 4096 + 100
+    rng = np.random.default_rng(99)
+    expo = rng.uniform(-44, 37, n)
+    g32 = (rng.choice([-1.0, 1.0], n) * 10.0 ** expo).astype(F)
+    g32[::17] = 0.0
+    g32[1::17] = -0.0
+    g32[2::17] = F(1e-45)                                # smallest denormal
+    g = workloads.f32_to_bf16_bits(g32) if dtype == "bf16" else g32
+    gd = _to_dev(g)
+    side32 = (rng.choice([-1.0, 1.0], n) * 10.0 ** rng.uniform(-40, 30, n)).astype(F)
+    side_d = _to_dev(side32)
+    d_o, d_g = oracle.dither(3, 1, 2), ndq.ndq_dither(3, 1, 2, 0)
+    for bucket, delta in ((4096, 0.0), (64, 0.0), (0, 0.0), (0, 1e-30), (0, 1e30), (0, 1.0)):
+        for levels in (3, 4, 256):
+            c_ref, s_ref = oracle.dq_encode(g, delta, levels, bucket, d_o)
+            codes, steps = ndq.ndq_dq_encode(gd, delta, levels, bucket, d_g)
+            assert np.array_equal(steps.cpu().numpy(), s_ref), (bucket, delta, levels)
+            assert codes.cpu().numpy().tobytes() == c_ref.tobytes(), (bucket, delta, levels)
+            ref = oracle.dq_decode(c_ref, n, levels, bucket, s_ref, d_o)
+            out = ndq.ndq_dq_decode(codes, n, levels, bucket, steps, d_g)
+            assert np.array_equal(out.cpu().numpy(), ref, equal_nan=True), (bucket, delta, levels)
+        for M, alpha in ((2, 1.0), (4, 1.0), (3, 1.0), (4, 0.75), (256, 1.0)):
+            c_ref, s_ref = oracle.nested_encode(g, delta, 16, M, bucket, d_o, alpha=alpha)
+            codes, steps = ndq.ndq_nested_encode(gd, delta, 16, M, alpha, bucket, d_g)
+            assert np.array_equal(steps.cpu().numpy(), s_ref), (bucket, delta, M)
+            assert codes.cpu().numpy().tobytes() == c_ref.tobytes(), (bucket, delta, M)
+            ref = oracle.nested_decode(c_ref, n, M, bucket, s_ref, d_o, side32, 0.5, alpha=alpha)
+            out = ndq.ndq_nested_decode(codes, n, M, alpha, bucket, steps, d_g, side_d, 0.5)
+            assert np.array_equal(out.cpu().numpy(), ref, equal_nan=True), (bucket, delta, M, alpha)
