@@ -776,6 +776,34 @@ def test_nested_side_scale_and_accumulate_implement_the_running_mean():
     assert np.array_equal(g2_a, g2_b)
 
 
+def test_algorithm_2_sum_has_the_noise_of_w_dithered_quantizers():
+    """Algorithm 2 end to end (oracle pipeline): with side information good enough
+    that coset errors are rare, every worker -- DQSG or nested -- contributes its
+    gradient plus an independent uniform error, so the decoded sum differs from
+    the true sum by noise of variance W Delta^2/12 while the nested workers send
+    log2(M) instead of log2(L) bits (abstract; Thm 4 with alpha = 1)."""
+    from oracle import pipeline as opipe
+    n, W, L, M = 1 << 19, 6, 64, 8
+    rng = np.random.default_rng(41)
+    common = rng.standard_normal(n) * 0.01
+    gs = [(common + rng.standard_normal(n) * 0.0004).astype(F) for _ in range(W)]
+    plan = (("dq", L),) + (("nested", M),) * (W - 1)
+    ds = opipe.dithers(W, list(range(W)), step=2)
+    codes, steps, delta = opipe.encode_all(plan, L, 0, True, gs, ds)
+    S, idx = opipe.decode_chain(plan, 0, n, codes, steps, ds, 1.0, want_indices=True)
+    wrong = 0.0
+    for w in range(1, W):
+        wrong += np.mean(idx[w] != oracle.fine_indices(gs[w], 0, steps[w], ds[w]))
+    assert wrong / (W - 1) < 1e-4                       # coset errors are negligible here
+    true_sum = np.sum(np.array(gs, dtype=np.float64), axis=0)
+    err = S.astype(np.float64) - true_sum
+    assert abs(err.mean()) < 4 * math.sqrt(W / 12 / n) * delta
+    assert abs(np.mean(err ** 2) / (W * delta ** 2 / 12) - 1) < 0.02
+    assert abs(np.corrcoef(err, true_sum)[0, 1]) < 5 / math.sqrt(n)
+    # bits on the wire per element: 6 for the DQSG worker, 3 for each nested one
+    assert codes[0].size * 8 // n == 6 and all(c.size * 8 // n == 3 for c in codes[1:])
+
+
 # --------------------------------------------------------------------------
 # aggregation (Algorithm 1 server: average of the reconstructed gradients)
 # --------------------------------------------------------------------------
