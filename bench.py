@@ -333,6 +333,10 @@ def main():
                   lambda: ndq.ndq_nested_decode(ca, n, M1, 0.9, wl.bucket, sa, ds[1], scratch, 1.0,
                                                 scratch, True),
                   pk1 + 4 * K + 8 * n, "shrinkage alpha = 0.9, running sum updated in place")
+        parts = [torch.empty(n, dtype=torch.float32, device="cuda").normal_() for _ in range(4)]
+        extra("aggregate_w4", lambda: ndq.ndq_aggregate(parts, 0.25, scratch), 20 * n,
+              "mean of four separately decoded gradients")
+        del parts
         extras.append({"index_entropy_bits_worker0": round(entropy0, 4), "fixed_width_bits": b0})
         del scratch, other_f32
 

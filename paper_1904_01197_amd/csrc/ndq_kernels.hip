@@ -505,7 +505,7 @@ __global__ __launch_bounds__(kBlock) void aggregate_kernel(AggArgs a)
             float4 x[8];
 #pragma unroll
             for (uint32_t j = 0; j < 8; ++j)
-                if (w0 + j < a.W) x[j] = *(const float4*)(a.g[w0 + j] + i);
+                if (w0 + j < a.W) x[j] = load_streaming_f4(a.g[w0 + j] + i);
 #pragma unroll
             for (uint32_t j = 0; j < 8; ++j)
                 if (w0 + j < a.W) {
@@ -514,7 +514,7 @@ __global__ __launch_bounds__(kBlock) void aggregate_kernel(AggArgs a)
                 }
         }
         if (a.finish) { acc.x = a.scale * acc.x; acc.y = a.scale * acc.y; acc.z = a.scale * acc.z; acc.w = a.scale * acc.w; }
-        *(float4*)(a.out + i) = acc;
+        store_streaming(a.out + i, acc.x, acc.y, acc.z, acc.w);
     } else {
         for (uint64_t e = i; e < a.n; ++e) {
             float acc = a.continue_sum ? a.out[e] : 0.0f;
