@@ -218,6 +218,26 @@ def test_decode_subtracts_the_dither_with_the_right_sign():
     assert oracle.dq_value_f64(code, 2.0, 0.25, 9) == 3.5
 
 
+def test_dqsg_decode_accumulates_into_a_running_sum():
+    """Algorithm 1 server: the reconstructions are summed; decoding with an
+    existing buffer adds g~ to it (one binary32 addition per element)."""
+    n = 10000
+    rng = np.random.default_rng(6)
+    g = (rng.standard_normal(n) * 0.01).astype(F)
+    d = oracle.dither(2, 2, 2)
+    codes, steps = oracle.dq_encode(g, 0.0, 16, 512, d)
+    plain = oracle.dq_decode(codes, n, 16, 512, steps, d)
+    base = (rng.standard_normal(n) * 0.01).astype(F)
+    acc = oracle.dq_decode(codes, n, 16, 512, steps, d, out=base.copy())
+    assert np.array_equal(acc, base + plain) and not np.array_equal(acc, plain)
+    # two workers summed the same way equal the aggregate of their reconstructions
+    d2 = oracle.dither(3, 2, 3)
+    codes2, steps2 = oracle.dq_encode(base, 0.0, 16, 512, d2)
+    total = oracle.dq_decode(codes2, n, 16, 512, steps2, d2, out=plain.copy())
+    assert np.array_equal(total, oracle.aggregate(
+        [plain, oracle.dq_decode(codes2, n, 16, 512, steps2, d2)], 1.0))
+
+
 def test_decoded_float32_is_within_2pow20_step_of_the_exact_value():
     """The binary32 reconstruction (two rounded operations) against the exact
     definition in binary64.  |q - v| <= 8.5, so the subtraction errs by at most
