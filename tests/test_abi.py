@@ -115,3 +115,20 @@ def test_parameter_selection_helpers_agree_with_oracle():
                     oracle.decode_error_bound(d1, M, alpha, s2)
     assert ndq.ndq_alpha_for_equal_variance(1.0, 0.05) == 0.0
     assert ndq.ndq_sqdiff_workspace() % 8 == 0 and ndq.ndq_sqdiff_workspace() >= 8
+
+
+def test_header_is_plain_c99(tmp_path):
+    """The boundary is a C ABI: the header must compile as strict C99 on its own."""
+    import subprocess
+    src = tmp_path / "use_ndq.c"
+    src.write_text('#include "ndq.h"\nint main(void) { ndq_dither d = {0, 0, 0, 0}; ndq_worker w;\n'
+                   '  w.codes = 0; w.steps = 0; w.kind = NDQ_WORKER_DQ; w.levels_or_M = 4; w.alpha = 1.0f;\n'
+                   '  w.dither = d; return (int)ndq_code_bits(w.levels_or_M) - 2 + NDQ_OK; }\n')
+    subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only",
+                           "-I", os.path.join(ROOT, "include"), str(src)])
+    # and it links against the built library
+    exe = tmp_path / "use_ndq"
+    libdir = os.path.join(ROOT, "paper_1904_01197_amd")
+    subprocess.check_call(["gcc", "-std=c99", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe),
+                           "-L", libdir, "-l:libndq.so", "-Wl,-rpath," + libdir])
+    assert subprocess.call([str(exe)]) == 0
