@@ -1,0 +1,535 @@
+// libndq, server side (gfx950): DQSG / NDQSG decoders, the fused server loop of
+// Algorithm 2, aggregation.  See include/ndq.h for the contract.
+#include <hip/hip_runtime.h>
+
+#include "ndq.h"
+#include "ndq_device.hpp"
+#include "ndq_host.hpp"
+
+namespace ndq {
+
+// ---------------------------------------------------------------------------
+// Decoder: Algorithm 1 server block (DQSG) / Algorithm 2 server loop (NDQSG)
+// ---------------------------------------------------------------------------
+struct DecodeArgs {
+    const unsigned char* codes;
+    const float* steps;
+    const float* side;     // nested modes
+    float* out;
+    Tiling tl;
+    uint64_t index0;
+    DitherStream ds;
+    Quant qp;
+    float side_scale;
+};
+
+template <int ROWS> struct DecTile { static constexpr uint32_t N = kWave * 4 * ROWS; };  // outputs per wave
+template <int MODE, int ACC> struct DecRows {
+    static constexpr int R = ((MODE == kDq || MODE == kDqHalf) && ACC == 0) ? kDecRowsStream : kDecRowsUpdate;
+};
+
+enum Acc { kStore = 0, kAccumulate = 1, kAccumulateInPlace = 2 };  // in place: out == side
+
+// One wave decodes one tile.  FULL: every element valid, no guards.  STRADDLE:
+// the code width does not divide 8, so four codes may cross a 32-bit word.
+template <int MODE, int ACC, bool FULL, bool STRADDLE>
+__device__ __forceinline__ void decode_tile(const DecodeArgs& a, const TileRef& t, int lane)
+{
+    const uint32_t bits = a.qp.bits;
+    const uint32_t* codes32 = (const uint32_t*)(a.codes + (t.start >> 3) * bits);
+    const float* side = a.side + t.start;
+    float* out = a.out + t.start;
+    const float step = a.steps[t.bucket];
+    const float inv = a.qp.alpha * inv_step(step);
+    const uint64_t block0 = (a.index0 + t.start) >> 2;
+
+    constexpr int kDecRows = DecRows<MODE, ACC>::R;
+    uint32_t packed[kDecRows];
+    float4 y[kDecRows], prev[kDecRows];
+#pragma unroll
+    for (int r = 0; r < kDecRows; ++r) {
+        const uint32_t o = (uint32_t)r * kWave * 4 + (uint32_t)lane * 4;
+        packed[r] = 0;
+        y[r] = make_float4(0.f, 0.f, 0.f, 0.f);
+        prev[r] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (FULL || o < t.len) {
+            const uint32_t bit = o * bits;
+            const uint32_t w = bit >> 5, sh = bit & 31u;
+            if (STRADDLE) {
+                // read the next word only if a valid code reaches into it (a ragged
+                // tail must not touch memory past the stream)
+                const uint32_t ncodes = FULL ? 4u : (t.len - o < 4u ? t.len - o : 4u);
+                uint64_t window = codes32[w];
+                if (sh + ncodes * bits > 32u) window |= (uint64_t)codes32[w + 1] << 32;
+                packed[r] = (uint32_t)(window >> sh);
+            } else {
+                packed[r] = codes32[w] >> sh;
+            }
+            if (FULL || o + 4 <= t.len) {
+                if (MODE == kNestedPow2 || MODE == kNestedAnyM || MODE == kNestedPow2Shrink)
+                    y[r] = load_streaming_f4(side + o);
+                if (ACC == kAccumulate) prev[r] = load_streaming_f4(out + o);
+            } else {
+                float ys[4] = {0.f, 0.f, 0.f, 0.f}, ps[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (uint32_t k = 0; k < 4; ++k)
+                    if (o + k < t.len) {
+                        if (MODE == kNestedPow2 || MODE == kNestedAnyM || MODE == kNestedPow2Shrink)
+                            ys[k] = side[o + k];
+                        if (ACC == kAccumulate) ps[k] = out[o + k];
+                    }
+                y[r] = make_float4(ys[0], ys[1], ys[2], ys[3]);
+                prev[r] = make_float4(ps[0], ps[1], ps[2], ps[3]);
+            }
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < kDecRows; ++r) {
+        const uint32_t o = (uint32_t)r * kWave * 4 + (uint32_t)lane * 4;
+        if (!FULL && o >= t.len) continue;
+        float v[4] = {0.f, 0.f, 0.f, 0.f};
+        if (MODE != kDqHalf) dither4(a.ds, block0 + (o >> 2), v);
+        const float ys[4] = {y[r].x, y[r].y, y[r].z, y[r].w};
+        const float ps[4] = {prev[r].x, prev[r].y, prev[r].z, prev[r].w};
+        float res[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const uint32_t c = __builtin_amdgcn_ubfe(packed[r], k * bits, bits);   // bit-field extract
+            float q, yk = 0.0f;
+            if (MODE == kDq || MODE == kDqHalf) {
+                q = (float)((int32_t)c + a.qp.q_min);
+            } else {
+                yk = ys[k] * a.side_scale;
+                q = coset_index_f<MODE>(c, yk, inv, v[k], a.qp);
+            }
+            const float val = (MODE == kDqHalf) ? step * q
+                                                : shrink<MODE>(index_value(q, step, v[k]), yk, a.qp);
+            if (ACC == kStore) res[k] = val;
+            else if (ACC == kAccumulate) res[k] = ps[k] + val;
+            else res[k] = ys[k] + val;
+        }
+        if (FULL || o + 4 <= t.len) {
+            store_streaming(out + o, res[0], res[1], res[2], res[3]);
+        } else {
+#pragma unroll
+            for (uint32_t k = 0; k < 4; ++k)
+                if (o + k < t.len) out[o + k] = res[k];
+        }
+    }
+}
+
+template <int MODE, int ACC, bool STRADDLE>
+__global__ __launch_bounds__(kBlock) void decode_kernel(DecodeArgs a)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    const uint32_t tile_id =
+        blockIdx.x * kWavesPerBlock + __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    constexpr uint32_t TILE = DecTile<DecRows<MODE, ACC>::R>::N;
+    const TileRef t = locate_tile(a.tl, tile_id, TILE);
+    if (t.len == TILE) decode_tile<MODE, ACC, true, STRADDLE>(a, t, lane);
+    else if (t.len != 0) decode_tile<MODE, ACC, false, STRADDLE>(a, t, lane);
+}
+
+// ---------------------------------------------------------------------------
+// Chain decoder: the whole server loop of Algorithm 2 in one pass.  The running
+// sum of a lane's elements lives in registers while the workers are folded in
+// one after the other; the next worker's code words and step are prefetched
+// while the current worker's dither is generated.
+// ---------------------------------------------------------------------------
+constexpr uint32_t kChainMax = 32;    // workers per launch
+#ifndef NDQ_CHAIN_ROWS
+#define NDQ_CHAIN_ROWS 2
+#endif
+constexpr int kChainRows = NDQ_CHAIN_ROWS;   // rows of 8 elements per lane and tile
+constexpr uint32_t kChainTile = kWave * kLaneElems * kChainRows;
+
+struct ChainWorker {
+    const unsigned char* codes;
+    const float* steps;
+    uint64_t index0;
+    DitherStream ds;
+    int32_t q_min;
+    uint32_t M;
+    float M_f, inv_M_f;
+    float alpha, beta;    // nested: shrinkage factor and 1 - alpha^2
+    float side_scale;     // 1/(workers folded in before this one); 0 for the first
+    uint32_t bits;
+    uint32_t mode;        // Mode
+    uint32_t first;       // S <- value instead of S + value
+};
+
+struct ChainArgs {
+    ChainWorker w[kChainMax];
+    float* out;
+    Tiling tl;
+    uint32_t W;
+    int continue_sum;     // S starts from out (an earlier group of workers)
+    int apply_scale;
+    float scale;
+};
+
+// What is prefetched per worker: the step and, per row, the words holding the
+// lane's eight codes (8*bits bits starting at a multiple of 8 bits).
+struct ChainFetch {
+    uint32_t w0[kChainRows], w1[kChainRows], w2[kChainRows];
+    float step;
+};
+
+template <bool FULL>
+__device__ __forceinline__ void chain_fetch(const ChainWorker& cw, const TileRef& t, int lane,
+                                            ChainFetch& f)
+{
+    const uint32_t bits = cw.bits;
+    const uint32_t* codes32 = (const uint32_t*)(cw.codes + (t.start >> 3) * bits);
+    f.step = cw.steps[t.bucket];
+#pragma unroll
+    for (int r = 0; r < kChainRows; ++r) {
+        const uint32_t o = (uint32_t)(r * kWave + lane) * kLaneElems;
+        f.w0[r] = 0; f.w1[r] = 0; f.w2[r] = 0;
+        if (FULL || o < t.len) {
+            const uint32_t bit = o * bits;                     // multiple of 8
+            const uint32_t w = bit >> 5, sh = bit & 31u;
+            // bits used from word w on; a ragged tail only counts its valid codes so
+            // that no word past the stream is touched
+            const uint32_t ncodes = FULL ? 8u : (t.len - o < 8u ? t.len - o : 8u);
+            const uint32_t end = sh + ncodes * bits;
+            f.w0[r] = codes32[w];
+            if (end > 32u) f.w1[r] = codes32[w + 1];
+            if (end > 64u) f.w2[r] = codes32[w + 2];
+        }
+    }
+}
+
+template <int MODE>
+__device__ __forceinline__ void chain_fold(const ChainWorker& cw, const ChainFetch& f,
+                                           uint64_t block0, int lane, float (&S)[kChainRows][8])
+{
+    const uint32_t bits = cw.bits;
+    const float step = f.step;
+    const float inv = cw.alpha * inv_step(step);
+    Quant qp;
+    qp.M = cw.M; qp.M_f = cw.M_f; qp.inv_M_f = cw.inv_M_f; qp.q_min = cw.q_min;
+    qp.alpha = cw.alpha; qp.beta = cw.beta;
+#pragma unroll
+    for (int r = 0; r < kChainRows; ++r) {
+        const uint32_t o = (uint32_t)(r * kWave + lane) * kLaneElems;
+        const uint32_t sh = (o * bits) & 31u;
+        // the lane's 8*bits code bits, in two halves of four codes
+        const uint64_t low = (((uint64_t)f.w1[r] << 32) | f.w0[r]) >> sh;
+        const uint64_t high = sh ? ((uint64_t)f.w2[r] << (64u - sh)) : 0u;
+        const uint64_t chunk = low | high;
+        const uint32_t half[2] = {(uint32_t)chunk, (uint32_t)(chunk >> (4u * bits))};
+        float v[8];
+        dither8(cw.ds, block0 + (o >> 3), v);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const uint32_t c = __builtin_amdgcn_ubfe(half[k >> 2], (k & 3) * bits, bits);   // bit-field extract
+            float q, yk = 0.0f;
+            if (MODE == kDq) {
+                q = (float)((int32_t)c + qp.q_min);
+            } else {
+                yk = S[r][k] * cw.side_scale;
+                q = coset_index_f<MODE>(c, yk, inv, v[k], qp);
+            }
+            const float val = shrink<MODE>(index_value(q, step, v[k]), yk, qp);
+            S[r][k] = (MODE == kDq && cw.first) ? val : S[r][k] + val;
+        }
+    }
+}
+
+template <bool FULL>
+__device__ __forceinline__ void chain_tile(const ChainArgs& a, const TileRef& t, int lane)
+{
+    float S[kChainRows][8];
+    float* out = a.out + t.start;
+#pragma unroll
+    for (int r = 0; r < kChainRows; ++r) {
+        const uint32_t o = (uint32_t)(r * kWave + lane) * kLaneElems;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            S[r][k] = 0.0f;
+            if (a.continue_sum && (FULL || o + k < t.len)) S[r][k] = out[o + k];
+        }
+    }
+    ChainFetch cur;
+    chain_fetch<FULL>(a.w[0], t, lane, cur);
+    ChainFetch nxt = cur;
+    for (uint32_t w = 0; w < a.W; ++w) {
+        const ChainWorker& cw = a.w[w];
+        if (w + 1 < a.W) chain_fetch<FULL>(a.w[w + 1], t, lane, nxt);
+        const uint64_t block0 = (cw.index0 + t.start) >> 3;
+        if (cw.mode == kDq) chain_fold<kDq>(cw, cur, block0, lane, S);
+        else if (cw.mode == kNestedPow2) chain_fold<kNestedPow2>(cw, cur, block0, lane, S);
+        else if (cw.mode == kNestedPow2Shrink) chain_fold<kNestedPow2Shrink>(cw, cur, block0, lane, S);
+        else chain_fold<kNestedAnyM>(cw, cur, block0, lane, S);
+        cur = nxt;
+    }
+#pragma unroll
+    for (int r = 0; r < kChainRows; ++r) {
+        const uint32_t o = (uint32_t)(r * kWave + lane) * kLaneElems;
+        float res[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) res[k] = a.apply_scale ? a.scale * S[r][k] : S[r][k];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            if (FULL || o + 4 * j + 4 <= t.len) {
+                store_streaming(out + o + 4 * j, res[4 * j], res[4 * j + 1], res[4 * j + 2], res[4 * j + 3]);
+            } else {
+#pragma unroll
+                for (uint32_t k = 0; k < 4; ++k)
+                    if (o + 4 * j + k < t.len) out[o + 4 * j + k] = res[4 * j + k];
+            }
+        }
+    }
+}
+
+#ifndef NDQ_CHAIN_WAVES_PER_EU
+#define NDQ_CHAIN_WAVES_PER_EU 6
+#endif
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(NDQ_CHAIN_WAVES_PER_EU)))
+void chain_kernel(ChainArgs a)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    const uint32_t tile_id =
+        blockIdx.x * kWavesPerBlock + __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const TileRef t = locate_tile(a.tl, tile_id, kChainTile);
+    if (t.len == kChainTile) chain_tile<true>(a, t, lane);
+    else if (t.len != 0) chain_tile<false>(a, t, lane);
+}
+
+// ---------------------------------------------------------------------------
+// Aggregation: Algorithm 1 server, "compute the average"
+// ---------------------------------------------------------------------------
+constexpr uint32_t kAggMax = 32;
+struct AggArgs {
+    const float* g[kAggMax];
+    float* out;
+    uint64_t n;
+    uint32_t W;
+    int continue_sum;   // start from out (partial sum of an earlier group of workers)
+    int finish;         // multiply by scale
+    float scale;
+};
+
+__global__ __launch_bounds__(kBlock) void aggregate_kernel(AggArgs a)
+{
+    const uint64_t i4 = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+    const uint64_t i = i4 * 4;
+    if (i >= a.n) return;
+    if (i + 4 <= a.n) {
+        float4 acc = a.continue_sum ? *(const float4*)(a.out + i) : make_float4(0.f, 0.f, 0.f, 0.f);
+        for (uint32_t w0 = 0; w0 < a.W; w0 += 8) {
+            float4 x[8];
+#pragma unroll
+            for (uint32_t j = 0; j < 8; ++j)
+                if (w0 + j < a.W) x[j] = load_streaming_f4(a.g[w0 + j] + i);
+#pragma unroll
+            for (uint32_t j = 0; j < 8; ++j)
+                if (w0 + j < a.W) {
+                    acc.x = acc.x + x[j].x; acc.y = acc.y + x[j].y;
+                    acc.z = acc.z + x[j].z; acc.w = acc.w + x[j].w;
+                }
+        }
+        if (a.finish) { acc.x = a.scale * acc.x; acc.y = a.scale * acc.y; acc.z = a.scale * acc.z; acc.w = a.scale * acc.w; }
+        store_streaming(a.out + i, acc.x, acc.y, acc.z, acc.w);
+    } else {
+        for (uint64_t e = i; e < a.n; ++e) {
+            float acc = a.continue_sum ? a.out[e] : 0.0f;
+            for (uint32_t w = 0; w < a.W; ++w) acc = acc + a.g[w][e];
+            a.out[e] = a.finish ? a.scale * acc : acc;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Host side: dispatch
+// ---------------------------------------------------------------------------
+template <int MODE, int ACC, bool STRADDLE>
+static int run_decode3(DecodeArgs a, uint64_t n, uint32_t bucket, hipStream_t s)
+{
+    const int rc = make_tiling(n, bucket, DecTile<DecRows<MODE, ACC>::R>::N, &a.tl);
+    if (rc != NDQ_OK) return rc;
+    hipLaunchKernelGGL((decode_kernel<MODE, ACC, STRADDLE>), dim3(blocks_for(a.tl.total_tiles)),
+                       dim3(kBlock), 0, s, a);
+    return launched();
+}
+
+template <int MODE, bool STRADDLE>
+static int run_decode2(const DecodeArgs& a, uint64_t n, uint32_t bucket, int acc, hipStream_t s)
+{
+    if (acc == kStore) return run_decode3<MODE, kStore, STRADDLE>(a, n, bucket, s);
+    if (acc == kAccumulate) return run_decode3<MODE, kAccumulate, STRADDLE>(a, n, bucket, s);
+    return run_decode3<MODE, kAccumulateInPlace, STRADDLE>(a, n, bucket, s);
+}
+
+template <int MODE>
+static int run_decode(const DecodeArgs& a, uint64_t n, uint32_t bucket, int acc, hipStream_t s)
+{
+    // four b-bit codes sit inside one 32-bit word exactly when 4b divides 32
+    const bool straddle = (32u % (4u * a.qp.bits)) != 0u;
+    return straddle ? run_decode2<MODE, true>(a, n, bucket, acc, s)
+                    : run_decode2<MODE, false>(a, n, bucket, acc, s);
+}
+
+static int decode_common(const void* codes, size_t n, uint32_t levels, uint32_t M, bool nested,
+                         bool half, float alpha, uint32_t bucket, const float* steps,
+                         const ndq_dither* d,
+                         const float* side, float side_scale, float* out, int accumulate,
+                         void* stream)
+{
+    DecodeArgs a;
+    int rc = make_quant(levels, M, nested, alpha, &a.qp);
+    if (rc != NDQ_OK) return rc;
+    if (!d) return NDQ_EINVAL;
+    if (n == 0) return NDQ_OK;
+    if (!codes || !steps || !out || (nested && !side)) return NDQ_EINVAL;
+    if (n >= kMaxN) return NDQ_EUNSUPPORTED;
+    if (!aligned16(codes) || !aligned16(out) || !aligned4(steps) || (nested && !aligned16(side)))
+        return NDQ_EALIGN;
+    if (bucket % 64u != 0u || (d->offset & 7u) != 0u) return NDQ_EALIGN;
+    if (nested && side != out) {
+        // partial overlap of side and out would race between waves
+        const uintptr_t s0 = (uintptr_t)side, o0 = (uintptr_t)out, len = (uintptr_t)n * 4u;
+        if (s0 < o0 + len && o0 < s0 + len) return NDQ_EINVAL;
+    }
+    a.codes = (const unsigned char*)codes;
+    a.steps = steps;
+    a.side = nested ? side : out;
+    a.out = out;
+    a.index0 = d->offset;
+    a.ds = make_stream(d);
+    a.side_scale = side_scale;
+    hipStream_t s = (hipStream_t)stream;
+    int acc = accumulate ? kAccumulate : kStore;
+    if (nested && accumulate && side == out) acc = kAccumulateInPlace;
+    if (!nested) return half ? run_decode<kDqHalf>(a, n, bucket, acc, s)
+                             : run_decode<kDq>(a, n, bucket, acc, s);
+    if (is_pow2(M) && alpha == 1.0f) return run_decode<kNestedPow2>(a, n, bucket, acc, s);
+    if (is_pow2(M)) return run_decode<kNestedPow2Shrink>(a, n, bucket, acc, s);
+    return run_decode<kNestedAnyM>(a, n, bucket, acc, s);
+}
+
+}  // namespace ndq
+
+extern "C" {
+
+int ndq_dq_decode(const void* codes, size_t n, uint32_t levels, uint32_t bucket,
+                  const float* steps, const ndq_dither* d, float* out, int accumulate,
+                  void* stream)
+{
+    return ndq::decode_common(codes, n, levels, 0u, false, false, 1.0f, bucket, steps, d, nullptr,
+                              1.0f, out, accumulate, stream);
+}
+
+int ndq_dq_decode_half(const void* codes, size_t n, uint32_t levels, uint32_t bucket,
+                       const float* steps, float* out, int accumulate, void* stream)
+{
+    const ndq_dither none = {0u, 0u, 0u, 0u};   // no dither is regenerated
+    return ndq::decode_common(codes, n, levels, 0u, false, true, 1.0f, bucket, steps, &none,
+                              nullptr, 1.0f, out, accumulate, stream);
+}
+
+int ndq_nested_decode(const void* codes, size_t n, uint32_t M, float alpha, uint32_t bucket,
+                      const float* steps, const ndq_dither* d, const float* side,
+                      float side_scale, float* out, int accumulate, void* stream)
+{
+    // `levels` plays no part in decoding: the step travels in `steps`
+    return ndq::decode_common(codes, n, 2u, M, true, false, alpha, bucket, steps, d, side,
+                              side_scale, out, accumulate, stream);
+}
+
+int ndq_aggregate(const float* const* gs, uint32_t W, size_t n, float scale, float* out,
+                  void* stream)
+{
+    using namespace ndq;
+    if (!gs || W < 1u || W > 1024u) return NDQ_EINVAL;
+    if (n == 0) return NDQ_OK;
+    if (!out) return NDQ_EINVAL;
+    if (n >= kMaxN) return NDQ_EUNSUPPORTED;
+    if (!aligned16(out)) return NDQ_EALIGN;
+    for (uint32_t w = 0; w < W; ++w) {
+        if (!gs[w]) return NDQ_EINVAL;
+        if (!aligned16(gs[w])) return NDQ_EALIGN;
+        if (W > kAggMax && gs[w] == out) return NDQ_EINVAL;
+    }
+    const uint64_t threads = (n + 3) / 4;
+    const uint64_t blocks = (threads + kBlock - 1) / kBlock;
+    if (blocks >= ((uint64_t)1 << 31)) return NDQ_EUNSUPPORTED;
+    for (uint32_t w0 = 0; w0 < W; w0 += kAggMax) {
+        AggArgs a;
+        a.W = (W - w0 < kAggMax) ? W - w0 : kAggMax;
+        for (uint32_t j = 0; j < kAggMax; ++j) a.g[j] = j < a.W ? gs[w0 + j] : nullptr;
+        a.out = out;
+        a.n = n;
+        a.continue_sum = w0 != 0u;
+        a.finish = w0 + kAggMax >= W;
+        a.scale = scale;
+        hipLaunchKernelGGL(aggregate_kernel, dim3((uint32_t)blocks), dim3(kBlock), 0,
+                           (hipStream_t)stream, a);
+        if (launched() != NDQ_OK) return NDQ_ELAUNCH;
+    }
+    return NDQ_OK;
+}
+
+int ndq_decode_chain(const ndq_worker* workers, uint32_t W, size_t n, uint32_t bucket,
+                     float scale, float* out, void* stream)
+{
+    using namespace ndq;
+    if (!workers || W < 1u || W > 1024u) return NDQ_EINVAL;
+    if (workers[0].kind != NDQ_WORKER_DQ) return NDQ_EINVAL;   // nothing to decode against yet
+    for (uint32_t p = 0; p < W; ++p) {
+        const ndq_worker& wk = workers[p];
+        if (wk.kind != NDQ_WORKER_DQ && wk.kind != NDQ_WORKER_NESTED) return NDQ_EINVAL;
+        if (wk.levels_or_M < 2u || wk.levels_or_M > 256u) return NDQ_EINVAL;
+        if (wk.kind == NDQ_WORKER_NESTED && !(wk.alpha > 0.0f && wk.alpha <= 1.0f)) return NDQ_EINVAL;
+    }
+    if (n == 0) return NDQ_OK;
+    if (!out) return NDQ_EINVAL;
+    if (n >= kMaxN) return NDQ_EUNSUPPORTED;
+    if (!aligned16(out) || bucket % 64u != 0u) return NDQ_EALIGN;
+    for (uint32_t p = 0; p < W; ++p) {
+        const ndq_worker& wk = workers[p];
+        if (!wk.codes || !wk.steps) return NDQ_EINVAL;
+        if (!aligned16(wk.codes) || !aligned4(wk.steps) || (wk.dither.offset & 7u) != 0u)
+            return NDQ_EALIGN;
+    }
+    ChainArgs a;
+    int rc = make_tiling(n, bucket, kChainTile, &a.tl);
+    if (rc != NDQ_OK) return rc;
+    a.out = out;
+    a.scale = scale;
+    for (uint32_t p0 = 0; p0 < W; p0 += kChainMax) {
+        a.W = (W - p0 < kChainMax) ? W - p0 : kChainMax;
+        a.continue_sum = p0 != 0u;
+        a.apply_scale = (p0 + kChainMax >= W) && scale != 1.0f;
+        for (uint32_t j = 0; j < a.W; ++j) {
+            const ndq_worker& wk = workers[p0 + j];
+            const bool nested = wk.kind == NDQ_WORKER_NESTED;
+            Quant qp;
+            make_quant(nested ? 2u : wk.levels_or_M, wk.levels_or_M, nested, wk.alpha, &qp);
+            ChainWorker& cw = a.w[j];
+            cw.codes = (const unsigned char*)wk.codes;
+            cw.steps = wk.steps;
+            cw.index0 = wk.dither.offset;
+            cw.ds = make_stream(&wk.dither);
+            cw.q_min = qp.q_min;
+            cw.M = qp.M;
+            cw.M_f = qp.M_f;
+            cw.inv_M_f = qp.inv_M_f;
+            cw.alpha = qp.alpha;
+            cw.beta = qp.beta;
+            cw.side_scale = (p0 + j) ? 1.0f / (float)(p0 + j) : 0.0f;
+            cw.bits = qp.bits;
+            cw.mode = !nested ? kDq
+                              : (!is_pow2(wk.levels_or_M) ? kNestedAnyM
+                                 : (wk.alpha == 1.0f ? kNestedPow2 : kNestedPow2Shrink));
+            cw.first = (p0 + j) == 0u;
+        }
+        hipLaunchKernelGGL(chain_kernel, dim3(blocks_for(a.tl.total_tiles)), dim3(kBlock), 0,
+                           (hipStream_t)stream, a);
+        if (launched() != NDQ_OK) return NDQ_ELAUNCH;
+    }
+    return NDQ_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,317 @@
+// libndq, worker side (gfx950): max-norm scale factors, DQSG / NDQSG encoders.
+// See include/ndq.h for the contract.
+//
+// Every kernel of the library is a streaming pass: one wave owns one tile of
+// consecutive elements, issues all of its 16-byte loads up front, regenerates
+// the dither with Philox in registers and writes coalesced vectors.  Nothing
+// is a contraction, so no MFMA; LDS is used only to transpose the small packed
+// codes into stream order.
+#include <hip/hip_runtime.h>
+
+#include "ndq.h"
+#include "ndq_device.hpp"
+#include "ndq_host.hpp"
+
+namespace ndq {
+
+// ---------------------------------------------------------------------------
+// Encoder: Algorithm 1 worker block (DQSG) / Algorithm 2 worker block (NDQSG)
+// ---------------------------------------------------------------------------
+struct EncodeArgs {
+    const void* g;
+    unsigned char* codes;
+    float* steps;          // written (fused / preset) or read (two-pass)
+    Tiling tl;
+    uint64_t index0;       // dither offset of element 0
+    uint64_t total_bytes;  // size of the packed stream incl. zero padding
+    DitherStream ds;
+    Quant qp;
+    float preset_step;     // > 0: bucket == 0 with a caller-set step
+};
+
+template <int DT> struct EncRows { static constexpr int R = kEncLoads / Elem<DT>::V; };
+template <int DT> struct EncTile { static constexpr uint32_t N = kWave * kLaneElems * EncRows<DT>::R; };
+
+// One wave encodes one tile: loads it (all 16-byte loads issued back to back),
+// finds the step, quantizes, and leaves the packed codes in `stage` in stream
+// order.  A lane owns 8 consecutive elements per row: one Philox block, and
+// 8 codes = `bits` whole bytes of the stream.  FULL: every element of the tile
+// is valid -- no guards anywhere.
+template <int DT, int MODE, bool FUSED, bool FULL>
+__device__ __forceinline__ void encode_tile(const EncodeArgs& a, const TileRef& t, uint32_t tile_id,
+                                            unsigned char* stage, int lane)
+{
+    using T = Elem<DT>;
+    constexpr int ROWS = EncRows<DT>::R;
+    const uint32_t bits = a.qp.bits;
+    const typename T::scalar* tile = (const typename T::scalar*)a.g + t.start;
+    typename T::Row raw[ROWS];
+#pragma unroll
+    for (int r = 0; r < ROWS; ++r)
+        raw[r] = load_row<DT, FULL>(tile, (uint32_t)(r * kWave + lane) * kLaneElems, t.len);
+
+    float step;
+    if (FUSED) {
+        // the bucket is this tile: kappa = max|g| in registers (Sec. 3.1 eq. (2))
+        typename T::maxacc m = T::max_init();
+#pragma unroll
+        for (int r = 0; r < ROWS; ++r) m = T::max_update(m, raw[r]);
+        step = step_from_kappa(wave_max(T::max_final(m)), a.qp.levels);
+        if (lane == 0) a.steps[t.bucket] = step;
+    } else if (a.preset_step > 0.0f) {
+        step = a.preset_step;
+        if (tile_id == 0 && lane == 0) a.steps[0] = step;
+    } else {
+        step = a.steps[t.bucket];
+    }
+    const float inv = a.qp.alpha * inv_step(step);   // alpha = 1 unless a nested worker shrinks
+    const uint64_t block0 = (a.index0 + t.start) >> 3;
+
+#pragma unroll
+    for (int r = 0; r < ROWS; ++r) {
+        const uint32_t o = (uint32_t)(r * kWave + lane) * kLaneElems;
+        float v[8];
+        dither8(a.ds, block0 + (o >> 3), v);
+        uint32_t quad[2];
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            uint32_t chunk = 0;
+            if (MODE == kDqNarrow) {
+                // codes of <= 6 bits: sum (q_k - q_min) 2^(k b) stays an exact float below 2^24
+                float acc = a.qp.pack_bias;
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    float q = dq_index_f(T::get(raw[r], 4 * h + k), inv, v[4 * h + k], a.qp);
+                    if (!FULL && o + 4 * h + k >= t.len) q = a.qp.q_min_f;
+                    acc = __builtin_fmaf(q, __uint_as_float((127u + k * bits) << 23), acc);
+                }
+                chunk = (uint32_t)acc;
+            } else {
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    uint32_t c = encode_one<MODE>(T::get(raw[r], 4 * h + k), inv, v[4 * h + k], a.qp);
+                    if (!FULL && o + 4 * h + k >= t.len) c = 0;
+                    chunk |= c << (k * bits);
+                }
+            }
+            quad[h] = chunk;
+        }
+        // eight consecutive codes -> `bits` bytes at byte (o/8)*bits of the tile's stream
+        const uint64_t chunk8 = (uint64_t)quad[0] | ((uint64_t)quad[1] << (4 * bits));
+        unsigned char* p = stage + (o >> 3) * bits;
+        switch (bits) {
+            case 1: *p = (unsigned char)chunk8; break;
+            case 2: *(uint16_t*)p = (uint16_t)chunk8; break;
+            case 4: *(uint32_t*)p = (uint32_t)chunk8; break;
+            case 8: *(uint64_t*)p = chunk8; break;
+            default:
+                for (uint32_t k = 0; k < bits; ++k) p[k] = (unsigned char)(chunk8 >> (8 * k));
+        }
+    }
+    if (lane == 0) *(uint64_t*)(stage + (size_t)EncTile<DT>::N / 8 * bits) = 0;  // pad unit
+}
+
+// FUSED: the bucket fits one tile; its max-norm is reduced in registers and
+// the step is written.  Otherwise the step is the preset one or read from
+// `steps` (filled by absmax_kernel + steps_from_kappa_kernel).
+// Occupancy target.  The bfloat16 encoder is bound by instruction issue with a
+// burst of loads at the start of every tile; eight waves per SIMD (64 registers)
+// hide that burst better than four (+8 % measured).  The binary32 encoder moves
+// twice the bytes per element and measured best with the registers it asks for.
+template <int DT> struct EncWaves { static constexpr int W = DT == 1 ? 8 : 4; };
+template <int DT, int MODE, bool FUSED>
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(EncWaves<DT>::W)))
+void encode_kernel(EncodeArgs a)
+{
+    constexpr uint32_t TILE = EncTile<DT>::N;
+    __shared__ __align__(16) unsigned char stage_all[kWavesPerBlock][TILE + 8];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);   // wave-uniform
+    unsigned char* stage = stage_all[wave];
+
+    const uint32_t tile_id = blockIdx.x * kWavesPerBlock + wave;
+    const TileRef t = locate_tile(a.tl, tile_id, TILE);
+    const uint32_t bits = a.qp.bits;
+    if (t.len == TILE) encode_tile<DT, MODE, FUSED, true>(a, t, tile_id, stage, lane);
+    else if (t.len != 0) encode_tile<DT, MODE, FUSED, false>(a, t, tile_id, stage, lane);
+    __syncthreads();
+    if (t.len != 0) {
+        const uint64_t byte0 = (t.start >> 3) * bits;                 // tile start is a multiple of 64
+        const bool last = t.start + t.len == a.tl.n;
+        const uint64_t nbytes = last ? a.total_bytes - byte0 : (uint64_t)(t.len >> 3) * bits;
+        const uint32_t units = (uint32_t)(nbytes >> 3);
+        uint64_t* dst = (uint64_t*)(a.codes + byte0);
+        const uint64_t* src = (const uint64_t*)stage;
+        for (uint32_t u = lane; u < units; u += kWave) dst[u] = src[u];
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Max-norm per bucket (two-pass path and ndq_absmax)
+// ---------------------------------------------------------------------------
+__global__ void fill_zero_kernel(uint32_t* p, uint64_t n)
+{
+    const uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0u;
+}
+
+template <int DT>
+__global__ __launch_bounds__(kBlock) void absmax_kernel(const void* g, Tiling tl, uint32_t* kappa_bits)
+{
+    using T = Elem<DT>;
+    constexpr uint32_t TILE = EncTile<DT>::N;
+    const int lane = threadIdx.x & (kWave - 1);
+    const uint32_t tile_id =
+        blockIdx.x * kWavesPerBlock + __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const TileRef t = locate_tile(tl, tile_id, TILE);
+    if (t.len == 0) return;
+    const typename T::scalar* tile = (const typename T::scalar*)g + t.start;
+    constexpr int ROWS = EncRows<DT>::R;
+    typename T::Row raw[ROWS];
+    if (t.len == TILE) {
+#pragma unroll
+        for (int r = 0; r < ROWS; ++r)
+            raw[r] = load_row<DT, true>(tile, (uint32_t)(r * kWave + lane) * kLaneElems, t.len);
+    } else {
+#pragma unroll
+        for (int r = 0; r < ROWS; ++r)
+            raw[r] = load_row<DT, false>(tile, (uint32_t)(r * kWave + lane) * kLaneElems, t.len);
+    }
+    typename T::maxacc acc = T::max_init();
+#pragma unroll
+    for (int r = 0; r < ROWS; ++r) acc = T::max_update(acc, raw[r]);
+    const float m = wave_max(T::max_final(acc));
+    // non-negative floats order like their bit patterns
+    if (lane == 0) atomicMax(kappa_bits + t.bucket, __float_as_uint(m));
+}
+
+__global__ void steps_from_kappa_kernel(float* steps, uint64_t K, uint32_t levels)
+{
+    const uint64_t b = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (b < K) steps[b] = step_from_kappa(steps[b], levels);
+}
+
+// ---------------------------------------------------------------------------
+// Host side: dispatch
+// ---------------------------------------------------------------------------
+template <int DT>
+static int run_absmax(const void* g, const Tiling& tl, uint64_t K, float* kappa, hipStream_t s)
+{
+    hipLaunchKernelGGL(fill_zero_kernel, dim3((uint32_t)((K + 255) / 256)), dim3(256), 0, s,
+                       (uint32_t*)kappa, K);
+    if (launched() != NDQ_OK) return NDQ_ELAUNCH;
+    hipLaunchKernelGGL(absmax_kernel<DT>, dim3(blocks_for(tl.total_tiles)), dim3(kBlock), 0, s, g, tl,
+                       (uint32_t*)kappa);
+    return launched();
+}
+
+template <int DT, int MODE>
+static int run_encode(const EncodeArgs& a, bool fused, hipStream_t s)
+{
+    const dim3 grid(blocks_for(a.tl.total_tiles)), block(kBlock);
+    if (fused) hipLaunchKernelGGL((encode_kernel<DT, MODE, true>), grid, block, 0, s, a);
+    else hipLaunchKernelGGL((encode_kernel<DT, MODE, false>), grid, block, 0, s, a);
+    return launched();
+}
+
+static int encode_common(const void* g, ndq_dtype dt, size_t n, float delta, uint32_t levels,
+                         uint32_t M, bool nested, float alpha, uint32_t bucket, const ndq_dither* d,
+                         void* codes_out, float* steps_out, void* stream)
+{
+    EncodeArgs a;
+    int rc = make_quant(levels, M, nested, alpha, &a.qp);
+    if (rc != NDQ_OK) return rc;
+    if (dt != NDQ_F32 && dt != NDQ_BF16) return NDQ_EINVAL;
+    if (!d) return NDQ_EINVAL;
+    if (n == 0) return NDQ_OK;
+    if (!g || !codes_out || !steps_out) return NDQ_EINVAL;
+    if (!(delta == delta)) return NDQ_EINVAL;
+    if (n >= kMaxN) return NDQ_EUNSUPPORTED;
+    if (!aligned16(g) || !aligned16(codes_out) || !aligned4(steps_out)) return NDQ_EALIGN;
+    if (bucket % 64u != 0u || (d->offset & 7u) != 0u) return NDQ_EALIGN;
+
+    const uint32_t tile = dt == NDQ_F32 ? EncTile<0>::N : EncTile<1>::N;
+    rc = make_tiling(n, bucket, tile, &a.tl);
+    if (rc != NDQ_OK) return rc;
+    a.g = g;
+    a.codes = (unsigned char*)codes_out;
+    a.steps = steps_out;
+    a.index0 = d->offset;
+    a.total_bytes = packed_bytes(n, a.qp.bits);
+    a.ds = make_stream(d);
+    a.preset_step = (bucket == 0u && delta > 0.0f) ? delta : 0.0f;
+    hipStream_t s = (hipStream_t)stream;
+
+    const bool fused = bucket != 0u && bucket <= tile;
+    if (!fused && a.preset_step == 0.0f) {
+        // two passes: max-norm per bucket, then steps, then the encoder reads them
+        const uint64_t K = bucket ? (n + bucket - 1) / bucket : 1;
+        rc = dt == NDQ_F32 ? run_absmax<0>(g, a.tl, K, steps_out, s)
+                           : run_absmax<1>(g, a.tl, K, steps_out, s);
+        if (rc != NDQ_OK) return rc;
+        hipLaunchKernelGGL(steps_from_kappa_kernel, dim3((uint32_t)((K + 255) / 256)), dim3(256), 0,
+                           s, steps_out, K, levels);
+        if (launched() != NDQ_OK) return NDQ_ELAUNCH;
+    }
+#ifndef NDQ_NARROW_MAX_BITS
+#define NDQ_NARROW_MAX_BITS 6u
+#endif
+    const int mode = !nested ? (a.qp.bits <= NDQ_NARROW_MAX_BITS ? kDqNarrow : kDq)
+                             : (is_pow2(M) ? kNestedPow2 : kNestedAnyM);
+    if (dt == NDQ_F32) {
+        if (mode == kDqNarrow) return run_encode<0, kDqNarrow>(a, fused, s);
+        if (mode == kDq) return run_encode<0, kDq>(a, fused, s);
+        if (mode == kNestedPow2) return run_encode<0, kNestedPow2>(a, fused, s);
+        return run_encode<0, kNestedAnyM>(a, fused, s);
+    }
+    if (mode == kDqNarrow) return run_encode<1, kDqNarrow>(a, fused, s);
+    if (mode == kDq) return run_encode<1, kDq>(a, fused, s);
+    if (mode == kNestedPow2) return run_encode<1, kNestedPow2>(a, fused, s);
+    return run_encode<1, kNestedAnyM>(a, fused, s);
+}
+
+}  // namespace ndq
+
+extern "C" {
+
+int ndq_absmax(const void* g, ndq_dtype dt, size_t n, uint32_t bucket, float* kappa_out,
+               void* stream)
+{
+    using namespace ndq;
+    if (dt != NDQ_F32 && dt != NDQ_BF16) return NDQ_EINVAL;
+    if (!kappa_out) return NDQ_EINVAL;
+    if (n >= kMaxN) return NDQ_EUNSUPPORTED;
+    if (!aligned4(kappa_out) || bucket % 64u != 0u) return NDQ_EALIGN;
+    hipStream_t s = (hipStream_t)stream;
+    if (n == 0) {   // one (empty) bucket: its max-norm is 0
+        if (bucket != 0u) return NDQ_OK;
+        hipLaunchKernelGGL(fill_zero_kernel, dim3(1), dim3(256), 0, s, (uint32_t*)kappa_out, (uint64_t)1);
+        return launched();
+    }
+    if (!g) return NDQ_EINVAL;
+    if (!aligned16(g)) return NDQ_EALIGN;
+    Tiling tl;
+    const uint32_t tile = dt == NDQ_F32 ? EncTile<0>::N : EncTile<1>::N;
+    int rc = make_tiling(n, bucket, tile, &tl);
+    if (rc != NDQ_OK) return rc;
+    const uint64_t K = bucket ? (n + bucket - 1) / bucket : 1;
+    return dt == NDQ_F32 ? run_absmax<0>(g, tl, K, kappa_out, s) : run_absmax<1>(g, tl, K, kappa_out, s);
+}
+
+int ndq_dq_encode(const void* g, ndq_dtype dt, size_t n, float delta, uint32_t levels,
+                  uint32_t bucket, const ndq_dither* d, void* codes_out, float* steps_out,
+                  void* stream)
+{
+    return ndq::encode_common(g, dt, n, delta, levels, 0u, false, 1.0f, bucket, d, codes_out,
+                              steps_out, stream);
+}
+
+int ndq_nested_encode(const void* g, ndq_dtype dt, size_t n, float delta, uint32_t levels,
+                      uint32_t M, float alpha, uint32_t bucket, const ndq_dither* d,
+                      void* codes_out, float* steps_out, void* stream)
+{
+    return ndq::encode_common(g, dt, n, delta, levels, M, true, alpha, bucket, d, codes_out,
+                              steps_out, stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,80 @@
+// Host-side helpers shared by the translation units of libndq: size rules,
+// argument checks, tiling and quantizer parameters, launch status.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "ndq.h"
+#include "ndq_device.hpp"
+
+namespace ndq {
+
+inline uint32_t code_bits(uint32_t x)
+{
+    if (x < 2u || x > 256u) return 0u;
+    uint32_t b = 0u;
+    while ((1u << b) < x) ++b;
+    return b;
+}
+
+inline size_t packed_bytes(size_t n, uint32_t bits)
+{
+    const size_t bytes = (n * (size_t)bits + 7u) / 8u;
+    return (bytes + 15u) / 16u * 16u;
+}
+
+inline bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
+inline bool aligned4(const void* p) { return ((uintptr_t)p & 3u) == 0; }
+constexpr uint64_t kMaxN = (uint64_t)1 << 40;
+
+inline int make_tiling(uint64_t n, uint32_t bucket, uint32_t tile, Tiling* tl)
+{
+    tl->n = n;
+    tl->bucket_len = bucket ? bucket : n;
+    const uint64_t K = bucket ? (n + bucket - 1) / bucket : 1;
+    const uint64_t tpb = (tl->bucket_len + tile - 1) / tile;
+    if (tpb * K >= ((uint64_t)1 << 31) || tpb >= ((uint64_t)1 << 31)) return NDQ_EUNSUPPORTED;
+    tl->tiles_per_bucket = (uint32_t)tpb;
+    tl->total_tiles = (uint32_t)(tpb * K);
+    return NDQ_OK;
+}
+
+inline int make_quant(uint32_t levels, uint32_t M, bool nested, float alpha, Quant* qp)
+{
+    if (levels < 2u || levels > 256u) return NDQ_EINVAL;
+    if (nested && (M < 2u || M > 256u)) return NDQ_EINVAL;
+    if (nested && !(alpha > 0.0f && alpha <= 1.0f)) return NDQ_EINVAL;
+    qp->alpha = nested ? alpha : 1.0f;
+    qp->beta = (float)(1.0 - (double)qp->alpha * (double)qp->alpha);
+    qp->levels = levels;
+    qp->q_min = -(int32_t)(levels / 2u);
+    qp->q_min_f = (float)qp->q_min;
+    qp->q_max_f = (float)(qp->q_min + (int32_t)levels - 1);
+    qp->M = nested ? M : 1u;
+    qp->M_f = (float)qp->M;
+    qp->inv_M_f = 1.0f / qp->M_f;   // exact when M is a power of two, unused otherwise
+    qp->bits = code_bits(nested ? M : levels);
+    float weights = 0.0f;
+    for (uint32_t k = 0; k < 4; ++k) weights += (float)(1u << (k * qp->bits < 31u ? k * qp->bits : 31u));
+    qp->pack_bias = -qp->q_min_f * weights;   // exact for bits <= 6, the only user
+    return NDQ_OK;
+}
+
+inline bool is_pow2(uint32_t x) { return (x & (x - 1u)) == 0u; }
+
+inline DitherStream make_stream(const ndq_dither* d)
+{
+    DitherStream s;
+    s.key0 = (uint32_t)d->seed;
+    s.key1 = (uint32_t)(d->seed >> 32);
+    s.step = d->step;
+    s.worker = d->worker;
+    return s;
+}
+
+inline int launched() { return hipGetLastError() == hipSuccess ? NDQ_OK : NDQ_ELAUNCH; }
+
+inline uint32_t blocks_for(uint32_t tiles) { return (tiles + kWavesPerBlock - 1) / kWavesPerBlock; }
+
+}  // namespace ndq

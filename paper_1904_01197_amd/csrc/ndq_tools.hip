@@ -1,0 +1,389 @@
+// libndq, beyond the headline path (gfx950): entropy of an index stream, dense
+// base-L stream, sigma_z^2 estimate and Thm 4's parameter helpers, size rules and
+// status text.  See include/ndq.h for the contract.
+#include <hip/hip_runtime.h>
+
+#include <math.h>
+
+#include "ndq.h"
+#include "ndq_device.hpp"
+#include "ndq_host.hpp"
+
+namespace ndq {
+
+// ---------------------------------------------------------------------------
+// Histogram and entropy of an index stream (Sec. 4: the bit rate after entropy
+// coding is reported through the entropy of the transmitted indices).
+// A thread reads units of 32 codes (= `bits` consecutive 32-bit words) with a
+// small bit reader.  Counting: 1-bit and 2-bit streams by population count in
+// registers; up to 16 bins in a private LDS column per thread (no conflicts);
+// wider codes with LDS atomics on one histogram per workgroup.
+// ---------------------------------------------------------------------------
+constexpr int kHistBlock = 256;
+
+__global__ __launch_bounds__(kHistBlock) void histogram_kernel(const uint32_t* __restrict__ words,
+                                                               uint64_t n, uint32_t bits,
+                                                               unsigned long long* hist)
+{
+    __shared__ uint32_t cols[16][kHistBlock];   // bits <= 4: one column per thread
+    __shared__ uint32_t wide[256];              // bits  > 4: shared, atomic
+    const uint32_t tid = threadIdx.x;
+    const uint32_t nbins = 1u << bits;
+    for (uint32_t b = 0; b < 16; ++b) cols[b][tid] = 0u;
+    wide[tid] = 0u;
+    __syncthreads();
+
+    const uint64_t units = (n + 31u) >> 5;
+    const uint32_t mask = nbins - 1u;
+    uint32_t c1 = 0u, c2 = 0u, c3 = 0u, seen = 0u;   // registers for the 1- and 2-bit paths
+    for (uint64_t u = (uint64_t)blockIdx.x * kHistBlock + tid; u < units;
+         u += (uint64_t)gridDim.x * kHistBlock) {
+        const uint32_t valid = (u + 1u == units) ? (uint32_t)(n - (u << 5)) : 32u;
+        const uint32_t* p = words + u * bits;
+        if (bits == 1u) {
+            uint32_t w = p[0];
+            if (valid < 32u) w &= (1u << valid) - 1u;
+            c1 += __builtin_popcount(w);
+            seen += valid;
+        } else if (bits == 2u) {
+#pragma unroll
+            for (uint32_t j = 0; j < 2; ++j) {
+                const uint32_t have = valid > 16u * j ? (valid - 16u * j < 16u ? valid - 16u * j : 16u) : 0u;
+                uint32_t w = have ? p[j] : 0u;
+                uint32_t field = have == 16u ? 0x55555555u : ((1u << (2u * have)) - 1u) & 0x55555555u;
+                const uint32_t lo = w & field, hi = (w >> 1) & field;
+                c1 += __builtin_popcount(lo & ~hi);
+                c2 += __builtin_popcount(hi & ~lo);
+                c3 += __builtin_popcount(lo & hi);
+                seen += have;
+            }
+        } else {
+            uint64_t buf = 0u;
+            uint32_t have = 0u, next = 0u;
+            for (uint32_t j = 0; j < valid; ++j) {
+                if (have < bits) {
+                    buf |= (uint64_t)p[next++] << have;
+                    have += 32u;
+                }
+                const uint32_t code = (uint32_t)buf & mask;
+                buf >>= bits;
+                have -= bits;
+                if (bits <= 4u) cols[code][tid] += 1u;      // private column: no race
+                else atomicAdd(&wide[code], 1u);
+            }
+        }
+    }
+    if (bits == 1u) {
+        cols[1][tid] = c1; cols[0][tid] = seen - c1;
+    } else if (bits == 2u) {
+        cols[1][tid] = c1; cols[2][tid] = c2; cols[3][tid] = c3; cols[0][tid] = seen - c1 - c2 - c3;
+    }
+    __syncthreads();
+    if (bits <= 4u) {
+        // 16 threads per bin add up the bin's 256 columns, then one atomic per bin and block
+        const uint32_t bin = tid >> 4, part = tid & 15u;
+        uint32_t sum = 0u;
+        for (uint32_t k = 0; k < kHistBlock / 16; ++k) sum += cols[bin][part * (kHistBlock / 16) + k];
+#pragma unroll
+        for (int sft = 8; sft >= 1; sft >>= 1) sum += __shfl_xor(sum, sft, 16);
+        if (part == 0u && bin < nbins && sum) atomicAdd(hist + bin, (unsigned long long)sum);
+    } else if (tid < nbins && wide[tid]) {
+        atomicAdd(hist + tid, (unsigned long long)wide[tid]);
+    }
+}
+
+__global__ void fill_zero64_kernel(unsigned long long* p, uint32_t count)
+{
+    if (threadIdx.x < count) p[threadIdx.x] = 0ull;
+}
+
+// -sum p log2 p over at most 256 bins, binary64, fixed reduction order
+__global__ __launch_bounds__(256) void entropy_kernel(const unsigned long long* hist, uint32_t nbins,
+                                                      uint64_t n, double* entropy_out)
+{
+    __shared__ double term[256];
+    const uint32_t tid = threadIdx.x;
+    double t = 0.0;
+    if (tid < nbins && n) {
+        const unsigned long long h = hist[tid];
+        if (h) {
+            const double p = (double)h / (double)n;
+            t = -p * log2(p);
+        }
+    }
+    term[tid] = t;
+    __syncthreads();
+    for (uint32_t s = 128; s >= 1; s >>= 1) {
+        if (tid < s) term[tid] += term[tid + s];
+        __syncthreads();
+    }
+    if (tid == 0) entropy_out[0] = term[0];
+}
+
+// ---------------------------------------------------------------------------
+// Dense base-L stream (Sec. 4 Table 1 counts log2 L bits per index): k indices
+// per 32-bit word as the number sum_j c_j L^j.  Transcoders between the
+// fixed-width stream and the dense one.  A thread owns 8 dense words = 8k
+// indices = k*bits whole bytes of the fixed-width stream, so no two threads
+// touch the same byte.
+// ---------------------------------------------------------------------------
+struct DenseArgs {
+    unsigned char* fixed;     // fixed-width stream (read by pack, written by unpack)
+    uint32_t* dense;          // dense stream (written by pack, read by unpack)
+    uint64_t n;               // indices
+    uint64_t fixed_valid;     // ceil(n*bits/8): bytes of the fixed stream that hold indices
+    uint64_t fixed_total;     // its padded size
+    uint64_t dense_valid;     // ceil(n/k) words that hold indices
+    uint64_t dense_total;     // padded size in words
+    uint32_t levels, k, bits;
+};
+
+__global__ __launch_bounds__(256) void dense_pack_kernel(DenseArgs a)
+{
+    const uint64_t t = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const uint64_t w0 = t * 8u;
+    if (w0 >= a.dense_total) return;
+    uint64_t byte = t * a.k * a.bits;
+    const uint32_t mask = (1u << a.bits) - 1u;
+    uint32_t buf = 0u, have = 0u;
+    for (uint32_t j = 0; j < 8u; ++j) {
+        const uint64_t w = w0 + j;
+        if (w >= a.dense_total) break;
+        uint64_t value = 0u, weight = 1u;
+        for (uint32_t d = 0; d < a.k; ++d) {
+            if (have < a.bits) {
+                const uint32_t b = byte < a.fixed_valid ? a.fixed[byte] : 0u;
+                ++byte;
+                buf |= b << have;
+                have += 8u;
+            }
+            uint32_t c = buf & mask;
+            buf >>= a.bits;
+            have -= a.bits;
+            if (w * a.k + d >= a.n) c = 0u;
+            value += c * weight;
+            weight *= a.levels;
+        }
+        a.dense[w] = (uint32_t)value;
+    }
+}
+
+__global__ __launch_bounds__(256) void dense_unpack_kernel(DenseArgs a)
+{
+    const uint64_t t = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    uint64_t byte = t * a.k * a.bits;
+    if (byte >= a.fixed_total) return;
+    const uint64_t w0 = t * 8u;
+    uint32_t buf = 0u, have = 0u;
+    for (uint32_t j = 0; j < 8u; ++j) {
+        const uint64_t w = w0 + j;
+        uint32_t value = w < a.dense_valid ? a.dense[w] : 0u;
+        for (uint32_t d = 0; d < a.k; ++d) {
+            uint32_t c = value % a.levels;
+            value /= a.levels;
+            if (w * a.k + d >= a.n) c = 0u;
+            buf |= c << have;
+            have += a.bits;
+            if (have >= 8u) {
+                if (byte < a.fixed_total) a.fixed[byte] = (unsigned char)buf;
+                ++byte;
+                buf >>= 8;
+                have -= 8u;
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// sum_i (a_i - b_i)^2 in binary64 (the sigma_z^2 estimate behind Thm 4's parameter
+// choice).  Two passes over a fixed grid so that the reduction order, and hence
+// the result, does not depend on scheduling.
+// ---------------------------------------------------------------------------
+constexpr uint32_t kSqBlocks = 1024;
+
+__device__ __forceinline__ double block_sum_256(double x, double* sh)
+{
+    const uint32_t tid = threadIdx.x;
+    sh[tid] = x;
+    __syncthreads();
+    for (uint32_t s = 128; s >= 1; s >>= 1) {
+        if (tid < s) sh[tid] += sh[tid + s];
+        __syncthreads();
+    }
+    return sh[0];
+}
+
+__global__ __launch_bounds__(256) void sqdiff_partial_kernel(const float* __restrict__ a,
+                                                             const float* __restrict__ b, uint64_t n,
+                                                             double* partial)
+{
+    __shared__ double sh[256];
+    const uint64_t n4 = n >> 2;
+    double acc = 0.0;
+    for (uint64_t i = (uint64_t)blockIdx.x * 256u + threadIdx.x; i < n4; i += (uint64_t)kSqBlocks * 256u) {
+        const float4 x = ((const float4*)a)[i], y = ((const float4*)b)[i];
+        const double d0 = (double)x.x - (double)y.x, d1 = (double)x.y - (double)y.y;
+        const double d2 = (double)x.z - (double)y.z, d3 = (double)x.w - (double)y.w;
+        acc += d0 * d0; acc += d1 * d1; acc += d2 * d2; acc += d3 * d3;
+    }
+    if (blockIdx.x == 0 && threadIdx.x < (n & 3u)) {       // the last n mod 4 elements
+        const uint64_t i = (n4 << 2) + threadIdx.x;
+        const double d = (double)a[i] - (double)b[i];
+        acc += d * d;
+    }
+    const double total = block_sum_256(acc, sh);
+    if (threadIdx.x == 0) partial[blockIdx.x] = total;
+}
+
+__global__ __launch_bounds__(256) void sqdiff_final_kernel(const double* partial, double* out)
+{
+    __shared__ double sh[256];
+    double acc = 0.0;
+    for (uint32_t j = 0; j < kSqBlocks / 256u; ++j) acc += partial[j * 256u + threadIdx.x];
+    const double total = block_sum_256(acc, sh);
+    if (threadIdx.x == 0) out[0] = total;
+}
+
+}  // namespace ndq
+
+extern "C" {
+
+uint32_t ndq_code_bits(uint32_t levels_or_M) { return ndq::code_bits(levels_or_M); }
+
+size_t ndq_packed_bytes(size_t n, uint32_t bits) { return ndq::packed_bytes(n, bits); }
+
+size_t ndq_num_buckets(size_t n, uint32_t bucket)
+{
+    return bucket ? (n + bucket - 1u) / bucket : 1u;
+}
+
+int ndq_code_entropy(const void* codes, size_t n, uint32_t bits, uint64_t* hist_out,
+                     double* entropy_out, void* stream)
+{
+    using namespace ndq;
+    if (bits < 1u || bits > 8u || !hist_out) return NDQ_EINVAL;
+    if (n >= kMaxN) return NDQ_EUNSUPPORTED;
+    if (((uintptr_t)hist_out & 7u) != 0u || ((uintptr_t)entropy_out & 7u) != 0u) return NDQ_EALIGN;
+    if (n != 0 && !codes) return NDQ_EINVAL;
+    if (n != 0 && !aligned16(codes)) return NDQ_EALIGN;
+    hipStream_t s = (hipStream_t)stream;
+    const uint32_t nbins = 1u << bits;
+    hipLaunchKernelGGL(fill_zero64_kernel, dim3(1), dim3(256), 0, s, (unsigned long long*)hist_out, nbins);
+    if (launched() != NDQ_OK) return NDQ_ELAUNCH;
+    if (n != 0) {
+        const uint64_t units = (n + 31u) >> 5;
+        uint64_t blocks = (units + kHistBlock - 1) / kHistBlock;
+        if (blocks > 4096u) blocks = 4096u;
+        hipLaunchKernelGGL(histogram_kernel, dim3((uint32_t)blocks), dim3(kHistBlock), 0, s,
+                           (const uint32_t*)codes, (uint64_t)n, bits, (unsigned long long*)hist_out);
+        if (launched() != NDQ_OK) return NDQ_ELAUNCH;
+    }
+    if (entropy_out) {
+        hipLaunchKernelGGL(entropy_kernel, dim3(1), dim3(256), 0, s,
+                           (const unsigned long long*)hist_out, nbins, (uint64_t)n, entropy_out);
+        if (launched() != NDQ_OK) return NDQ_ELAUNCH;
+    }
+    return NDQ_OK;
+}
+
+uint32_t ndq_dense_group(uint32_t levels)
+{
+    if (levels < 2u || levels > 256u) return 0u;
+    uint32_t k = 0u;
+    uint64_t power = 1u;
+    while (power * levels <= ((uint64_t)1 << 32)) { power *= levels; ++k; }
+    return k;
+}
+
+size_t ndq_dense_bytes(size_t n, uint32_t levels)
+{
+    const uint32_t k = ndq_dense_group(levels);
+    if (!k) return 0u;
+    const size_t words = (n + k - 1u) / k;
+    return (words * 4u + 15u) / 16u * 16u;
+}
+
+static int dense_common(const void* fixed, const void* dense, size_t n, uint32_t levels, bool pack,
+                        void* stream)
+{
+    using namespace ndq;
+    DenseArgs a;
+    a.k = ndq_dense_group(levels);
+    if (!a.k) return NDQ_EINVAL;
+    if (n == 0) return NDQ_OK;
+    if (!fixed || !dense) return NDQ_EINVAL;
+    if (n >= kMaxN) return NDQ_EUNSUPPORTED;
+    if (!aligned16(fixed) || !aligned16(dense)) return NDQ_EALIGN;
+    a.fixed = (unsigned char*)fixed;
+    a.dense = (uint32_t*)dense;
+    a.n = n;
+    a.levels = levels;
+    a.bits = code_bits(levels);
+    a.fixed_valid = ((uint64_t)n * a.bits + 7u) / 8u;
+    a.fixed_total = packed_bytes(n, a.bits);
+    a.dense_valid = ((uint64_t)n + a.k - 1u) / a.k;
+    a.dense_total = ndq_dense_bytes(n, levels) / 4u;
+    const uint64_t per_thread_bytes = (uint64_t)a.k * a.bits;
+    const uint64_t threads = pack ? (a.dense_total + 7u) / 8u
+                                  : (a.fixed_total + per_thread_bytes - 1u) / per_thread_bytes;
+    const uint64_t blocks = (threads + 255u) / 256u;
+    if (blocks >= ((uint64_t)1 << 31)) return NDQ_EUNSUPPORTED;
+    if (pack) hipLaunchKernelGGL(dense_pack_kernel, dim3((uint32_t)blocks), dim3(256), 0, (hipStream_t)stream, a);
+    else hipLaunchKernelGGL(dense_unpack_kernel, dim3((uint32_t)blocks), dim3(256), 0, (hipStream_t)stream, a);
+    return launched();
+}
+
+int ndq_dense_pack(const void* codes, size_t n, uint32_t levels, void* dense_out, void* stream)
+{
+    return dense_common(codes, dense_out, n, levels, true, stream);
+}
+
+int ndq_dense_unpack(const void* dense, size_t n, uint32_t levels, void* codes_out, void* stream)
+{
+    return dense_common(codes_out, dense, n, levels, false, stream);
+}
+
+double ndq_alpha_for_equal_variance(double delta1, double sigma_z2)
+{
+    const double arg = 1.0 - delta1 * delta1 / (12.0 * sigma_z2);
+    return arg > 0.0 ? sqrt(arg) : 0.0;
+}
+
+double ndq_decode_error_bound(double delta1, uint32_t M, double alpha, double sigma_z2)
+{
+    const double delta2 = (double)M * delta1;
+    return delta1 * delta1 / (3.0 * delta2 * delta2) + 4.0 * alpha * alpha * sigma_z2 / (delta2 * delta2);
+}
+
+size_t ndq_sqdiff_workspace(void) { return ndq::kSqBlocks * sizeof(double); }
+
+int ndq_sqdiff(const float* a, const float* b, size_t n, double* workspace, double* out,
+               void* stream)
+{
+    using namespace ndq;
+    if (!workspace || !out) return NDQ_EINVAL;
+    if (n != 0 && (!a || !b)) return NDQ_EINVAL;
+    if (n >= kMaxN) return NDQ_EUNSUPPORTED;
+    if (((uintptr_t)workspace & 7u) || ((uintptr_t)out & 7u)) return NDQ_EALIGN;
+    if (n != 0 && (!aligned16(a) || !aligned16(b))) return NDQ_EALIGN;
+    hipStream_t s = (hipStream_t)stream;
+    hipLaunchKernelGGL(sqdiff_partial_kernel, dim3(kSqBlocks), dim3(256), 0, s, a, b, (uint64_t)n,
+                       workspace);
+    if (launched() != NDQ_OK) return NDQ_ELAUNCH;
+    hipLaunchKernelGGL(sqdiff_final_kernel, dim3(1), dim3(256), 0, s, (const double*)workspace, out);
+    return launched();
+}
+
+const char* ndq_strerror(int rc)
+{
+    switch (rc) {
+        case NDQ_OK: return "success";
+        case NDQ_EINVAL: return "invalid argument (null pointer, levels or M outside [2,256], overlapping buffers, bad W)";
+        case NDQ_EALIGN: return "alignment violated (16-byte data pointers, bucket multiple of 64, offset multiple of 8)";
+        case NDQ_EUNSUPPORTED: return "vector too long for one call";
+        case NDQ_ELAUNCH: return "the HIP runtime refused a kernel launch";
+        default: return "unknown ndq status";
+    }
+}
+
+}  // extern "C"
