@@ -422,8 +422,24 @@ def test_config5_full_size_sampled_slices():
             assert np.array_equal(got_s, s_ref[w]), (lo, w)
         ref = opipe.decode_chain(wl.plan, wl.bucket, span, c_ref, s_ref, ds_o, wl.out_scale)
         assert np.array_equal(out[lo:hi].cpu().numpy(), ref), lo
-    # properties that hold at any size
+    # properties that hold at any size, checked on all 2^27 elements with device-side
+    # tensor arithmetic: the DQSG reconstruction error of worker 0 is within half a
+    # step except where the index saturated (about 1e-4 of the elements), has mean 0
+    # and variance 1/12 in units of the bucket's step (Thm 1 / Lemma 2)
     assert bool(torch.isfinite(out).all())
+    g0 = ndq.ndq_dq_decode(bufs.codes[0], n, wl.plan[0][1], wl.bucket, bufs.steps[0], ds_g[0])
+    g0 -= dev[0].float()
+    st = bufs.steps[0].repeat_interleave(wl.bucket)[:n]
+    ok = st > 0
+    e = (g0[ok] / st[ok]).double()
+    del g0, st
+    inside = e.abs() <= 0.5 + 2.0 ** -12
+    clipped = 1.0 - inside.double().mean().item()
+    assert clipped < 1e-3, clipped
+    e_in = e[inside]
+    assert abs(e_in.mean().item()) < 5.0 * (1.0 / 12 / e_in.numel()) ** 0.5 + 1e-4
+    assert abs(e_in.var().item() * 12 - 1) < 0.01
+    del e, e_in, inside, ok
     fused = out.clone()
     # the call-by-call schedule gives the same 2^27 values
     bufs2 = pipeline.allocate(wl, n)
@@ -819,3 +835,57 @@ def test_extreme_magnitudes_denormals_and_signed_zeros(dtype):
             ref = oracle.nested_decode(c_ref, n, M, bucket, s_ref, d_o, side32, 0.5, alpha=alpha)
             out = ndq.ndq_nested_decode(codes, n, M, alpha, bucket, steps, d_g, side_d, 0.5)
             assert np.array_equal(out.cpu().numpy(), ref, equal_nan=True), (bucket, delta, M, alpha)
+
+
+def test_randomized_differential_against_oracle():
+    """300 seeded random draws of (n, dtype, bucket, levels, M, alpha, preset, offset,
+    accumulate form): every entry point against the oracle, bit for bit."""
+    rng = np.random.default_rng(20240611)
+    dev = _gpu()
+    for case in range(300):
+        n = int(rng.choice([rng.integers(1, 300), rng.integers(300, 5000), rng.integers(5000, 40000)]))
+        dtype = "bf16" if rng.random() < 0.5 else "f32"
+        bucket = int(rng.choice([0, 64, 128, 1024, 2048, 4096, 4160, 8192]))
+        levels = int(rng.choice([2, 3, 4, 5, 7, 8, 15, 16, 17, 64, 100, 255, 256]))
+        M = int(rng.choice([2, 3, 4, 5, 8, 16, 31, 256]))
+        alpha = float(rng.choice([1.0, 1.0, 0.9, 0.5]))
+        offset = int(rng.choice([0, 8, 4096, (1 << 33) + 64])) if bucket == 0 else \
+            int(rng.choice([0, 1, 7, 1 << 22])) * bucket
+        preset = bucket == 0 and rng.random() < 0.5
+        seed, step, worker = int(rng.integers(0, 1 << 62)), int(rng.integers(0, 1 << 31)), int(rng.integers(0, 64))
+        g = _make(n, dtype, seed=case, heavy=rng.random() < 0.3)
+        gf = workloads.bf16_bits_to_f32(g) if dtype == "bf16" else g
+        kappa = float(np.abs(gf).max())
+        delta = float(F(2 * kappa / (levels - 1))) if preset and kappa > 0 else 0.0
+        d_o, d_g = oracle.dither(seed, step, worker, offset), ndq.ndq_dither(seed, step, worker, offset)
+        gd = _to_dev(g)
+        tag = (case, n, dtype, bucket, levels, M, alpha, offset, preset)
+        # DQSG
+        c_ref, s_ref = oracle.dq_encode(g, delta, levels, bucket, d_o)
+        codes, steps = ndq.ndq_dq_encode(gd, delta, levels, bucket, d_g)
+        assert np.array_equal(steps.cpu().numpy(), s_ref), tag
+        assert codes.cpu().numpy().tobytes() == c_ref.tobytes(), tag
+        ref = oracle.dq_decode(c_ref, n, levels, bucket, s_ref, d_o)
+        assert np.array_equal(ndq.ndq_dq_decode(codes, n, levels, bucket, steps, d_g).cpu().numpy(), ref), tag
+        assert np.array_equal(ndq.ndq_dq_decode_half(codes, n, levels, bucket, steps).cpu().numpy(),
+                              oracle.dq_decode_half(c_ref, n, levels, bucket, s_ref)), tag
+        # nested against the DQSG reconstruction as side information, in place
+        m_ref, t_ref = oracle.nested_encode(g, delta, levels, M, bucket, d_o, alpha=alpha)
+        mc, ms = ndq.ndq_nested_encode(gd, delta, levels, M, alpha, bucket, d_g)
+        assert np.array_equal(ms.cpu().numpy(), t_ref), tag
+        assert mc.cpu().numpy().tobytes() == m_ref.tobytes(), tag
+        S_ref = ref.copy()
+        oracle.nested_decode(m_ref, n, M, bucket, t_ref, d_o, S_ref, 1.0, out=S_ref, alpha=alpha)
+        S = torch.from_numpy(ref).to(dev)
+        ndq.ndq_nested_decode(mc, n, M, alpha, bucket, ms, d_g, S, 1.0, S, True)
+        assert np.array_equal(S.cpu().numpy(), S_ref), tag
+        # the same two workers through the fused loop
+        out = ndq.ndq_decode_chain([(codes, steps, ndq.NDQ_WORKER_DQ, levels, d_g),
+                                    (mc, ms, ndq.NDQ_WORKER_NESTED, M, d_g, alpha)], n, bucket, 1.0)
+        assert np.array_equal(out.cpu().numpy(), S_ref), tag
+        # entropy and dense form of the index streams
+        bits = oracle.code_bits(levels)
+        hist, _ = ndq.ndq_code_entropy(codes, n, bits)
+        assert np.array_equal(hist.cpu().numpy().astype(np.uint64), oracle.code_histogram(c_ref, n, bits)), tag
+        dense = ndq.ndq_dense_pack(codes, n, levels)
+        assert dense.cpu().numpy().tobytes() == oracle.dense_pack(oracle.unpack(c_ref, n, bits), levels).tobytes(), tag
