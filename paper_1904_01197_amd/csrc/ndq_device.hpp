@@ -358,11 +358,27 @@ __device__ __forceinline__ typename Elem<DT>::Row load_row(const void* tile, uin
     return row;
 }
 
+// Maximum of a non-negative float over the 64 lanes of a wave, returned in every
+// lane.  Non-negative floats order like their bit patterns, so the reduction
+// runs on integers: four data-parallel-primitive steps inside each row of 16
+// lanes (no LDS traffic), then the four row results are combined on the scalar
+// unit.  Every lane of the wave must be active at the call.
 __device__ __forceinline__ float wave_max(float x)
 {
-#pragma unroll
-    for (int s = 32; s >= 1; s >>= 1) x = __builtin_fmaxf(x, __shfl_xor(x, s, kWave));
-    return x;
+    int v = (int)__float_as_uint(x);
+    int t;
+    t = __builtin_amdgcn_update_dpp(0, v, 0xB1, 0xF, 0xF, false);   // quad_perm [1,0,3,2]
+    v = v > t ? v : t;
+    t = __builtin_amdgcn_update_dpp(0, v, 0x4E, 0xF, 0xF, false);   // quad_perm [2,3,0,1]
+    v = v > t ? v : t;
+    t = __builtin_amdgcn_update_dpp(0, v, 0x141, 0xF, 0xF, false);  // row_half_mirror
+    v = v > t ? v : t;
+    t = __builtin_amdgcn_update_dpp(0, v, 0x140, 0xF, 0xF, false);  // row_mirror
+    v = v > t ? v : t;
+    const int r0 = __builtin_amdgcn_readlane(v, 0), r1 = __builtin_amdgcn_readlane(v, 16);
+    const int r2 = __builtin_amdgcn_readlane(v, 32), r3 = __builtin_amdgcn_readlane(v, 48);
+    const int m01 = r0 > r1 ? r0 : r1, m23 = r2 > r3 ? r2 : r3;
+    return __uint_as_float((uint32_t)(m01 > m23 ? m01 : m23));
 }
 
 // Tile geometry.  A vector is cut into buckets (one step each; bucket == 0: the
