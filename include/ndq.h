@@ -156,9 +156,13 @@ int ndq_nested_decode(const void* codes, size_t n, uint32_t M, float alpha, uint
  * Delta_1^2/12 of DQSG (0 when the argument is not positive: the side
  * information alone is already better).  ndq_decode_error_bound: Thm 4's bound
  * Delta_1^2/(3 Delta_2^2) + 4 alpha^2 sigma_z^2/Delta_2^2 on the probability of a
- * coset decode error, Delta_2 = M Delta_1. */
+ * coset decode error, Delta_2 = M Delta_1.  ndq_nesting_ratio_for_error: the
+ * smallest nesting ratio M in [2, 256] (fewest bits per code) for which that
+ * bound is at most p_max; 0 when even M = 256 does not reach it or an argument
+ * is out of range (delta1 <= 0, alpha outside [0, 1], sigma_z2 < 0, p_max <= 0). */
 double ndq_alpha_for_equal_variance(double delta1, double sigma_z2);
 double ndq_decode_error_bound(double delta1, uint32_t M, double alpha, double sigma_z2);
+uint32_t ndq_nesting_ratio_for_error(double delta1, double alpha, double sigma_z2, double p_max);
 
 /* Estimate of n*sigma_z^2 for that selection (Thm 4's model g = y + z): out[0] =
  * sum_i (a_i - b_i)^2 in binary64, with a fixed reduction order (the same inputs

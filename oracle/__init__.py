@@ -82,6 +82,8 @@ def lib():
         L.oracle_alpha_for_equal_variance.restype = C.c_double
         L.oracle_decode_error_bound.argtypes = [C.c_double, u32, C.c_double, C.c_double]
         L.oracle_decode_error_bound.restype = C.c_double
+        L.oracle_nesting_ratio_for_error.argtypes = [C.c_double, C.c_double, C.c_double, C.c_double]
+        L.oracle_nesting_ratio_for_error.restype = u32
         L.oracle_sqdiff_sum.argtypes = [vp, vp, sz]
         L.oracle_sqdiff_sum.restype = C.c_double
         L.oracle_packed_bytes.argtypes = [sz, u32]
@@ -210,6 +212,10 @@ def alpha_for_equal_variance(delta1, sigma_z2):
 
 def decode_error_bound(delta1, M, alpha, sigma_z2):
     return lib().oracle_decode_error_bound(delta1, M, alpha, sigma_z2)
+
+
+def nesting_ratio_for_error(delta1, alpha, sigma_z2, p_max):
+    return lib().oracle_nesting_ratio_for_error(delta1, alpha, sigma_z2, p_max)
 
 
 def sqdiff_sum(a, b):

@@ -201,6 +201,17 @@ double oracle_decode_error_bound(double delta1, uint32_t M, double alpha, double
     return delta1 * delta1 / (3.0 * delta2 * delta2) + 4.0 * alpha * alpha * sigma_z2 / (delta2 * delta2);
 }
 
+/* Smallest nesting ratio whose Thm 4 bound is at most p_max: the definition,
+ * tried in increasing order (fewest bits first); 0 if none up to 256 fits. */
+uint32_t oracle_nesting_ratio_for_error(double delta1, double alpha, double sigma_z2, double p_max)
+{
+    if (!(delta1 > 0.0) || !(alpha >= 0.0 && alpha <= 1.0) || !(sigma_z2 >= 0.0) || !(p_max > 0.0))
+        return 0;
+    for (uint32_t M = 2; M <= 256; ++M)
+        if (oracle_decode_error_bound(delta1, M, alpha, sigma_z2) <= p_max) return M;
+    return 0;
+}
+
 double oracle_sqdiff_sum(const float* a, const float* b, size_t n)
 {
     double acc = 0.0;

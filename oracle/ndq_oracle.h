@@ -98,6 +98,7 @@ float oracle_nested_value_alpha(uint32_t m, float y, float delta, float alpha, f
  * coset decode error, Delta_1^2/(3 Delta_2^2) + 4 alpha^2 sigma_z^2/Delta_2^2. */
 double oracle_alpha_for_equal_variance(double delta1, double sigma_z2);
 double oracle_decode_error_bound(double delta1, uint32_t M, double alpha, double sigma_z2);
+uint32_t oracle_nesting_ratio_for_error(double delta1, double alpha, double sigma_z2, double p_max);
 /* sigma_z^2 estimate: sum_i (a_i - b_i)^2 in binary64 (divide by n for the mean) */
 double oracle_sqdiff_sum(const float* a, const float* b, size_t n);
 

@@ -355,6 +355,21 @@ double ndq_decode_error_bound(double delta1, uint32_t M, double alpha, double si
     return delta1 * delta1 / (3.0 * delta2 * delta2) + 4.0 * alpha * alpha * sigma_z2 / (delta2 * delta2);
 }
 
+uint32_t ndq_nesting_ratio_for_error(double delta1, double alpha, double sigma_z2, double p_max)
+{
+    if (!(delta1 > 0.0) || !(alpha >= 0.0 && alpha <= 1.0) || !(sigma_z2 >= 0.0) || !(p_max > 0.0))
+        return 0;
+    // bound(M) = c / M^2 with c = 1/3 + 4 alpha^2 sigma_z^2 / Delta_1^2: start at
+    // the real-valued root and let the bound itself settle the last unit.
+    const double c = 1.0 / 3.0 + 4.0 * alpha * alpha * sigma_z2 / (delta1 * delta1);
+    const double root = sqrt(c / p_max);
+    if (!(root <= 257.0)) return 0;
+    uint32_t M = root < 2.0 ? 2u : (uint32_t)root;
+    while (M > 2 && ndq_decode_error_bound(delta1, M - 1, alpha, sigma_z2) <= p_max) --M;
+    while (M <= 256 && ndq_decode_error_bound(delta1, M, alpha, sigma_z2) > p_max) ++M;
+    return M <= 256 ? M : 0;
+}
+
 size_t ndq_sqdiff_workspace(void) { return ndq::kSqBlocks * sizeof(double); }
 
 int ndq_sqdiff(const float* a, const float* b, size_t n, double* workspace, double* out,

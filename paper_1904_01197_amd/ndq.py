@@ -21,7 +21,7 @@ EXPORTS = ("ndq_code_bits", "ndq_packed_bytes", "ndq_num_buckets", "ndq_absmax",
            "ndq_dq_decode", "ndq_dq_decode_half", "ndq_nested_encode", "ndq_nested_decode", "ndq_aggregate",
            "ndq_decode_chain", "ndq_code_entropy", "ndq_dense_group", "ndq_dense_bytes",
            "ndq_dense_pack", "ndq_dense_unpack", "ndq_alpha_for_equal_variance",
-           "ndq_decode_error_bound", "ndq_sqdiff_workspace", "ndq_sqdiff", "ndq_strerror")
+           "ndq_decode_error_bound", "ndq_nesting_ratio_for_error", "ndq_sqdiff_workspace", "ndq_sqdiff", "ndq_strerror")
 
 
 class ndq_dither(C.Structure):
@@ -80,6 +80,8 @@ def lib():
         L.ndq_alpha_for_equal_variance.restype = C.c_double
         L.ndq_decode_error_bound.argtypes = [C.c_double, u32, C.c_double, C.c_double]
         L.ndq_decode_error_bound.restype = C.c_double
+        L.ndq_nesting_ratio_for_error.argtypes = [C.c_double, C.c_double, C.c_double, C.c_double]
+        L.ndq_nesting_ratio_for_error.restype = u32
         L.ndq_sqdiff_workspace.argtypes, L.ndq_sqdiff_workspace.restype = [], sz
         L.ndq_sqdiff.argtypes, L.ndq_sqdiff.restype = [vp, vp, sz, vp, vp, vp], ci
         L.ndq_dense_group.argtypes, L.ndq_dense_group.restype = [u32], u32
@@ -294,6 +296,10 @@ def ndq_alpha_for_equal_variance(delta1, sigma_z2):
 
 def ndq_decode_error_bound(delta1, M, alpha, sigma_z2):
     return lib().ndq_decode_error_bound(delta1, M, alpha, sigma_z2)
+
+
+def ndq_nesting_ratio_for_error(delta1, alpha, sigma_z2, p_max):
+    return lib().ndq_nesting_ratio_for_error(delta1, alpha, sigma_z2, p_max)
 
 
 def ndq_sqdiff_workspace():

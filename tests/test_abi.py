@@ -114,6 +114,20 @@ def test_parameter_selection_helpers_agree_with_oracle():
                 assert ndq.ndq_decode_error_bound(d1, M, alpha, s2) == \
                     oracle.decode_error_bound(d1, M, alpha, s2)
     assert ndq.ndq_alpha_for_equal_variance(1.0, 0.05) == 0.0
+    rng = np.random.default_rng(23)
+    cases = [(1.0, 1.0, 0.0, 1 / 12), (1.0, 1.0, 0.0, 1.0), (1.0, 1.0, 1e6, 1e-3), (0.0, 1.0, 1.0, 0.1),
+             (1.0, 1.5, 1.0, 0.1), (1.0, 1.0, -1.0, 0.1), (1.0, 1.0, 1.0, 0.0), (1.0, 1.0, 1.0, float("nan")),
+             (1.0, 1.0, 16383.9, 1.0), (1.0, 1.0, 16384.0, 1.0), (1e-3, 1.0, 0.0, 1e-300)]
+    for _ in range(2000):
+        d1 = float(10 ** rng.uniform(-4, 0))
+        cases.append((d1, float(rng.uniform(0.0, 1.0)), float((d1 * 10 ** rng.uniform(-2, 1.5)) ** 2),
+                      float(10 ** rng.uniform(-4, 0))))
+    seen = set()
+    for c in cases:
+        M = ndq.ndq_nesting_ratio_for_error(*c)
+        assert M == oracle.nesting_ratio_for_error(*c), c
+        seen.add(M)
+    assert 0 in seen and 2 in seen and len(seen) > 40
     assert ndq.ndq_sqdiff_workspace() % 8 == 0 and ndq.ndq_sqdiff_workspace() >= 8
 
 

@@ -772,6 +772,51 @@ def test_shrinkage_lowers_the_decode_error_rate_as_theorem_4_says():
     assert abs(oracle.decode_error_bound(1.0, 2, 0.5, 0.25) - (1 / 12 + 0.0625)) < 1e-15
 
 
+def test_nesting_ratio_chosen_from_theorem_4_meets_the_target_error_rate():
+    """Thm 4 and the paragraph before it: the nesting ratio is chosen so that the decode
+    error probability stays in an acceptable range.  Pins: the closed form of the smallest M
+    (the bound is c/M^2), minimality, and a Monte-Carlo run whose measured error rate at the
+    chosen M stays under the target."""
+    # closed form: bound = (1/3 + 4 alpha^2 sigma^2 / Delta_1^2) / M^2
+    assert oracle.nesting_ratio_for_error(1.0, 1.0, 0.0, 1 / 12) == 2          # (1/3)/4 = 1/12
+    assert oracle.nesting_ratio_for_error(1.0, 1.0, 0.0, 0.08) == 3            # 1/12 > 0.08 >= 1/27
+    assert oracle.nesting_ratio_for_error(0.5, 1.0, 0.25, 0.05) == 10          # c = 1/3 + 4: sqrt(86.67) = 9.3
+    assert oracle.nesting_ratio_for_error(0.5, 0.5, 0.25, 0.05) == 6           # c = 1/3 + 1: sqrt(26.67) = 5.2
+    assert oracle.nesting_ratio_for_error(1.0, 1.0, 1e6, 1e-3) == 0            # out of reach
+    assert oracle.nesting_ratio_for_error(1.0, 1.0, 0.0, 1.0) == 2             # never below 2
+    for bad in ((0.0, 1.0, 1.0, 0.1), (1.0, 1.5, 1.0, 0.1), (1.0, 1.0, -1.0, 0.1), (1.0, 1.0, 1.0, 0.0)):
+        assert oracle.nesting_ratio_for_error(*bad) == 0
+    rng = np.random.default_rng(17)
+    for _ in range(200):
+        d1 = float(10 ** rng.uniform(-4, 0))
+        s2 = float((d1 * 10 ** rng.uniform(-1, 1.2)) ** 2)
+        alpha = float(rng.uniform(0.2, 1.0))
+        p = float(10 ** rng.uniform(-3, -0.5))
+        M = oracle.nesting_ratio_for_error(d1, alpha, s2, p)
+        c = 1 / 3 + 4 * alpha ** 2 * s2 / d1 ** 2
+        expect = max(2, math.ceil(math.sqrt(c / p) - 1e-9))
+        if expect > 256:
+            assert M == 0
+            continue
+        assert abs(M - expect) <= 1 and M >= 2
+        assert oracle.decode_error_bound(d1, M, alpha, s2) <= p
+        assert M == 2 or oracle.decode_error_bound(d1, M - 1, alpha, s2) > p
+    # Monte-Carlo: measured error rate at the chosen M under the target
+    n, delta, target = 1 << 18, 0.01, 0.02
+    sigma = 1.3 * delta
+    M = oracle.nesting_ratio_for_error(delta, 1.0, sigma ** 2, target)
+    assert M == math.ceil(math.sqrt((1 / 3 + 4 * 1.69) / target))               # 19
+    y = (rng.standard_normal(n) * 0.05).astype(F)
+    g = (y + rng.standard_normal(n) * sigma).astype(F)
+    d = oracle.dither(4, 0, 1)
+    codes, steps = oracle.nested_encode(g, F(delta), 16, M, 0, d)
+    ghat = oracle.nested_decode(codes, n, M, 0, steps, d, y, 1.0)
+    wrong = np.abs(ghat.astype(np.float64) - g) > float(steps[0]) * (0.5 + 1e-3)
+    assert wrong.mean() <= target
+    # one step smaller in M would be allowed a higher rate than the target by the bound
+    assert oracle.decode_error_bound(delta, M - 1, 1.0, sigma ** 2) > target
+
+
 def test_nested_side_scale_and_accumulate_implement_the_running_mean():
     """Algorithm 2 server loop: the side information is the mean of the
     gradients decoded so far; keeping their running sum S and passing
