@@ -100,7 +100,7 @@ __device__ __forceinline__ void decode_tile(const DecodeArgs& a, const TileRef& 
                 q = (float)((int32_t)c + a.qp.q_min);
             } else {
                 yk = ys[k] * a.side_scale;
-                q = coset_index_f<MODE>(c, yk, inv, v[k], a.qp);
+                q = coset_index_f<MODE>((float)c, yk, inv, v[k], a.qp);
             }
             const float val = (MODE == kDqHalf) ? step * q
                                                 : shrink<MODE>(index_value(q, step, v[k]), yk, a.qp);
@@ -175,6 +175,11 @@ struct ChainFetch {
     float step;
 };
 
+// Code widths 1, 2 and 4: a lane's eight codes are exactly 1, 2 or 4 bytes at a
+// multiple of their size, so in a full tile one narrow load fetches them with
+// nothing to shift or join afterwards.
+__device__ __forceinline__ bool chain_aligned(uint32_t bits) { return bits == 1u || bits == 2u || bits == 4u; }
+
 template <bool FULL>
 __device__ __forceinline__ void chain_fetch(const ChainWorker& cw, const TileRef& t, int lane,
                                             ChainFetch& f)
@@ -182,6 +187,16 @@ __device__ __forceinline__ void chain_fetch(const ChainWorker& cw, const TileRef
     const uint32_t bits = cw.bits;
     const uint32_t* codes32 = (const uint32_t*)(cw.codes + (t.start >> 3) * bits);
     f.step = cw.steps[t.bucket];
+    if (FULL && chain_aligned(bits)) {
+        const unsigned char* mine = (const unsigned char*)codes32 + (uint32_t)lane * bits;
+#pragma unroll
+        for (int r = 0; r < kChainRows; ++r) {
+            const unsigned char* p = mine + (uint32_t)(r * kWave) * bits;
+            f.w0[r] = bits == 1u ? (uint32_t)*p : bits == 2u ? (uint32_t)*(const uint16_t*)p : *(const uint32_t*)p;
+            f.w1[r] = 0; f.w2[r] = 0;
+        }
+        return;
+    }
 #pragma unroll
     for (int r = 0; r < kChainRows; ++r) {
         const uint32_t o = (uint32_t)(r * kWave + lane) * kLaneElems;
@@ -200,11 +215,18 @@ __device__ __forceinline__ void chain_fetch(const ChainWorker& cw, const TileRef
     }
 }
 
-template <int MODE>
+// Folds one worker into the running sum S of a tile.  WIDTH: 1, 2, 4 = that many
+// code bits, fetched by chain_fetch's aligned path (full tiles only); -1 = any
+// width up to kFieldAsFloatMaxBits; 0 = any width.  All but 0 turn the codes into
+// floats with FieldAsFloat.  FIRST: the running sum starts with this worker.
+template <int MODE, int WIDTH, bool FIRST = false>
 __device__ __forceinline__ void chain_fold(const ChainWorker& cw, const ChainFetch& f,
                                            uint64_t block0, int lane, float (&S)[kChainRows][8])
 {
-    const uint32_t bits = cw.bits;
+    constexpr bool ALIGNED = WIDTH > 0;
+    constexpr int NF = (WIDTH == 1 || WIDTH == 2) ? 8 : 4;     // fields taken from one 32-bit group
+    const uint32_t bits = ALIGNED ? (uint32_t)WIDTH : cw.bits;
+    const FieldAsFloat<NF> field(WIDTH != 0 ? bits : 1u, MODE == kDq ? (float)cw.q_min : 0.0f);
     const float step = f.step;
     const float inv = cw.alpha * inv_step(step);
     Quant qp;
@@ -213,28 +235,55 @@ __device__ __forceinline__ void chain_fold(const ChainWorker& cw, const ChainFet
 #pragma unroll
     for (int r = 0; r < kChainRows; ++r) {
         const uint32_t o = (uint32_t)(r * kWave + lane) * kLaneElems;
-        const uint32_t sh = (o * bits) & 31u;
-        // the lane's 8*bits code bits, in two halves of four codes
-        const uint64_t low = (((uint64_t)f.w1[r] << 32) | f.w0[r]) >> sh;
-        const uint64_t high = sh ? ((uint64_t)f.w2[r] << (64u - sh)) : 0u;
-        const uint64_t chunk = low | high;
-        const uint32_t half[2] = {(uint32_t)chunk, (uint32_t)(chunk >> (4u * bits))};
+        uint32_t half[2];
+        if (ALIGNED) {
+            half[0] = f.w0[r];
+            half[1] = NF == 8 ? f.w0[r] : f.w0[r] >> (4u * bits);
+        } else {
+            const uint32_t sh = (o * bits) & 31u;
+            // the lane's 8*bits code bits, in two halves of four codes
+            const uint64_t low = (((uint64_t)f.w1[r] << 32) | f.w0[r]) >> sh;
+            const uint64_t high = sh ? ((uint64_t)f.w2[r] << (64u - sh)) : 0u;
+            const uint64_t chunk = low | high;
+            half[0] = (uint32_t)chunk;
+            half[1] = (uint32_t)(chunk >> (4u * bits));
+        }
         float v[8];
         dither8(cw.ds, block0 + (o >> 3), v);
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
-            const uint32_t c = __builtin_amdgcn_ubfe(half[k >> 2], (k & 3) * bits, bits);   // bit-field extract
+            // the code as a float: plus q_min for DQSG, as it is for a nested worker
+            float c_f;
+            if (WIDTH != 0) {
+                c_f = NF == 8 ? field.get(half[0], k) : field.get(half[k >> 2], k & 3);
+            } else {
+                const uint32_t c = __builtin_amdgcn_ubfe(half[k >> 2], (k & 3) * bits, bits);
+                c_f = MODE == kDq ? (float)((int32_t)c + qp.q_min) : (float)c;
+            }
             float q, yk = 0.0f;
             if (MODE == kDq) {
-                q = (float)((int32_t)c + qp.q_min);
+                q = c_f;
             } else {
                 yk = S[r][k] * cw.side_scale;
-                q = coset_index_f<MODE>(c, yk, inv, v[k], qp);
+                q = coset_index_f<MODE>(c_f, yk, inv, v[k], qp);
             }
             const float val = shrink<MODE>(index_value(q, step, v[k]), yk, qp);
-            S[r][k] = (MODE == kDq && cw.first) ? val : S[r][k] + val;
+            S[r][k] = FIRST ? val : S[r][k] + val;
         }
     }
+}
+
+// Picks the instantiation for a worker's code width.
+template <int MODE, bool FULL, bool FIRST>
+__device__ __forceinline__ void chain_fold_width(const ChainWorker& cw, const ChainFetch& f,
+                                                 uint64_t block0, int lane, float (&S)[kChainRows][8])
+{
+    const uint32_t bits = cw.bits;
+    if (FULL && bits == 1u) chain_fold<MODE, 1, FIRST>(cw, f, block0, lane, S);
+    else if (FULL && bits == 2u) chain_fold<MODE, 2, FIRST>(cw, f, block0, lane, S);
+    else if (FULL && bits == 4u) chain_fold<MODE, 4, FIRST>(cw, f, block0, lane, S);
+    else if (bits <= kFieldAsFloatMaxBits) chain_fold<MODE, -1, FIRST>(cw, f, block0, lane, S);
+    else chain_fold<MODE, 0, FIRST>(cw, f, block0, lane, S);
 }
 
 template <bool FULL>
@@ -258,10 +307,16 @@ __device__ __forceinline__ void chain_tile(const ChainArgs& a, const TileRef& t,
         const ChainWorker& cw = a.w[w];
         if (w + 1 < a.W) chain_fetch<FULL>(a.w[w + 1], t, lane, nxt);
         const uint64_t block0 = (cw.index0 + t.start) >> 3;
-        if (cw.mode == kDq) chain_fold<kDq>(cw, cur, block0, lane, S);
-        else if (cw.mode == kNestedPow2) chain_fold<kNestedPow2>(cw, cur, block0, lane, S);
-        else if (cw.mode == kNestedPow2Shrink) chain_fold<kNestedPow2Shrink>(cw, cur, block0, lane, S);
-        else chain_fold<kNestedAnyM>(cw, cur, block0, lane, S);
+        if (cw.mode == kDq) {
+            if (cw.first) chain_fold_width<kDq, FULL, true>(cw, cur, block0, lane, S);
+            else chain_fold_width<kDq, FULL, false>(cw, cur, block0, lane, S);
+        } else if (cw.mode == kNestedPow2) {
+            chain_fold_width<kNestedPow2, FULL, false>(cw, cur, block0, lane, S);
+        } else if (cw.mode == kNestedPow2Shrink) {
+            chain_fold_width<kNestedPow2Shrink, FULL, false>(cw, cur, block0, lane, S);
+        } else {
+            chain_fold_width<kNestedAnyM, FULL, false>(cw, cur, block0, lane, S);
+        }
         cur = nxt;
     }
 #pragma unroll

@@ -197,14 +197,40 @@ __device__ __forceinline__ float index_value(float q, float step, float v)
     return step * centred;
 }
 
+// Field j of a packed group of codes as a float, plus a constant, in two
+// full-rate operations instead of extract + add + convert: the field is masked
+// in place into the mantissa of 2^23 (the float 2^23 + c 2^(j b), an integer, so
+// exact), then one fma scales it down and removes the 2^23 -- every product and
+// sum is exactly representable, so the result is c + constant with no rounding.
+// Needs (j + 1) b <= 23.
+template <int NF>
+struct FieldAsFloat {
+    uint32_t mask[NF];
+    float scale[NF], offset[NF];
+    __device__ __forceinline__ FieldAsFloat(uint32_t bits, float constant)
+    {
+#pragma unroll
+        for (uint32_t j = 0; j < (uint32_t)NF; ++j) {
+            mask[j] = ((1u << bits) - 1u) << (j * bits);
+            scale[j] = __uint_as_float((127u - j * bits) << 23);
+            offset[j] = constant - __uint_as_float((150u - j * bits) << 23);
+        }
+    }
+    __device__ __forceinline__ float get(uint32_t group, int j) const
+    {
+        const uint32_t x = __builtin_amdgcn_bitop3_b32(group, mask[j], 0x4B000000u, 0xEA);  // (group & mask) | 2^23
+        return __builtin_fmaf(__uint_as_float(x), scale[j], offset[j]);
+    }
+};
+constexpr uint32_t kFieldAsFloatMaxBits = 5;   // four fields of a group stay inside 23 bits
+
 // Coset decoder of eq. (8), alpha = 1: the integer congruent to m (mod M) nearest
 // to y/Delta + v, returned as a float.  m + M*k is formed by one fma: exact while
 // below 2^24 and otherwise rounded once, exactly like converting the integer.
 template <int MODE>
-__device__ __forceinline__ float coset_index_f(uint32_t m, float y, float inv, float v,
+__device__ __forceinline__ float coset_index_f(float m_f, float y, float inv, float v,
                                                const Quant& qp)
 {
-    const float m_f = (float)m;
     const float c = __builtin_fmaf(y, inv, v);
     const float diff = c - m_f;
     float k = (MODE == kNestedPow2 || MODE == kNestedPow2Shrink) ? diff * qp.inv_M_f : diff / qp.M_f;
