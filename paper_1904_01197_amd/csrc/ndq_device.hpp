@@ -134,8 +134,12 @@ __device__ __forceinline__ float inv_step(float step)
 //   kNestedPow2   : NDQSG, M a power of two (mask / exact scale); decoder: alpha = 1
 //   kNestedPow2Shrink : decoder only: M a power of two, shrinkage factor alpha < 1
 //   kNestedAnyM   : NDQSG, any M in [2,256], any shrinkage factor alpha in (0,1]
+//   kNestedPow2Bounded : encoder only: M a power of two and the step derived from
+//                   the bucket's own max-norm, so |g/Delta + v| <= 128.1 (see
+//                   nested_low_bits)
 // ---------------------------------------------------------------------------
-enum Mode { kDq = 0, kNestedPow2 = 1, kNestedAnyM = 2, kDqNarrow = 3, kDqHalf = 4, kNestedPow2Shrink = 5 };
+enum Mode { kDq = 0, kNestedPow2 = 1, kNestedAnyM = 2, kDqNarrow = 3, kDqHalf = 4, kNestedPow2Shrink = 5,
+            kNestedPow2Bounded = 6 };
 
 struct Quant {
     float q_min_f, q_max_f;  // DQSG index range as floats
@@ -172,6 +176,18 @@ __device__ __forceinline__ uint32_t nested_code(float g, float inv, float v, con
     int32_t m = q % (int32_t)qp.M;
     if (m < 0) m += (int32_t)qp.M;
     return (uint32_t)m;
+}
+
+// Fine index of eq. (7) for |t| < 2^22, t = g/Delta + v, as a word whose low 22
+// bits are the index in two's complement: adding 1.5 * 2^23 moves t into the
+// binade whose unit in the last place is 1, so that one addition rounds it to
+// the nearest integer, ties to even (1.5 * 2^23 is even: the parity of the sum is
+// the parity of the index) -- exactly rint(t), without convert or mask.  The
+// index mod 2^b is then the low b bits.
+__device__ __forceinline__ uint32_t nested_low_bits(float g, float inv, float v)
+{
+    const float t = __builtin_fmaf(g, inv, v);
+    return __float_as_uint(t + 12582912.0f);
 }
 
 template <int MODE>

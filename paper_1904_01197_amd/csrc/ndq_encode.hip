@@ -86,6 +86,17 @@ __device__ __forceinline__ void encode_tile(const EncodeArgs& a, const TileRef& 
                     acc = __builtin_fmaf(q, __uint_as_float((127u + k * bits) << 23), acc);
                 }
                 chunk = (uint32_t)acc;
+            } else if (MODE == kNestedPow2Bounded) {
+                // each code enters at the top of the word and moves down as the next
+                // ones arrive: one funnel shift per code keeps exactly its low `bits` bits
+                uint32_t acc = 0;
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    uint32_t low = nested_low_bits(T::get(raw[r], 4 * h + k), inv, v[4 * h + k]);
+                    if (!FULL && o + 4 * h + k >= t.len) low = 0;
+                    acc = __builtin_amdgcn_alignbit(low, acc, bits);
+                }
+                chunk = acc >> (32u - 4u * bits);
             } else {
 #pragma unroll
                 for (int k = 0; k < 4; ++k) {
@@ -118,7 +129,10 @@ __device__ __forceinline__ void encode_tile(const EncodeArgs& a, const TileRef& 
 // burst of loads at the start of every tile; eight waves per SIMD (64 registers)
 // hide that burst better than four (+8 % measured).  The binary32 encoder moves
 // twice the bytes per element and measured best with the registers it asks for.
-template <int DT> struct EncWaves { static constexpr int W = DT == 1 ? 8 : 4; };
+#ifndef NDQ_ENC_WAVES_BF16
+#define NDQ_ENC_WAVES_BF16 8
+#endif
+template <int DT> struct EncWaves { static constexpr int W = DT == 1 ? NDQ_ENC_WAVES_BF16 : 4; };
 template <int DT, int MODE, bool FUSED>
 __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(EncWaves<DT>::W)))
 void encode_kernel(EncodeArgs a)
@@ -256,17 +270,21 @@ static int encode_common(const void* g, ndq_dtype dt, size_t n, float delta, uin
 #ifndef NDQ_NARROW_MAX_BITS
 #define NDQ_NARROW_MAX_BITS 6u
 #endif
+    // a step derived from the data bounds |g/Delta|; a caller's preset step does not
     const int mode = !nested ? (a.qp.bits <= NDQ_NARROW_MAX_BITS ? kDqNarrow : kDq)
-                             : (is_pow2(M) ? kNestedPow2 : kNestedAnyM);
+                             : (!is_pow2(M) ? kNestedAnyM
+                                            : (a.preset_step > 0.0f ? kNestedPow2 : kNestedPow2Bounded));
     if (dt == NDQ_F32) {
         if (mode == kDqNarrow) return run_encode<0, kDqNarrow>(a, fused, s);
         if (mode == kDq) return run_encode<0, kDq>(a, fused, s);
         if (mode == kNestedPow2) return run_encode<0, kNestedPow2>(a, fused, s);
+        if (mode == kNestedPow2Bounded) return run_encode<0, kNestedPow2Bounded>(a, fused, s);
         return run_encode<0, kNestedAnyM>(a, fused, s);
     }
     if (mode == kDqNarrow) return run_encode<1, kDqNarrow>(a, fused, s);
     if (mode == kDq) return run_encode<1, kDq>(a, fused, s);
     if (mode == kNestedPow2) return run_encode<1, kNestedPow2>(a, fused, s);
+    if (mode == kNestedPow2Bounded) return run_encode<1, kNestedPow2Bounded>(a, fused, s);
     return run_encode<1, kNestedAnyM>(a, fused, s);
 }
 
