@@ -247,6 +247,43 @@ def test_nested_encode_decode_matches_oracle(dtype, M, levels, bucket):
         assert np.array_equal(s_inp.cpu().numpy(), ref_inp)
 
 
+@pytest.mark.parametrize("bucket", [0, 2048])
+def test_exact_rounding_ties_go_to_the_even_index_on_the_gpu_too(bucket):
+    """Every element is built so that g/Delta + v is exactly an integer plus one half (the
+    step is exactly 1: max|g| = 2 with 5 levels): the encoders must break the tie like
+    rint, towards the even index.  Exercises the magic-constant rounding of the nested
+    encoder, the DQSG encoder, and the decoders on the codes that result."""
+    n = 3 * 2048 + 192
+    d_o, d_g = oracle.dither(5, 1, 3), ndq.ndq_dither(5, 1, 3, 0)
+    v = oracle.unit_dithers(d_o, n).astype(np.float64)
+    rng = np.random.default_rng(8)
+    half = rng.choice(np.array([-1.5, -0.5, 0.5, 1.5]), n)
+    g = (half - v).astype(F)
+    assert np.array_equal(g.astype(np.float64) + v, half)          # exact ties in binary32
+    g[::2048] = F(2.0)                                             # pins every bucket's max-norm
+    g[-1] = F(-2.0)
+    gd = _to_dev(g)
+    for levels, M in ((5, 2), (5, 4), (5, 8)):
+        c_ref, s_ref = oracle.nested_encode(g, 0.0, levels, M, bucket, d_o)
+        assert np.all(s_ref == F(1.0))
+        codes, steps = ndq.ndq_nested_encode(gd, 0.0, levels, M, 1.0, bucket, d_g)
+        assert np.array_equal(steps.cpu().numpy(), s_ref)
+        assert codes.cpu().numpy().tobytes() == c_ref.tobytes(), (levels, M)
+        # the tie rule itself: the index is the even neighbour
+        q = oracle.fine_indices(g, bucket, s_ref, d_o)
+        ties = np.ones(n, bool); ties[::2048] = False; ties[-1] = False
+        assert np.all(q[ties] % 2 == 0) and np.array_equal(np.abs(q[ties] - half[ties]), np.full(ties.sum(), 0.5))
+        side = (g + F(0.25)).astype(F)
+        ref = oracle.nested_decode(c_ref, n, M, bucket, s_ref, d_o, side, 1.0)
+        out = ndq.ndq_nested_decode(codes, n, M, 1.0, bucket, steps, d_g, _to_dev(side), 1.0)
+        assert np.array_equal(out.cpu().numpy(), ref)
+    c_ref, s_ref = oracle.dq_encode(g, 0.0, 5, bucket, d_o)
+    codes, steps = ndq.ndq_dq_encode(gd, 0.0, 5, bucket, d_g)
+    assert codes.cpu().numpy().tobytes() == c_ref.tobytes()
+    assert np.array_equal(ndq.ndq_dq_decode(codes, n, 5, bucket, steps, d_g).cpu().numpy(),
+                          oracle.dq_decode(c_ref, n, 5, bucket, s_ref, d_o))
+
+
 def test_nested_equals_dqsg_inside_guaranteed_region_on_gpu():
     """|g - y| < (M-1) Delta / 2  =>  the nested reconstruction is the DQSG one."""
     n, M, levels = 1 << 18, 4, 64
