@@ -50,23 +50,41 @@ def parse_args():
     return ap.parse_args()
 
 
-VALU_PEAK_TOPS = 256 * 64 * 2.4e9 / 1e12   # 256 CUs x 64 lanes x 2.4 GHz = 39.3 T lane-ops/s
+# VALU roof.  A gfx950 SIMD retires a wave64 instruction of the simple classes
+# (fp32 add/mul/fma, integer add, logic) in 2 cycles and one of the other classes
+# (conversions, shifts and bit-fields, min/max/med3, rounding, 32-bit integer
+# multiplies) in 4: 256 CUs x 4 SIMDs x 32 lanes x 2.4 GHz = 78.6 T full-rate
+# lane-operations/s, which is the published 157.3 TFLOP/s fp32 figure at 2 flops
+# per fma.  Work is counted in full-rate equivalents: a half-rate operation is 2.
+VALU_PEAK_TOPS = 256 * 4 * 32 * 2.4e9 / 1e12
 
-# Algorithmic 32-bit lane-operations per element, counted from the arithmetic the
-# header states on a machine with a 32x32->64 multiply, a three-input logic op and
-# fma (what gfx950 has); work that is uniform across a wave (key schedule, step,
-# 1/step) is not counted.
-OPS_PHILOX = 5      # 10 rounds x (2 multiplies + 2 three-input xors) per 8 elements
-OPS_DITHER = 3      # take the 16-bit half, convert, fma onto the mid-point grid
+# Algorithmic lane-operations per element in full-rate equivalents, counted from
+# the arithmetic the header states on a machine with a 32x32->64 multiply, a
+# three-input logic op and fma (what gfx950 has); work that is uniform across a
+# wave (key schedule, step, 1/step) is not counted.
+OPS_PHILOX = (20 * 2 + 20 * 1) / 8.0   # 10 rounds x (2 multiplies (half rate) + 2 xor3) per 8 elements
+OPS_DITHER = 2 + 1                      # convert the 16-bit half (half rate), fma onto the mid-point grid
+
+
+def _ops_encode(bf16, nested_pow2_own_step):
+    widen = 1.5 if bf16 else 0.0        # low half: shift (2), high half: mask (1)
+    absmax = 1.0 if bf16 else 2.0       # packed 16-bit max per 2 elements / max(|.|)
+    if nested_pow2_own_step:            # fma, magic-constant add, funnel shift (2)
+        quant = 1 + 1 + 2
+    else:                               # fma, rint (2), clip (2), pack fma, convert per 4 codes
+        quant = 1 + 2 + 2 + 1 + 0.5
+    return OPS_PHILOX + OPS_DITHER + widen + absmax + quant
+
+
 OPS = {
-    # widen (bf16) + |.|max + fma + rint + clip + offset/pack (2)
-    "encode": lambda bf16: OPS_PHILOX + OPS_DITHER + 7 + (1 if bf16 else 0),
-    # extract + offset + convert + subtract dither + scale (+ add when accumulating)
-    "dq_decode_store": lambda bf16: OPS_PHILOX + OPS_DITHER + 5,
-    "dq_decode_accumulate": lambda bf16: OPS_PHILOX + OPS_DITHER + 6,
-    # extract, convert, side scale, fma, subtract, divide by M, rint, clamp, fma,
-    # subtract dither, scale, add to the running sum
-    "nested_decode": lambda bf16: OPS_PHILOX + OPS_DITHER + 12,
+    "dq_encode": lambda bf16: _ops_encode(bf16, False),
+    "nested_encode": lambda bf16: _ops_encode(bf16, True),
+    # code -> float (mask, fma) + subtract dither + scale (+ add when accumulating)
+    "dq_decode_store": lambda bf16: OPS_PHILOX + OPS_DITHER + 4,
+    "dq_decode_accumulate": lambda bf16: OPS_PHILOX + OPS_DITHER + 5,
+    # code -> float (2), side scale, fma, subtract, divide by M, rint (2), clamp (2),
+    # fma, subtract dither, scale, add to the running sum
+    "nested_decode": lambda bf16: OPS_PHILOX + OPS_DITHER + 15,
 }
 
 
@@ -206,8 +224,10 @@ def main():
         count += 1
         chain_bytes += (n * bits + 7) // 8 + 4 * K
         chain_ops += n * OPS[dkind](bf16)
-        calls.append((enc_key, enc, algorithmic_bytes("encode", n, bits, K, s_in),
-                      n * OPS["encode"](bf16)))
+        own_step = wl.bucket != 0 or preset == 0.0
+        enc_ops = OPS["nested_encode" if (kind != "dq" and arg & (arg - 1) == 0 and own_step)
+                      else "dq_encode"](bf16)
+        calls.append((enc_key, enc, algorithmic_bytes("encode", n, bits, K, s_in), n * enc_ops))
         decs.append((dec_key, dec, algorithmic_bytes(dkind, n, bits, K, s_in),
                      n * OPS[dkind](bf16)))
     if args.schedule == "fused":
@@ -269,7 +289,7 @@ def main():
     else:
         roofline = {"bound": "alu", "kernel": dominant["kernel"],
                     "achieved": round(alu_frac * VALU_PEAK_TOPS, 2),
-                    "peak": round(VALU_PEAK_TOPS, 2), "unit": "Tlane-op/s",
+                    "peak": round(VALU_PEAK_TOPS, 2), "unit": "Tlane-op/s (full-rate equivalents)",
                     "frac": round(alu_frac, 4)}
     roofline.update({"traffic": measured_traffic(dominant["kernel"]),
                      "algorithmic_bytes_per_launch": dominant["algorithmic_bytes"],

@@ -10,7 +10,6 @@ CSRC = os.path.join(HERE, "csrc")
 SOURCES = [os.path.join(CSRC, f) for f in ("ndq_encode.hip", "ndq_decode.hip", "ndq_tools.hip")]
 HEADERS = [os.path.join(CSRC, "ndq_device.hpp"), os.path.join(CSRC, "ndq_host.hpp"),
            os.path.join(ROOT, "include", "ndq.h")]
-OBJDIR = os.path.join(HERE, "_build")
 
 HIPCC_FLAGS = [
     "-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC",
@@ -38,7 +37,8 @@ def build_library(force=True, verbose=False, so=None):
     if force or stale:
         hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
         extra = os.environ.get("NDQ_EXTRA_HIPCC_FLAGS", "").split()
-        objdir = OBJDIR + "_" + os.path.basename(so).replace(".", "_")
+        objdir = os.path.join(os.path.dirname(os.path.abspath(so)),
+                              "_build_" + os.path.basename(so).replace(".", "_"))
         os.makedirs(objdir, exist_ok=True)
         inc = ["-I", os.path.join(ROOT, "include"), "-I", CSRC]
         objs = [os.path.join(objdir, os.path.basename(src) + ".o") for src in SOURCES]
