@@ -199,6 +199,52 @@ __global__ __launch_bounds__(kBlock) void absmax_kernel(const void* g, Tiling tl
     if (lane == 0) atomicMax(kappa_bits + t.bucket, __float_as_uint(m));
 }
 
+// The same for buckets of many tiles (a whole vector at the extreme), where one
+// atomic per tile would serialize every tile on one address: a workgroup's
+// waves stride over the bucket's tiles with the running max in registers, and
+// the workgroup issues a single atomic at the end.
+template <int DT>
+__global__ __launch_bounds__(kBlock) void absmax_span_kernel(const void* g, Tiling tl, uint32_t* kappa_bits,
+                                                            uint32_t blocks_per_bucket)
+{
+    using T = Elem<DT>;
+    constexpr uint32_t TILE = EncTile<DT>::N;
+    constexpr int ROWS = EncRows<DT>::R;
+    __shared__ float part[kWavesPerBlock];
+    const int lane = threadIdx.x & (kWave - 1);
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const uint32_t bucket = blockIdx.x / blocks_per_bucket;
+    const uint32_t first = (blockIdx.x - bucket * blocks_per_bucket) * kWavesPerBlock + wave;
+    const uint32_t stride = blocks_per_bucket * kWavesPerBlock;
+    typename T::maxacc acc = T::max_init();
+    for (uint32_t j = first; j < tl.tiles_per_bucket; j += stride) {
+        const TileRef t = locate_tile(tl, bucket * tl.tiles_per_bucket + j, TILE);
+        if (t.len == 0) break;   // past the end of the vector: so are this wave's later tiles
+        const typename T::scalar* tile = (const typename T::scalar*)g + t.start;
+        typename T::Row raw[ROWS];
+        if (t.len == TILE) {
+#pragma unroll
+            for (int r = 0; r < ROWS; ++r)
+                raw[r] = load_row<DT, true>(tile, (uint32_t)(r * kWave + lane) * kLaneElems, t.len);
+        } else {
+#pragma unroll
+            for (int r = 0; r < ROWS; ++r)
+                raw[r] = load_row<DT, false>(tile, (uint32_t)(r * kWave + lane) * kLaneElems, t.len);
+        }
+#pragma unroll
+        for (int r = 0; r < ROWS; ++r) acc = T::max_update(acc, raw[r]);
+    }
+    const float m = wave_max(T::max_final(acc));
+    if (lane == 0) part[wave] = m;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float all = part[0];
+#pragma unroll
+        for (int w = 1; w < kWavesPerBlock; ++w) all = __builtin_fmaxf(all, part[w]);
+        atomicMax(kappa_bits + bucket, __float_as_uint(all));
+    }
+}
+
 __global__ void steps_from_kappa_kernel(float* steps, uint64_t K, uint32_t levels)
 {
     const uint64_t b = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -214,6 +260,17 @@ static int run_absmax(const void* g, const Tiling& tl, uint64_t K, float* kappa,
     hipLaunchKernelGGL(fill_zero_kernel, dim3((uint32_t)((K + 255) / 256)), dim3(256), 0, s,
                        (uint32_t*)kappa, K);
     if (launched() != NDQ_OK) return NDQ_ELAUNCH;
+    // many tiles per bucket: a few hundred tiles per workgroup, about 4096 workgroups in all
+    constexpr uint32_t kSpanMinTiles = 64, kSpanTarget = 4096;
+    if (tl.tiles_per_bucket >= kSpanMinTiles && K <= kSpanTarget) {
+        uint32_t per_bucket = kSpanTarget / (uint32_t)K;
+        const uint32_t most = tl.tiles_per_bucket / (2 * kWavesPerBlock);   // at least two tiles per wave
+        if (per_bucket > most) per_bucket = most;
+        if (per_bucket < 1) per_bucket = 1;
+        hipLaunchKernelGGL(absmax_span_kernel<DT>, dim3((uint32_t)K * per_bucket), dim3(kBlock), 0, s, g, tl,
+                           (uint32_t*)kappa, per_bucket);
+        return launched();
+    }
     hipLaunchKernelGGL(absmax_kernel<DT>, dim3(blocks_for(tl.total_tiles)), dim3(kBlock), 0, s, g, tl,
                        (uint32_t*)kappa);
     return launched();

@@ -134,6 +134,30 @@ def test_absmax_matches_oracle(dtype):
             assert np.array_equal(got, ref), (n, bucket)
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_absmax_of_buckets_that_span_many_tiles(dtype):
+    """Whole-vector and very large buckets take the kernel whose workgroups stride over a
+    bucket's tiles; the maximum sits in a different place for every bucket, the last
+    bucket is short and ragged, and the encoder that reads those steps must agree too."""
+    n = 5 * (1 << 18) + 4096 * 3 + 77 * 8
+    g = _make(n, dtype, seed=31)
+    gf = workloads.bf16_bits_to_f32(g) if dtype == "bf16" else g
+    peak = F(np.abs(gf).max() * 3)
+    for b, pos in enumerate((5, (1 << 18) + 262143, 2 * (1 << 18) + 131072, 3 * (1 << 18) + 70001,
+                             4 * (1 << 18) + 1, n - 1)):
+        val = np.array([peak * F(1 + b)], dtype=F)
+        g[pos] = workloads.f32_to_bf16_bits(val)[0] if dtype == "bf16" else val[0]
+    gd = _to_dev(g)
+    d_o, d_g = oracle.dither(2, 0, 1), ndq.ndq_dither(2, 0, 1, 0)
+    for bucket in (0, 1 << 18, 1 << 19):
+        ref = oracle.absmax(g, bucket)
+        assert np.array_equal(ndq.ndq_absmax(gd, bucket).cpu().numpy(), ref), bucket
+        c_ref, s_ref = oracle.dq_encode(g, 0.0, 16, bucket, d_o)
+        codes, steps = ndq.ndq_dq_encode(gd, 0.0, 16, bucket, d_g)
+        assert np.array_equal(steps.cpu().numpy(), s_ref), bucket
+        assert codes.cpu().numpy().tobytes() == c_ref.tobytes(), bucket
+
+
 def test_degenerate_inputs():
     dev = _gpu()
     d_o, d_g = oracle.dither(1, 1, 1), ndq.ndq_dither(1, 1, 1, 0)
