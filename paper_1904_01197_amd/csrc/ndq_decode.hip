@@ -166,13 +166,15 @@ struct ChainArgs {
     int continue_sum;     // S starts from out (an earlier group of workers)
     int apply_scale;
     float scale;
+    uint32_t row_buckets; // 1: a bucket is one row of a tile (tiling is by tile, a step per row)
+    uint32_t num_buckets;
 };
 
 // What is prefetched per worker: the step and, per row, the words holding the
 // lane's eight codes (8*bits bits starting at a multiple of 8 bits).
 struct ChainFetch {
     uint32_t w0[kChainRows], w1[kChainRows], w2[kChainRows];
-    float step;
+    float step[kChainRows];
 };
 
 // Code widths 1, 2 and 4: a lane's eight codes are exactly 1, 2 or 4 bytes at a
@@ -180,13 +182,23 @@ struct ChainFetch {
 // nothing to shift or join afterwards.
 __device__ __forceinline__ bool chain_aligned(uint32_t bits) { return bits == 1u || bits == 2u || bits == 4u; }
 
-template <bool FULL>
-__device__ __forceinline__ void chain_fetch(const ChainWorker& cw, const TileRef& t, int lane,
-                                            ChainFetch& f)
+// ROWB: a bucket is one row of the tile (the tiling is by tile and every row has
+// its own step); otherwise one step serves the tile.
+template <bool FULL, bool ROWB>
+__device__ __forceinline__ void chain_fetch(const ChainArgs& a, const ChainWorker& cw, const TileRef& t,
+                                            int lane, ChainFetch& f)
 {
     const uint32_t bits = cw.bits;
     const uint32_t* codes32 = (const uint32_t*)(cw.codes + (t.start >> 3) * bits);
-    f.step = cw.steps[t.bucket];
+    if (ROWB) {
+#pragma unroll
+        for (int r = 0; r < kChainRows; ++r) {
+            const uint32_t b = t.bucket * kChainRows + r;          // rows past the last bucket get 0
+            f.step[r] = b < a.num_buckets ? cw.steps[b] : 0.0f;
+        }
+    } else {
+        f.step[0] = cw.steps[t.bucket];
+    }
     if (FULL && chain_aligned(bits)) {
         const unsigned char* mine = (const unsigned char*)codes32 + (uint32_t)lane * bits;
 #pragma unroll
@@ -219,7 +231,7 @@ __device__ __forceinline__ void chain_fetch(const ChainWorker& cw, const TileRef
 // code bits, fetched by chain_fetch's aligned path (full tiles only); -1 = any
 // width up to kFieldAsFloatMaxBits; 0 = any width.  All but 0 turn the codes into
 // floats with FieldAsFloat.  FIRST: the running sum starts with this worker.
-template <int MODE, int WIDTH, bool FIRST = false>
+template <int MODE, int WIDTH, bool FIRST, bool ROWB>
 __device__ __forceinline__ void chain_fold(const ChainWorker& cw, const ChainFetch& f,
                                            uint64_t block0, int lane, float (&S)[kChainRows][8])
 {
@@ -227,14 +239,17 @@ __device__ __forceinline__ void chain_fold(const ChainWorker& cw, const ChainFet
     constexpr int NF = (WIDTH == 1 || WIDTH == 2) ? 8 : 4;     // fields taken from one 32-bit group
     const uint32_t bits = ALIGNED ? (uint32_t)WIDTH : cw.bits;
     const FieldAsFloat<NF> field(WIDTH != 0 ? bits : 1u, MODE == kDq ? (float)cw.q_min : 0.0f);
-    const float step = f.step;
-    const float inv = cw.alpha * inv_step(step);
+    float inv_row[kChainRows];
+#pragma unroll
+    for (int r = 0; r < kChainRows; ++r)
+        inv_row[r] = (ROWB || r == 0) ? cw.alpha * inv_step(f.step[ROWB ? r : 0]) : inv_row[0];
     Quant qp;
     qp.M = cw.M; qp.M_f = cw.M_f; qp.inv_M_f = cw.inv_M_f; qp.q_min = cw.q_min;
     qp.alpha = cw.alpha; qp.beta = cw.beta;
 #pragma unroll
     for (int r = 0; r < kChainRows; ++r) {
         const uint32_t o = (uint32_t)(r * kWave + lane) * kLaneElems;
+        const float step = f.step[ROWB ? r : 0], inv = inv_row[r];
         uint32_t half[2];
         if (ALIGNED) {
             half[0] = f.w0[r];
@@ -274,19 +289,19 @@ __device__ __forceinline__ void chain_fold(const ChainWorker& cw, const ChainFet
 }
 
 // Picks the instantiation for a worker's code width.
-template <int MODE, bool FULL, bool FIRST>
+template <int MODE, bool FULL, bool FIRST, bool ROWB>
 __device__ __forceinline__ void chain_fold_width(const ChainWorker& cw, const ChainFetch& f,
                                                  uint64_t block0, int lane, float (&S)[kChainRows][8])
 {
     const uint32_t bits = cw.bits;
-    if (FULL && bits == 1u) chain_fold<MODE, 1, FIRST>(cw, f, block0, lane, S);
-    else if (FULL && bits == 2u) chain_fold<MODE, 2, FIRST>(cw, f, block0, lane, S);
-    else if (FULL && bits == 4u) chain_fold<MODE, 4, FIRST>(cw, f, block0, lane, S);
-    else if (bits <= kFieldAsFloatMaxBits) chain_fold<MODE, -1, FIRST>(cw, f, block0, lane, S);
-    else chain_fold<MODE, 0, FIRST>(cw, f, block0, lane, S);
+    if (FULL && bits == 1u) chain_fold<MODE, 1, FIRST, ROWB>(cw, f, block0, lane, S);
+    else if (FULL && bits == 2u) chain_fold<MODE, 2, FIRST, ROWB>(cw, f, block0, lane, S);
+    else if (FULL && bits == 4u) chain_fold<MODE, 4, FIRST, ROWB>(cw, f, block0, lane, S);
+    else if (bits <= kFieldAsFloatMaxBits) chain_fold<MODE, -1, FIRST, ROWB>(cw, f, block0, lane, S);
+    else chain_fold<MODE, 0, FIRST, ROWB>(cw, f, block0, lane, S);
 }
 
-template <bool FULL>
+template <bool FULL, bool ROWB>
 __device__ __forceinline__ void chain_tile(const ChainArgs& a, const TileRef& t, int lane)
 {
     float S[kChainRows][8];
@@ -301,21 +316,21 @@ __device__ __forceinline__ void chain_tile(const ChainArgs& a, const TileRef& t,
         }
     }
     ChainFetch cur;
-    chain_fetch<FULL>(a.w[0], t, lane, cur);
+    chain_fetch<FULL, ROWB>(a, a.w[0], t, lane, cur);
     ChainFetch nxt = cur;
     for (uint32_t w = 0; w < a.W; ++w) {
         const ChainWorker& cw = a.w[w];
-        if (w + 1 < a.W) chain_fetch<FULL>(a.w[w + 1], t, lane, nxt);
+        if (w + 1 < a.W) chain_fetch<FULL, ROWB>(a, a.w[w + 1], t, lane, nxt);
         const uint64_t block0 = (cw.index0 + t.start) >> 3;
         if (cw.mode == kDq) {
-            if (cw.first) chain_fold_width<kDq, FULL, true>(cw, cur, block0, lane, S);
-            else chain_fold_width<kDq, FULL, false>(cw, cur, block0, lane, S);
+            if (cw.first) chain_fold_width<kDq, FULL, true, ROWB>(cw, cur, block0, lane, S);
+            else chain_fold_width<kDq, FULL, false, ROWB>(cw, cur, block0, lane, S);
         } else if (cw.mode == kNestedPow2) {
-            chain_fold_width<kNestedPow2, FULL, false>(cw, cur, block0, lane, S);
+            chain_fold_width<kNestedPow2, FULL, false, ROWB>(cw, cur, block0, lane, S);
         } else if (cw.mode == kNestedPow2Shrink) {
-            chain_fold_width<kNestedPow2Shrink, FULL, false>(cw, cur, block0, lane, S);
+            chain_fold_width<kNestedPow2Shrink, FULL, false, ROWB>(cw, cur, block0, lane, S);
         } else {
-            chain_fold_width<kNestedAnyM, FULL, false>(cw, cur, block0, lane, S);
+            chain_fold_width<kNestedAnyM, FULL, false, ROWB>(cw, cur, block0, lane, S);
         }
         cur = nxt;
     }
@@ -341,6 +356,7 @@ __device__ __forceinline__ void chain_tile(const ChainArgs& a, const TileRef& t,
 #ifndef NDQ_CHAIN_WAVES_PER_EU
 #define NDQ_CHAIN_WAVES_PER_EU 6
 #endif
+template <bool ROWB>
 __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(NDQ_CHAIN_WAVES_PER_EU)))
 void chain_kernel(ChainArgs a)
 {
@@ -348,8 +364,8 @@ void chain_kernel(ChainArgs a)
     const uint32_t tile_id =
         blockIdx.x * kWavesPerBlock + __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     const TileRef t = locate_tile(a.tl, tile_id, kChainTile);
-    if (t.len == kChainTile) chain_tile<true>(a, t, lane);
-    else if (t.len != 0) chain_tile<false>(a, t, lane);
+    if (t.len == kChainTile) chain_tile<true, ROWB>(a, t, lane);
+    else if (t.len != 0) chain_tile<false, ROWB>(a, t, lane);
 }
 
 // ---------------------------------------------------------------------------
@@ -549,7 +565,10 @@ int ndq_decode_chain(const ndq_worker* workers, uint32_t W, size_t n, uint32_t b
             return NDQ_EALIGN;
     }
     ChainArgs a;
-    int rc = make_tiling(n, bucket, kChainTile, &a.tl);
+    // buckets of exactly one row share a tile, each row with its own step
+    a.row_buckets = (kChainRows > 1 && bucket == kWave * kLaneElems) ? 1u : 0u;
+    a.num_buckets = (uint32_t)ndq_num_buckets(n, bucket);
+    int rc = make_tiling(n, a.row_buckets ? kChainTile : bucket, kChainTile, &a.tl);
     if (rc != NDQ_OK) return rc;
     a.out = out;
     a.scale = scale;
@@ -580,8 +599,12 @@ int ndq_decode_chain(const ndq_worker* workers, uint32_t W, size_t n, uint32_t b
                                  : (wk.alpha == 1.0f ? kNestedPow2 : kNestedPow2Shrink));
             cw.first = (p0 + j) == 0u;
         }
-        hipLaunchKernelGGL(chain_kernel, dim3(blocks_for(a.tl.total_tiles)), dim3(kBlock), 0,
-                           (hipStream_t)stream, a);
+        if (a.row_buckets)
+            hipLaunchKernelGGL(chain_kernel<true>, dim3(blocks_for(a.tl.total_tiles)), dim3(kBlock), 0,
+                               (hipStream_t)stream, a);
+        else
+            hipLaunchKernelGGL(chain_kernel<false>, dim3(blocks_for(a.tl.total_tiles)), dim3(kBlock), 0,
+                               (hipStream_t)stream, a);
         if (launched() != NDQ_OK) return NDQ_ELAUNCH;
     }
     return NDQ_OK;

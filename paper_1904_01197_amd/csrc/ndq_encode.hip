@@ -27,6 +27,8 @@ struct EncodeArgs {
     DitherStream ds;
     Quant qp;
     float preset_step;     // > 0: bucket == 0 with a caller-set step
+    uint32_t rows_log2;    // MULTI: a bucket is 2^rows_log2 rows of a tile
+    uint32_t num_buckets;  // MULTI: buckets in the call (steps to write)
 };
 
 template <int DT> struct EncRows { static constexpr int R = kEncLoads / Elem<DT>::V; };
@@ -36,8 +38,9 @@ template <int DT> struct EncTile { static constexpr uint32_t N = kWave * kLaneEl
 // finds the step, quantizes, and leaves the packed codes in `stage` in stream
 // order.  A lane owns 8 consecutive elements per row: one Philox block, and
 // 8 codes = `bits` whole bytes of the stream.  FULL: every element of the tile
-// is valid -- no guards anywhere.
-template <int DT, int MODE, bool FUSED, bool FULL>
+// is valid -- no guards anywhere.  MULTI (with FUSED): the bucket is a whole
+// number of rows and several buckets share the tile, each with its own step.
+template <int DT, int MODE, bool FUSED, bool FULL, bool MULTI>
 __device__ __forceinline__ void encode_tile(const EncodeArgs& a, const TileRef& t, uint32_t tile_id,
                                             unsigned char* stage, int lane)
 {
@@ -50,26 +53,58 @@ __device__ __forceinline__ void encode_tile(const EncodeArgs& a, const TileRef& 
     for (int r = 0; r < ROWS; ++r)
         raw[r] = load_row<DT, FULL>(tile, (uint32_t)(r * kWave + lane) * kLaneElems, t.len);
 
-    float step;
-    if (FUSED) {
-        // the bucket is this tile: kappa = max|g| in registers (Sec. 3.1 eq. (2))
-        typename T::maxacc m = T::max_init();
+    // 1/step per row (alpha/step for a nested worker that shrinks), wave-uniform
+    float inv_row[ROWS];
+    if (FUSED && MULTI) {
+        // max-norm of every row, then of aligned groups of 2 and 4 rows: a bucket is
+        // 1, 2 or 4 rows (Sec. 3.1 eq. (2) per bucket)
+        float k1[ROWS], k2[ROWS], k4[ROWS];
 #pragma unroll
-        for (int r = 0; r < ROWS; ++r) m = T::max_update(m, raw[r]);
-        step = step_from_kappa(wave_max(T::max_final(m)), a.qp.levels);
-        if (lane == 0) a.steps[t.bucket] = step;
-    } else if (a.preset_step > 0.0f) {
-        step = a.preset_step;
-        if (tile_id == 0 && lane == 0) a.steps[0] = step;
+        for (int r = 0; r < ROWS; ++r)
+            k1[r] = wave_max(T::max_final(T::max_update(T::max_init(), raw[r])));
+#pragma unroll
+        for (int r = 0; r < ROWS; ++r) k2[r] = __builtin_fmaxf(k1[r], k1[r ^ 1]);
+#pragma unroll
+        for (int r = 0; r < ROWS; ++r) k4[r] = __builtin_fmaxf(k2[r], k2[(r ^ 2) % ROWS]);
+        const uint32_t rl = a.rows_log2, group_mask = (1u << rl) - 1u;
+#pragma unroll
+        for (int r = 0; r < ROWS; ++r) {
+            if (((uint32_t)r & group_mask) == 0u) {   // first row of a bucket
+                const float kappa = rl == 0u ? k1[r] : rl == 1u ? k2[r] : k4[r];
+                const float step = step_from_kappa(kappa, a.qp.levels);
+                const uint32_t bucket = t.bucket * ((uint32_t)ROWS >> rl) + ((uint32_t)r >> rl);
+                if (lane == 0 && bucket < a.num_buckets) a.steps[bucket] = step;
+                inv_row[r] = __uint_as_float(
+                    __builtin_amdgcn_readfirstlane(__float_as_uint(a.qp.alpha * inv_step(step))));
+            } else {
+                inv_row[r] = inv_row[r > 0 ? r - 1 : 0];
+            }
+        }
     } else {
-        step = a.steps[t.bucket];
+        float step;
+        if (FUSED) {
+            // the bucket is this tile: kappa = max|g| in registers (Sec. 3.1 eq. (2))
+            typename T::maxacc m = T::max_init();
+#pragma unroll
+            for (int r = 0; r < ROWS; ++r) m = T::max_update(m, raw[r]);
+            step = step_from_kappa(wave_max(T::max_final(m)), a.qp.levels);
+            if (lane == 0) a.steps[t.bucket] = step;
+        } else if (a.preset_step > 0.0f) {
+            step = a.preset_step;
+            if (tile_id == 0 && lane == 0) a.steps[0] = step;
+        } else {
+            step = a.steps[t.bucket];
+        }
+        const float inv_all = a.qp.alpha * inv_step(step);   // alpha = 1 unless a nested worker shrinks
+#pragma unroll
+        for (int r = 0; r < ROWS; ++r) inv_row[r] = inv_all;
     }
-    const float inv = a.qp.alpha * inv_step(step);   // alpha = 1 unless a nested worker shrinks
     const uint64_t block0 = (a.index0 + t.start) >> 3;
 
 #pragma unroll
     for (int r = 0; r < ROWS; ++r) {
         const uint32_t o = (uint32_t)(r * kWave + lane) * kLaneElems;
+        const float inv = inv_row[r];
         float v[8];
         dither8(a.ds, block0 + (o >> 3), v);
         uint32_t quad[2];
@@ -133,7 +168,7 @@ __device__ __forceinline__ void encode_tile(const EncodeArgs& a, const TileRef& 
 #define NDQ_ENC_WAVES_BF16 8
 #endif
 template <int DT> struct EncWaves { static constexpr int W = DT == 1 ? NDQ_ENC_WAVES_BF16 : 4; };
-template <int DT, int MODE, bool FUSED>
+template <int DT, int MODE, bool FUSED, bool MULTI>
 __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(EncWaves<DT>::W)))
 void encode_kernel(EncodeArgs a)
 {
@@ -146,8 +181,8 @@ void encode_kernel(EncodeArgs a)
     const uint32_t tile_id = blockIdx.x * kWavesPerBlock + wave;
     const TileRef t = locate_tile(a.tl, tile_id, TILE);
     const uint32_t bits = a.qp.bits;
-    if (t.len == TILE) encode_tile<DT, MODE, FUSED, true>(a, t, tile_id, stage, lane);
-    else if (t.len != 0) encode_tile<DT, MODE, FUSED, false>(a, t, tile_id, stage, lane);
+    if (t.len == TILE) encode_tile<DT, MODE, FUSED, true, MULTI>(a, t, tile_id, stage, lane);
+    else if (t.len != 0) encode_tile<DT, MODE, FUSED, false, MULTI>(a, t, tile_id, stage, lane);
     __syncthreads();
     if (t.len != 0) {
         const uint64_t byte0 = (t.start >> 3) * bits;                 // tile start is a multiple of 64
@@ -277,11 +312,12 @@ static int run_absmax(const void* g, const Tiling& tl, uint64_t K, float* kappa,
 }
 
 template <int DT, int MODE>
-static int run_encode(const EncodeArgs& a, bool fused, hipStream_t s)
+static int run_encode(const EncodeArgs& a, bool fused, bool multi, hipStream_t s)
 {
     const dim3 grid(blocks_for(a.tl.total_tiles)), block(kBlock);
-    if (fused) hipLaunchKernelGGL((encode_kernel<DT, MODE, true>), grid, block, 0, s, a);
-    else hipLaunchKernelGGL((encode_kernel<DT, MODE, false>), grid, block, 0, s, a);
+    if (multi) hipLaunchKernelGGL((encode_kernel<DT, MODE, true, true>), grid, block, 0, s, a);
+    else if (fused) hipLaunchKernelGGL((encode_kernel<DT, MODE, true, false>), grid, block, 0, s, a);
+    else hipLaunchKernelGGL((encode_kernel<DT, MODE, false, false>), grid, block, 0, s, a);
     return launched();
 }
 
@@ -302,8 +338,15 @@ static int encode_common(const void* g, ndq_dtype dt, size_t n, float delta, uin
     if (bucket % 64u != 0u || (d->offset & 7u) != 0u) return NDQ_EALIGN;
 
     const uint32_t tile = dt == NDQ_F32 ? EncTile<0>::N : EncTile<1>::N;
-    rc = make_tiling(n, bucket, tile, &a.tl);
+    // buckets of 1, 2 or 4 whole rows (2, 4 or 8 to a tile) share tiles: the tiling is
+    // that of tile-sized buckets and the kernel finds a max-norm per group of rows
+    constexpr uint32_t row = kWave * kLaneElems;
+    const bool multi = bucket != 0u && bucket < tile && tile % bucket == 0u && bucket % row == 0u &&
+                       bucket / row <= 4u && (bucket / row & (bucket / row - 1u)) == 0u;
+    rc = make_tiling(n, multi ? tile : bucket, tile, &a.tl);
     if (rc != NDQ_OK) return rc;
+    a.rows_log2 = multi ? (bucket / row == 1u ? 0u : bucket / row == 2u ? 1u : 2u) : 0u;
+    a.num_buckets = (uint32_t)((n + (bucket ? bucket : n) - 1) / (bucket ? bucket : n));
     a.g = g;
     a.codes = (unsigned char*)codes_out;
     a.steps = steps_out;
@@ -313,7 +356,7 @@ static int encode_common(const void* g, ndq_dtype dt, size_t n, float delta, uin
     a.preset_step = (bucket == 0u && delta > 0.0f) ? delta : 0.0f;
     hipStream_t s = (hipStream_t)stream;
 
-    const bool fused = bucket != 0u && bucket <= tile;
+    const bool fused = bucket != 0u && bucket <= tile;   // (multi implies fused)
     if (!fused && a.preset_step == 0.0f) {
         // two passes: max-norm per bucket, then steps, then the encoder reads them
         const uint64_t K = bucket ? (n + bucket - 1) / bucket : 1;
@@ -332,17 +375,17 @@ static int encode_common(const void* g, ndq_dtype dt, size_t n, float delta, uin
                              : (!is_pow2(M) ? kNestedAnyM
                                             : (a.preset_step > 0.0f ? kNestedPow2 : kNestedPow2Bounded));
     if (dt == NDQ_F32) {
-        if (mode == kDqNarrow) return run_encode<0, kDqNarrow>(a, fused, s);
-        if (mode == kDq) return run_encode<0, kDq>(a, fused, s);
-        if (mode == kNestedPow2) return run_encode<0, kNestedPow2>(a, fused, s);
-        if (mode == kNestedPow2Bounded) return run_encode<0, kNestedPow2Bounded>(a, fused, s);
-        return run_encode<0, kNestedAnyM>(a, fused, s);
+        if (mode == kDqNarrow) return run_encode<0, kDqNarrow>(a, fused, multi, s);
+        if (mode == kDq) return run_encode<0, kDq>(a, fused, multi, s);
+        if (mode == kNestedPow2) return run_encode<0, kNestedPow2>(a, fused, multi, s);
+        if (mode == kNestedPow2Bounded) return run_encode<0, kNestedPow2Bounded>(a, fused, multi, s);
+        return run_encode<0, kNestedAnyM>(a, fused, multi, s);
     }
-    if (mode == kDqNarrow) return run_encode<1, kDqNarrow>(a, fused, s);
-    if (mode == kDq) return run_encode<1, kDq>(a, fused, s);
-    if (mode == kNestedPow2) return run_encode<1, kNestedPow2>(a, fused, s);
-    if (mode == kNestedPow2Bounded) return run_encode<1, kNestedPow2Bounded>(a, fused, s);
-    return run_encode<1, kNestedAnyM>(a, fused, s);
+    if (mode == kDqNarrow) return run_encode<1, kDqNarrow>(a, fused, multi, s);
+    if (mode == kDq) return run_encode<1, kDq>(a, fused, multi, s);
+    if (mode == kNestedPow2) return run_encode<1, kNestedPow2>(a, fused, multi, s);
+    if (mode == kNestedPow2Bounded) return run_encode<1, kNestedPow2Bounded>(a, fused, multi, s);
+    return run_encode<1, kNestedAnyM>(a, fused, multi, s);
 }
 
 }  // namespace ndq

@@ -64,7 +64,7 @@ SIZES = [1, 3, 63, 64, 65, 255, 2047, 2048, 2049, 4096 + 7, 3 * 4096, 5 * 2048 +
 @pytest.mark.parametrize("levels,bucket,preset", [
     (3, 0, False), (3, 0, True), (2, 64, False), (4, 4096, False), (5, 128, False),
     (8, 2048, False), (16, 2048, False), (16, 2112, False), (33, 8192, False), (100, 0, False),
-    (256, 1024, False), (255, 12288, False)])
+    (256, 1024, False), (255, 12288, False), (4, 512, False), (3, 1024, False)])
 def test_dq_encode_decode_matches_oracle(dtype, levels, bucket, preset):
     for n in SIZES:
         g = _make(n, dtype, seed=n + levels)
@@ -584,9 +584,12 @@ def test_decode_chain_matches_oracle_loop(dtype):
         ((("dq", 8), ("nested", 3), ("dq", 5), ("nested", 7), ("nested", 256), ("dq", 256)),
          8, 2112, 1.0, False),
         ((("dq", 3),), 3, 0, 1.0, False),
+        # buckets of one row of a tile (each row has its own step), and smaller ones
+        ((("dq", 4), ("nested", 2), ("nested", 4), ("dq", 9)), 4, 512, 0.25, False),
+        ((("dq", 16), ("nested", 4)), 16, 256, 1.0, False),
     ]
     for plan, fine, bucket, scale, shared in plans:
-        for n in (1, 255, 1024, 1025, 4096 * 3 + 77, 70001):
+        for n in (1, 255, 1024, 1025, 1536, 4096 * 3 + 77, 70001):
             _chain_case(plan, fine, bucket, n, dtype, seed=n, out_scale=scale, shared_step=shared)
 
 
