@@ -29,29 +29,53 @@ struct EncodeArgs {
     float preset_step;     // > 0: bucket == 0 with a caller-set step
     uint32_t rows_log2;    // MULTI: a bucket is 2^rows_log2 rows of a tile
     uint32_t num_buckets;  // MULTI: buckets in the call (steps to write)
+    uint32_t waves_log2;   // FUSED, not MULTI: a bucket is 2^waves_log2 tiles of one workgroup
 };
 
 template <int DT> struct EncRows { static constexpr int R = kEncLoads / Elem<DT>::V; };
 template <int DT> struct EncTile { static constexpr uint32_t N = kWave * kLaneElems * EncRows<DT>::R; };
 
-// One wave encodes one tile: loads it (all 16-byte loads issued back to back),
-// finds the step, quantizes, and leaves the packed codes in `stage` in stream
-// order.  A lane owns 8 consecutive elements per row: one Philox block, and
-// 8 codes = `bits` whole bytes of the stream.  FULL: every element of the tile
-// is valid -- no guards anywhere.  MULTI (with FUSED): the bucket is a whole
-// number of rows and several buckets share the tile, each with its own step.
+// A tile in registers: a lane owns 8 consecutive elements per row (one Philox
+// block, and 8 codes = `bits` whole bytes of the stream).
+template <int DT> struct TileRegs { typename Elem<DT>::Row row[EncRows<DT>::R]; };
+
+// Issues all 16-byte loads of a tile back to back.  FULL: every element of the
+// tile is valid, no guards; otherwise elements past the end read as zero.
+template <int DT, bool FULL>
+__device__ __forceinline__ void load_tile(const EncodeArgs& a, const TileRef& t, int lane, TileRegs<DT>& regs)
+{
+    using T = Elem<DT>;
+    const typename T::scalar* tile = (const typename T::scalar*)a.g + t.start;
+#pragma unroll
+    for (int r = 0; r < EncRows<DT>::R; ++r)
+        regs.row[r] = load_row<DT, FULL>(tile, (uint32_t)(r * kWave + lane) * kLaneElems, t.len);
+}
+
+// max |g| over the tile a wave holds (Sec. 3.1 eq. (2)), the same in every lane
+template <int DT>
+__device__ __forceinline__ float tile_max(const TileRegs<DT>& regs)
+{
+    using T = Elem<DT>;
+    typename T::maxacc m = T::max_init();
+#pragma unroll
+    for (int r = 0; r < EncRows<DT>::R; ++r) m = T::max_update(m, regs.row[r]);
+    return wave_max(T::max_final(m));
+}
+
+// One wave encodes the tile it holds: finds the step, quantizes, and leaves the
+// packed codes in `stage` in stream order.  FULL: no guards anywhere.  FUSED: the
+// step comes from `kappa`, the max-norm of the tile's bucket, found in registers.
+// MULTI (with FUSED): the bucket is a whole number of rows and several buckets
+// share the tile, each with its own step.
 template <int DT, int MODE, bool FUSED, bool FULL, bool MULTI>
 __device__ __forceinline__ void encode_tile(const EncodeArgs& a, const TileRef& t, uint32_t tile_id,
+                                            const TileRegs<DT>& regs, float kappa, bool writes_step,
                                             unsigned char* stage, int lane)
 {
     using T = Elem<DT>;
     constexpr int ROWS = EncRows<DT>::R;
     const uint32_t bits = a.qp.bits;
-    const typename T::scalar* tile = (const typename T::scalar*)a.g + t.start;
-    typename T::Row raw[ROWS];
-#pragma unroll
-    for (int r = 0; r < ROWS; ++r)
-        raw[r] = load_row<DT, FULL>(tile, (uint32_t)(r * kWave + lane) * kLaneElems, t.len);
+    const typename T::Row (&raw)[ROWS] = regs.row;
 
     // 1/step per row (alpha/step for a nested worker that shrinks), wave-uniform
     float inv_row[ROWS];
@@ -70,8 +94,8 @@ __device__ __forceinline__ void encode_tile(const EncodeArgs& a, const TileRef& 
 #pragma unroll
         for (int r = 0; r < ROWS; ++r) {
             if (((uint32_t)r & group_mask) == 0u) {   // first row of a bucket
-                const float kappa = rl == 0u ? k1[r] : rl == 1u ? k2[r] : k4[r];
-                const float step = step_from_kappa(kappa, a.qp.levels);
+                const float kappa_r = rl == 0u ? k1[r] : rl == 1u ? k2[r] : k4[r];
+                const float step = step_from_kappa(kappa_r, a.qp.levels);
                 const uint32_t bucket = t.bucket * ((uint32_t)ROWS >> rl) + ((uint32_t)r >> rl);
                 if (lane == 0 && bucket < a.num_buckets) a.steps[bucket] = step;
                 inv_row[r] = __uint_as_float(
@@ -83,12 +107,8 @@ __device__ __forceinline__ void encode_tile(const EncodeArgs& a, const TileRef& 
     } else {
         float step;
         if (FUSED) {
-            // the bucket is this tile: kappa = max|g| in registers (Sec. 3.1 eq. (2))
-            typename T::maxacc m = T::max_init();
-#pragma unroll
-            for (int r = 0; r < ROWS; ++r) m = T::max_update(m, raw[r]);
-            step = step_from_kappa(wave_max(T::max_final(m)), a.qp.levels);
-            if (lane == 0) a.steps[t.bucket] = step;
+            step = step_from_kappa(kappa, a.qp.levels);
+            if (lane == 0 && writes_step) a.steps[t.bucket] = step;
         } else if (a.preset_step > 0.0f) {
             step = a.preset_step;
             if (tile_id == 0 && lane == 0) a.steps[0] = step;
@@ -157,9 +177,6 @@ __device__ __forceinline__ void encode_tile(const EncodeArgs& a, const TileRef& 
     if (lane == 0) *(uint64_t*)(stage + (size_t)EncTile<DT>::N / 8 * bits) = 0;  // pad unit
 }
 
-// FUSED: the bucket fits one tile; its max-norm is reduced in registers and
-// the step is written.  Otherwise the step is the preset one or read from
-// `steps` (filled by absmax_kernel + steps_from_kappa_kernel).
 // Occupancy target.  The bfloat16 encoder is bound by instruction issue with a
 // burst of loads at the start of every tile; eight waves per SIMD (64 registers)
 // hide that burst better than four (+8 % measured).  The binary32 encoder moves
@@ -168,7 +185,11 @@ __device__ __forceinline__ void encode_tile(const EncodeArgs& a, const TileRef& 
 #define NDQ_ENC_WAVES_BF16 8
 #endif
 template <int DT> struct EncWaves { static constexpr int W = DT == 1 ? NDQ_ENC_WAVES_BF16 : 4; };
-template <int DT, int MODE, bool FUSED, bool MULTI>
+// FUSED: the bucket fits one tile.  MULTI: several buckets to a tile.  BLOCK: the
+// bucket is 2 or 4 tiles, all held by the waves of one workgroup.  In all three
+// the max-norm is found in registers and the step written; otherwise the step is
+// the preset one or read from `steps` (absmax + steps_from_kappa kernels).
+template <int DT, int MODE, bool FUSED, bool MULTI, bool BLOCK>
 __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(EncWaves<DT>::W)))
 void encode_kernel(EncodeArgs a)
 {
@@ -181,8 +202,38 @@ void encode_kernel(EncodeArgs a)
     const uint32_t tile_id = blockIdx.x * kWavesPerBlock + wave;
     const TileRef t = locate_tile(a.tl, tile_id, TILE);
     const uint32_t bits = a.qp.bits;
-    if (t.len == TILE) encode_tile<DT, MODE, FUSED, true, MULTI>(a, t, tile_id, stage, lane);
-    else if (t.len != 0) encode_tile<DT, MODE, FUSED, false, MULTI>(a, t, tile_id, stage, lane);
+    if (BLOCK) {
+        // A bucket of 2 or 4 tiles lies inside one workgroup (tile ids are consecutive
+        // and buckets start at multiples of their length): the waves exchange their
+        // tile maxima through LDS.  Every wave of the workgroup reaches the barrier,
+        // also one whose tile is empty.
+        __shared__ float part[kWavesPerBlock];
+        TileRegs<DT> regs;
+        if (t.len == TILE) load_tile<DT, true>(a, t, lane, regs);
+        else if (t.len != 0) load_tile<DT, false>(a, t, lane, regs);
+        float kappa = 0.0f;
+        if (t.len != 0) kappa = tile_max<DT>(regs);
+        if (lane == 0) part[wave] = kappa;
+        __syncthreads();
+        const uint32_t group = 1u << a.waves_log2, first = (uint32_t)wave & ~(group - 1u);
+        kappa = part[first];
+        for (uint32_t w = 1; w < group; ++w) kappa = __builtin_fmaxf(kappa, part[first + w]);
+        const bool writes_step = (uint32_t)wave == first;
+        if (t.len == TILE)
+            encode_tile<DT, MODE, true, true, false>(a, t, tile_id, regs, kappa, writes_step, stage, lane);
+        else if (t.len != 0)
+            encode_tile<DT, MODE, true, false, false>(a, t, tile_id, regs, kappa, writes_step, stage, lane);
+    } else if (t.len == TILE) {
+        TileRegs<DT> regs;
+        load_tile<DT, true>(a, t, lane, regs);
+        const float kappa = (FUSED && !MULTI) ? tile_max<DT>(regs) : 0.0f;
+        encode_tile<DT, MODE, FUSED, true, MULTI>(a, t, tile_id, regs, kappa, true, stage, lane);
+    } else if (t.len != 0) {
+        TileRegs<DT> regs;
+        load_tile<DT, false>(a, t, lane, regs);
+        const float kappa = (FUSED && !MULTI) ? tile_max<DT>(regs) : 0.0f;
+        encode_tile<DT, MODE, FUSED, false, MULTI>(a, t, tile_id, regs, kappa, true, stage, lane);
+    }
     __syncthreads();
     if (t.len != 0) {
         const uint64_t byte0 = (t.start >> 3) * bits;                 // tile start is a multiple of 64
@@ -315,9 +366,10 @@ template <int DT, int MODE>
 static int run_encode(const EncodeArgs& a, bool fused, bool multi, hipStream_t s)
 {
     const dim3 grid(blocks_for(a.tl.total_tiles)), block(kBlock);
-    if (multi) hipLaunchKernelGGL((encode_kernel<DT, MODE, true, true>), grid, block, 0, s, a);
-    else if (fused) hipLaunchKernelGGL((encode_kernel<DT, MODE, true, false>), grid, block, 0, s, a);
-    else hipLaunchKernelGGL((encode_kernel<DT, MODE, false, false>), grid, block, 0, s, a);
+    if (a.waves_log2 != 0u) hipLaunchKernelGGL((encode_kernel<DT, MODE, true, false, true>), grid, block, 0, s, a);
+    else if (multi) hipLaunchKernelGGL((encode_kernel<DT, MODE, true, true, false>), grid, block, 0, s, a);
+    else if (fused) hipLaunchKernelGGL((encode_kernel<DT, MODE, true, false, false>), grid, block, 0, s, a);
+    else hipLaunchKernelGGL((encode_kernel<DT, MODE, false, false, false>), grid, block, 0, s, a);
     return launched();
 }
 
@@ -346,6 +398,9 @@ static int encode_common(const void* g, ndq_dtype dt, size_t n, float delta, uin
     rc = make_tiling(n, multi ? tile : bucket, tile, &a.tl);
     if (rc != NDQ_OK) return rc;
     a.rows_log2 = multi ? (bucket / row == 1u ? 0u : bucket / row == 2u ? 1u : 2u) : 0u;
+    // buckets of 2 or 4 tiles: the waves of one workgroup hold the whole bucket
+    const bool block_fused = kWavesPerBlock == 4 && (bucket == 2u * tile || bucket == 4u * tile);
+    a.waves_log2 = block_fused ? (bucket == 2u * tile ? 1u : 2u) : 0u;
     a.num_buckets = (uint32_t)((n + (bucket ? bucket : n) - 1) / (bucket ? bucket : n));
     a.g = g;
     a.codes = (unsigned char*)codes_out;
@@ -356,7 +411,7 @@ static int encode_common(const void* g, ndq_dtype dt, size_t n, float delta, uin
     a.preset_step = (bucket == 0u && delta > 0.0f) ? delta : 0.0f;
     hipStream_t s = (hipStream_t)stream;
 
-    const bool fused = bucket != 0u && bucket <= tile;   // (multi implies fused)
+    const bool fused = (bucket != 0u && bucket <= tile) || block_fused;   // (multi implies fused)
     if (!fused && a.preset_step == 0.0f) {
         // two passes: max-norm per bucket, then steps, then the encoder reads them
         const uint64_t K = bucket ? (n + bucket - 1) / bucket : 1;

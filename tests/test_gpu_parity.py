@@ -64,7 +64,8 @@ SIZES = [1, 3, 63, 64, 65, 255, 2047, 2048, 2049, 4096 + 7, 3 * 4096, 5 * 2048 +
 @pytest.mark.parametrize("levels,bucket,preset", [
     (3, 0, False), (3, 0, True), (2, 64, False), (4, 4096, False), (5, 128, False),
     (8, 2048, False), (16, 2048, False), (16, 2112, False), (33, 8192, False), (100, 0, False),
-    (256, 1024, False), (255, 12288, False), (4, 512, False), (3, 1024, False)])
+    (256, 1024, False), (255, 12288, False), (4, 512, False), (3, 1024, False), (4, 16384, False),
+    (5, 4096, False)])
 def test_dq_encode_decode_matches_oracle(dtype, levels, bucket, preset):
     for n in SIZES:
         g = _make(n, dtype, seed=n + levels)
@@ -241,7 +242,7 @@ def test_argument_errors_are_reported_not_launched():
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("M,levels,bucket", [
     (2, 4, 4096), (4, 16, 0), (4, 8, 2048), (3, 7, 0), (8, 64, 512), (5, 16, 2112), (16, 256, 0),
-    (256, 256, 64), (7, 9, 8192)])
+    (256, 256, 64), (7, 9, 8192), (2, 4, 16384), (4, 16, 1024)])
 def test_nested_encode_decode_matches_oracle(dtype, M, levels, bucket):
     for n in SIZES:
         g = _make(n, dtype, seed=n + M, heavy=(dtype == "bf16"))
