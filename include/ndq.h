@@ -105,6 +105,10 @@ int ndq_absmax(const void* g, ndq_dtype dt, size_t n, uint32_t bucket, float* ka
  *   bucket == 0, delta <= 0: one step 2 max|g| / (levels-1) for the whole vector
  *   bucket  > 0            : one step per bucket from the bucket's own max-norm
  * codes_out: ndq_packed_bytes(n, ndq_code_bits(levels)) bytes, fully written.
+ * (Every bucket size gives the same bytes; speed differs.  One pass over g:
+ * buckets of 512, 1024, 2048, 4096 or 8192 elements (bfloat16: also 16384), and
+ * a preset step.  Other sizes, and bucket == 0 without a preset step, read g
+ * twice.)
  * steps_out: ndq_num_buckets(n, bucket) floats -- the transmitted scale factors
  * (Delta_b = 2 kappa_b/(L-1) travels in place of kappa_b: the same 32 bits). */
 int ndq_dq_encode(const void* g, ndq_dtype dt, size_t n, float delta, uint32_t levels,
