@@ -30,6 +30,33 @@ template <int MODE, int ACC> struct DecRows {
 
 enum Acc { kStore = 0, kAccumulate = 1, kAccumulateInPlace = 2 };  // in place: out == side
 
+// Four elements of a row: res = decoded value (stored, or added to ps / ys).
+// Returns whether a fast quotient was too close to a rounding tie (see Div).
+template <int MODE, int ACC, int DIV>
+__device__ __forceinline__ bool decode_row(const DecodeArgs& a, uint32_t packed, uint32_t bits,
+                                           const float (&ys)[4], const float (&ps)[4], const float (&v)[4],
+                                           float step, float inv, float (&res)[4])
+{
+    bool near_tie = false;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const uint32_t c = __builtin_amdgcn_ubfe(packed, k * bits, bits);   // bit-field extract
+        float q, yk = 0.0f;
+        if (MODE == kDq || MODE == kDqHalf) {
+            q = (float)((int32_t)c + a.qp.q_min);
+        } else {
+            yk = ys[k] * a.side_scale;
+            q = coset_index_f<MODE, DIV>((float)c, yk, inv, v[k], a.qp, near_tie);
+        }
+        const float val = (MODE == kDqHalf) ? step * q
+                                            : shrink<MODE>(index_value(q, step, v[k]), yk, a.qp);
+        if (ACC == kStore) res[k] = val;
+        else if (ACC == kAccumulate) res[k] = ps[k] + val;
+        else res[k] = ys[k] + val;
+    }
+    return near_tie;
+}
+
 // One wave decodes one tile.  FULL: every element valid, no guards.  STRADDLE:
 // the code width does not divide 8, so four codes may cross a 32-bit word.
 template <int MODE, int ACC, bool FULL, bool STRADDLE>
@@ -92,22 +119,10 @@ __device__ __forceinline__ void decode_tile(const DecodeArgs& a, const TileRef& 
         const float ys[4] = {y[r].x, y[r].y, y[r].z, y[r].w};
         const float ps[4] = {prev[r].x, prev[r].y, prev[r].z, prev[r].w};
         float res[4];
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const uint32_t c = __builtin_amdgcn_ubfe(packed[r], k * bits, bits);   // bit-field extract
-            float q, yk = 0.0f;
-            if (MODE == kDq || MODE == kDqHalf) {
-                q = (float)((int32_t)c + a.qp.q_min);
-            } else {
-                yk = ys[k] * a.side_scale;
-                q = coset_index_f<MODE>((float)c, yk, inv, v[k], a.qp);
-            }
-            const float val = (MODE == kDqHalf) ? step * q
-                                                : shrink<MODE>(index_value(q, step, v[k]), yk, a.qp);
-            if (ACC == kStore) res[k] = val;
-            else if (ACC == kAccumulate) res[k] = ps[k] + val;
-            else res[k] = ys[k] + val;
-        }
+        const bool near_tie = decode_row<MODE, ACC, kDivFast>(a, packed[r], bits, ys, ps, v, step, inv, res);
+        // wave-uniform and rare (M not a power of two only): redo the row with the division
+        if (MODE == kNestedAnyM && __builtin_amdgcn_ballot_w64(near_tie) != 0)
+            decode_row<MODE, ACC, kDivExact>(a, packed[r], bits, ys, ps, v, step, inv, res);
         if (FULL || o + 4 <= t.len) {
             store_streaming(out + o, res[0], res[1], res[2], res[3]);
         } else {
@@ -227,6 +242,30 @@ __device__ __forceinline__ void chain_fetch(const ChainArgs& a, const ChainWorke
     }
 }
 
+// One row of eight elements of one worker: next = S + (this worker's decoded
+// values), the side information being S scaled.  Returns whether any element's
+// fast quotient was too close to a rounding tie to be trusted (see Div).
+template <int MODE, bool FIRST, int DIV>
+__device__ __forceinline__ bool chain_row(const ChainWorker& cw, const Quant& qp, const float (&c_f)[8],
+                                          const float (&v)[8], float step, float inv,
+                                          const float (&S)[8], float (&next)[8])
+{
+    bool near_tie = false;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        float q, yk = 0.0f;
+        if (MODE == kDq) {
+            q = c_f[k];
+        } else {
+            yk = S[k] * cw.side_scale;
+            q = coset_index_f<MODE, DIV>(c_f[k], yk, inv, v[k], qp, near_tie);
+        }
+        const float val = shrink<MODE>(index_value(q, step, v[k]), yk, qp);
+        next[k] = FIRST ? val : S[k] + val;
+    }
+    return near_tie;
+}
+
 // Folds one worker into the running sum S of a tile.  WIDTH: 1, 2, 4 = that many
 // code bits, fetched by chain_fetch's aligned path (full tiles only); -1 = any
 // width up to kFieldAsFloatMaxBits; 0 = any width.  All but 0 turn the codes into
@@ -265,25 +304,43 @@ __device__ __forceinline__ void chain_fold(const ChainWorker& cw, const ChainFet
         }
         float v[8];
         dither8(cw.ds, block0 + (o >> 3), v);
+        if (MODE == kNestedAnyM) {
+            // the eight residues as floats, a fast pass, and -- wave-uniform and rare -- the
+            // row again with the true division where a quotient sat too close to a tie
+            float c_f[8];
 #pragma unroll
-        for (int k = 0; k < 8; ++k) {
-            // the code as a float: plus q_min for DQSG, as it is for a nested worker
-            float c_f;
-            if (WIDTH != 0) {
-                c_f = NF == 8 ? field.get(half[0], k) : field.get(half[k >> 2], k & 3);
-            } else {
-                const uint32_t c = __builtin_amdgcn_ubfe(half[k >> 2], (k & 3) * bits, bits);
-                c_f = MODE == kDq ? (float)((int32_t)c + qp.q_min) : (float)c;
+            for (int k = 0; k < 8; ++k) {
+                if (WIDTH != 0) c_f[k] = NF == 8 ? field.get(half[0], k) : field.get(half[k >> 2], k & 3);
+                else c_f[k] = (float)__builtin_amdgcn_ubfe(half[k >> 2], (k & 3) * bits, bits);
             }
-            float q, yk = 0.0f;
-            if (MODE == kDq) {
-                q = c_f;
-            } else {
-                yk = S[r][k] * cw.side_scale;
-                q = coset_index_f<MODE>(c_f, yk, inv, v[k], qp);
+            float next[8];
+            const bool near_tie = chain_row<MODE, FIRST, kDivFast>(cw, qp, c_f, v, step, inv, S[r], next);
+            if (__builtin_amdgcn_ballot_w64(near_tie) != 0)
+                chain_row<MODE, FIRST, kDivExact>(cw, qp, c_f, v, step, inv, S[r], next);
+#pragma unroll
+            for (int k = 0; k < 8; ++k) S[r][k] = next[k];
+        } else {
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                // the code as a float: plus q_min for DQSG, as it is for a nested worker
+                float c_f;
+                if (WIDTH != 0) {
+                    c_f = NF == 8 ? field.get(half[0], k) : field.get(half[k >> 2], k & 3);
+                } else {
+                    const uint32_t c = __builtin_amdgcn_ubfe(half[k >> 2], (k & 3) * bits, bits);
+                    c_f = MODE == kDq ? (float)((int32_t)c + qp.q_min) : (float)c;
+                }
+                float q, yk = 0.0f;
+                bool unused = false;
+                if (MODE == kDq) {
+                    q = c_f;
+                } else {
+                    yk = S[r][k] * cw.side_scale;
+                    q = coset_index_f<MODE, kDivExact>(c_f, yk, inv, v[k], qp, unused);
+                }
+                const float val = shrink<MODE>(index_value(q, step, v[k]), yk, qp);
+                S[r][k] = FIRST ? val : S[r][k] + val;
             }
-            const float val = shrink<MODE>(index_value(q, step, v[k]), yk, qp);
-            S[r][k] = FIRST ? val : S[r][k] + val;
         }
     }
 }
@@ -301,7 +358,7 @@ __device__ __forceinline__ void chain_fold_width(const ChainWorker& cw, const Ch
     else chain_fold<MODE, 0, FIRST, ROWB>(cw, f, block0, lane, S);
 }
 
-template <bool FULL, bool ROWB>
+template <bool FULL, bool ROWB, bool ANYM>
 __device__ __forceinline__ void chain_tile(const ChainArgs& a, const TileRef& t, int lane)
 {
     float S[kChainRows][8];
@@ -329,7 +386,7 @@ __device__ __forceinline__ void chain_tile(const ChainArgs& a, const TileRef& t,
             chain_fold_width<kNestedPow2, FULL, false, ROWB>(cw, cur, block0, lane, S);
         } else if (cw.mode == kNestedPow2Shrink) {
             chain_fold_width<kNestedPow2Shrink, FULL, false, ROWB>(cw, cur, block0, lane, S);
-        } else {
+        } else if (ANYM) {
             chain_fold_width<kNestedAnyM, FULL, false, ROWB>(cw, cur, block0, lane, S);
         }
         cur = nxt;
@@ -356,16 +413,20 @@ __device__ __forceinline__ void chain_tile(const ChainArgs& a, const TileRef& t,
 #ifndef NDQ_CHAIN_WAVES_PER_EU
 #define NDQ_CHAIN_WAVES_PER_EU 6
 #endif
-template <bool ROWB>
-__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(NDQ_CHAIN_WAVES_PER_EU)))
+// ANYM: some worker's nesting ratio is not a power of two.  Those workers take
+// the two-pass rows of chain_fold, which need more registers: that instantiation
+// runs four waves per SIMD, and the common one does not carry their code at all.
+template <bool ROWB, bool ANYM>
+__global__ __launch_bounds__(kBlock)
+__attribute__((amdgpu_waves_per_eu(ANYM ? 4 : NDQ_CHAIN_WAVES_PER_EU)))
 void chain_kernel(ChainArgs a)
 {
     const int lane = threadIdx.x & (kWave - 1);
     const uint32_t tile_id =
         blockIdx.x * kWavesPerBlock + __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     const TileRef t = locate_tile(a.tl, tile_id, kChainTile);
-    if (t.len == kChainTile) chain_tile<true, ROWB>(a, t, lane);
-    else if (t.len != 0) chain_tile<false, ROWB>(a, t, lane);
+    if (t.len == kChainTile) chain_tile<true, ROWB, ANYM>(a, t, lane);
+    else if (t.len != 0) chain_tile<false, ROWB, ANYM>(a, t, lane);
 }
 
 // ---------------------------------------------------------------------------
@@ -599,12 +660,14 @@ int ndq_decode_chain(const ndq_worker* workers, uint32_t W, size_t n, uint32_t b
                                  : (wk.alpha == 1.0f ? kNestedPow2 : kNestedPow2Shrink));
             cw.first = (p0 + j) == 0u;
         }
-        if (a.row_buckets)
-            hipLaunchKernelGGL(chain_kernel<true>, dim3(blocks_for(a.tl.total_tiles)), dim3(kBlock), 0,
-                               (hipStream_t)stream, a);
-        else
-            hipLaunchKernelGGL(chain_kernel<false>, dim3(blocks_for(a.tl.total_tiles)), dim3(kBlock), 0,
-                               (hipStream_t)stream, a);
+        bool any_m = false;
+        for (uint32_t j = 0; j < a.W; ++j) any_m = any_m || a.w[j].mode == kNestedAnyM;
+        const dim3 grid(blocks_for(a.tl.total_tiles)), block(kBlock);
+        hipStream_t hs = (hipStream_t)stream;
+        if (a.row_buckets && any_m) hipLaunchKernelGGL((chain_kernel<true, true>), grid, block, 0, hs, a);
+        else if (a.row_buckets) hipLaunchKernelGGL((chain_kernel<true, false>), grid, block, 0, hs, a);
+        else if (any_m) hipLaunchKernelGGL((chain_kernel<false, true>), grid, block, 0, hs, a);
+        else hipLaunchKernelGGL((chain_kernel<false, false>), grid, block, 0, hs, a);
         if (launched() != NDQ_OK) return NDQ_ELAUNCH;
     }
     return NDQ_OK;

@@ -137,16 +137,18 @@ __device__ __forceinline__ float inv_step(float step)
 //   kNestedPow2Bounded : encoder only: M a power of two and the step derived from
 //                   the bucket's own max-norm, so |g/Delta + v| <= 128.1 (see
 //                   nested_low_bits)
+//   kNestedAnyMBounded : encoder only: the same bound, any M up to 64 (see
+//                   nested_residue_f)
 // ---------------------------------------------------------------------------
 enum Mode { kDq = 0, kNestedPow2 = 1, kNestedAnyM = 2, kDqNarrow = 3, kDqHalf = 4, kNestedPow2Shrink = 5,
-            kNestedPow2Bounded = 6 };
+            kNestedPow2Bounded = 6, kNestedAnyMBounded = 7 };
 
 struct Quant {
     float q_min_f, q_max_f;  // DQSG index range as floats
     int32_t q_min;           // -(levels/2)
     uint32_t levels;         // fixes the step: Delta = 2 kappa/(levels-1)
     uint32_t M;              // nesting ratio Delta_2/Delta_1 (nested modes)
-    float M_f, inv_M_f;      // (float)M and, for powers of two, its exact reciprocal
+    float M_f, inv_M_f;      // (float)M and 1/M rounded to binary32 (exact for powers of two)
     uint32_t bits;           // code width
     float pack_bias;         // kDqNarrow: -q_min * sum_k 2^(k*bits), k = 0..3 (codes of <= 6 bits)
     float alpha, beta;       // nested: shrinkage factor and 1 - alpha^2 (kNestedAnyM when alpha < 1)
@@ -188,6 +190,18 @@ __device__ __forceinline__ uint32_t nested_low_bits(float g, float inv, float v)
 {
     const float t = __builtin_fmaf(g, inv, v);
     return __float_as_uint(t + 12582912.0f);
+}
+
+// Fine index of eq. (7) reduced mod M, as a float, for |q| <= 2^8 (a step derived
+// from the data) and any M in [2, 256]: k = floor(q/M) is floor(q * (1/M) + 1/(2M)).
+// The exact value q/M + 1/(2M) is at least 1/(2M) >= 2^-9 away from every
+// integer, the rounded reciprocal and the fma put the computed one within 2^-15
+// of it, so the floor is exact; q - k M is then formed exactly by one fma.
+__device__ __forceinline__ float nested_residue_f(float g, float inv, float v, const Quant& qp)
+{
+    const float q = __builtin_rintf(__builtin_fmaf(g, inv, v));
+    const float k = __builtin_floorf(__builtin_fmaf(q, qp.inv_M_f, 0.5f * qp.inv_M_f));
+    return __builtin_fmaf(-k, qp.M_f, q);
 }
 
 template <int MODE>
@@ -243,14 +257,32 @@ constexpr uint32_t kFieldAsFloatMaxBits = 5;   // four fields of a group stay in
 // Coset decoder of eq. (8), alpha = 1: the integer congruent to m (mod M) nearest
 // to y/Delta + v, returned as a float.  m + M*k is formed by one fma: exact while
 // below 2^24 and otherwise rounded once, exactly like converting the integer.
-template <int MODE>
+// How coset_index_f divides by M.  kDivExact: the correctly rounded quotient, as
+// the decoder is defined.  kDivFast: the product with the rounded reciprocal,
+// which differs from that quotient by less than 2^-22 |quotient| and therefore
+// rounds to the same integer unless it lies that close to a half-integer; the
+// caller is told (`near_tie`) and repeats the few affected rows with kDivExact.
+// For a power of two M the two coincide and near_tie is never set.
+enum Div { kDivExact = 0, kDivFast = 1 };
+
+template <int MODE, int DIV>
 __device__ __forceinline__ float coset_index_f(float m_f, float y, float inv, float v,
-                                               const Quant& qp)
+                                               const Quant& qp, bool& near_tie)
 {
     const float c = __builtin_fmaf(y, inv, v);
     const float diff = c - m_f;
-    float k = (MODE == kNestedPow2 || MODE == kNestedPow2Shrink) ? diff * qp.inv_M_f : diff / qp.M_f;
-    k = __builtin_rintf(k);
+    float k;
+    if (MODE == kNestedPow2 || MODE == kNestedPow2Shrink) {
+        k = __builtin_rintf(diff * qp.inv_M_f);        // exact scaling
+    } else if (DIV == kDivFast) {
+        const float approx = diff * qp.inv_M_f;
+        k = __builtin_rintf(approx);
+        const float off = approx - k;                                  // exact, in [-1/2, 1/2]
+        const float tol = __builtin_fmaf(__builtin_fabsf(approx), 0x1p-21f, 0x1p-21f);
+        near_tie = near_tie || (__builtin_fabsf(off) + tol >= 0.5f);
+    } else {
+        k = __builtin_rintf(diff / qp.M_f);
+    }
     k = __builtin_fminf(__builtin_fmaxf(k, -4194304.0f), 4194304.0f);
     return __builtin_fmaf(k, qp.M_f, m_f);
 }

@@ -141,6 +141,16 @@ __device__ __forceinline__ void encode_tile(const EncodeArgs& a, const TileRef& 
                     acc = __builtin_fmaf(q, __uint_as_float((127u + k * bits) << 23), acc);
                 }
                 chunk = (uint32_t)acc;
+            } else if (MODE == kNestedAnyMBounded) {
+                // residues of <= 6 bits packed like the narrow DQSG codes: exact float fma's
+                float acc = 0.0f;
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    float m = nested_residue_f(T::get(raw[r], 4 * h + k), inv, v[4 * h + k], a.qp);
+                    if (!FULL && o + 4 * h + k >= t.len) m = 0.0f;
+                    acc = __builtin_fmaf(m, __uint_as_float((127u + k * bits) << 23), acc);
+                }
+                chunk = (uint32_t)acc;
             } else if (MODE == kNestedPow2Bounded) {
                 // each code enters at the top of the word and moves down as the next
                 // ones arrive: one funnel shift per code keeps exactly its low `bits` bits
@@ -427,19 +437,22 @@ static int encode_common(const void* g, ndq_dtype dt, size_t n, float delta, uin
 #endif
     // a step derived from the data bounds |g/Delta|; a caller's preset step does not
     const int mode = !nested ? (a.qp.bits <= NDQ_NARROW_MAX_BITS ? kDqNarrow : kDq)
-                             : (!is_pow2(M) ? kNestedAnyM
+                             : (!is_pow2(M) ? ((a.preset_step > 0.0f || a.qp.bits > 6u) ? kNestedAnyM
+                                                                                       : kNestedAnyMBounded)
                                             : (a.preset_step > 0.0f ? kNestedPow2 : kNestedPow2Bounded));
     if (dt == NDQ_F32) {
         if (mode == kDqNarrow) return run_encode<0, kDqNarrow>(a, fused, multi, s);
         if (mode == kDq) return run_encode<0, kDq>(a, fused, multi, s);
         if (mode == kNestedPow2) return run_encode<0, kNestedPow2>(a, fused, multi, s);
         if (mode == kNestedPow2Bounded) return run_encode<0, kNestedPow2Bounded>(a, fused, multi, s);
+        if (mode == kNestedAnyMBounded) return run_encode<0, kNestedAnyMBounded>(a, fused, multi, s);
         return run_encode<0, kNestedAnyM>(a, fused, multi, s);
     }
     if (mode == kDqNarrow) return run_encode<1, kDqNarrow>(a, fused, multi, s);
     if (mode == kDq) return run_encode<1, kDq>(a, fused, multi, s);
     if (mode == kNestedPow2) return run_encode<1, kNestedPow2>(a, fused, multi, s);
     if (mode == kNestedPow2Bounded) return run_encode<1, kNestedPow2Bounded>(a, fused, multi, s);
+    if (mode == kNestedAnyMBounded) return run_encode<1, kNestedAnyMBounded>(a, fused, multi, s);
     return run_encode<1, kNestedAnyM>(a, fused, multi, s);
 }
 

@@ -53,7 +53,7 @@ inline int make_quant(uint32_t levels, uint32_t M, bool nested, float alpha, Qua
     qp->q_max_f = (float)(qp->q_min + (int32_t)levels - 1);
     qp->M = nested ? M : 1u;
     qp->M_f = (float)qp->M;
-    qp->inv_M_f = 1.0f / qp->M_f;   // exact when M is a power of two, unused otherwise
+    qp->inv_M_f = 1.0f / qp->M_f;   // exact when M is a power of two
     qp->bits = code_bits(nested ? M : levels);
     float weights = 0.0f;
     for (uint32_t k = 0; k < 4; ++k) weights += (float)(1u << (k * qp->bits < 31u ? k * qp->bits : 31u));
