@@ -309,6 +309,69 @@ def test_exact_rounding_ties_go_to_the_even_index_on_the_gpu_too(bucket):
                           oracle.dq_decode(c_ref, n, 5, bucket, s_ref, d_o))
 
 
+@pytest.mark.parametrize("M", [3, 5, 6, 7, 12])
+def test_coset_decisions_at_and_next_to_exact_ties_for_any_nesting_ratio(M):
+    """Side information placed midway between two coset points, or a few units in the last
+    place beside it: (y/Delta + v - m)/M is a half-integer or next to one.  The kernels divide
+    by M with a rounded reciprocal and must fall back to the true division there.  For every
+    element the y (within 16 ulps of the tie) is taken at which the reciprocal product and the
+    division round to different integers, where there is one: a kernel without the fallback
+    fails on those."""
+    n, levels, bucket = 3 * 1024 + 512 + 64, 5, 0
+    d_o, d_g = oracle.dither(11, 4, 6), ndq.ndq_dither(11, 4, 6, 0)
+    v = oracle.unit_dithers(d_o, n).astype(F)
+    rng = np.random.default_rng(M)
+    g = (rng.uniform(-1.9, 1.9, n)).astype(F)
+    g[0] = F(2.0)                                                   # max-norm 2, 5 levels: step exactly 1
+    codes_ref, steps_ref = oracle.nested_encode(g, 0.0, levels, M, bucket, d_o)
+    assert steps_ref[0] == F(1.0)
+    m = oracle.unpack(codes_ref, n, oracle.code_bits(M)).astype(F)
+    j = rng.integers(-100, 101, n).astype(np.float64)
+    y = (M * j + M / 2.0 + m.astype(np.float64) - v.astype(np.float64)).astype(F)
+    tie_bits, found = y.view(np.int32).copy(), np.zeros(n, bool)
+    for off in range(-16, 17):
+        cand = (tie_bits + off).view(F)
+        c = (cand.astype(np.float64) + v.astype(np.float64)).astype(F)          # fma(y, 1/Delta = 1, v)
+        diff = (c - m).astype(F)
+        differ = np.rint((diff / F(M)).astype(F)) != np.rint((diff * (F(1.0) / F(M))).astype(F))
+        take = differ & ~found
+        y[take] = cand[take]
+        found |= take
+    if M != 5:      # (the product with the rounded 1/5 happens to agree with the quotient near these ties)
+        assert found.sum() > 100
+    codes, steps = ndq.ndq_nested_encode(_to_dev(g), 0.0, levels, M, 1.0, bucket, d_g)
+    assert codes.cpu().numpy().tobytes() == codes_ref.tobytes()
+    ref = oracle.nested_decode(codes_ref, n, M, bucket, steps_ref, d_o, y, 1.0)
+    out = ndq.ndq_nested_decode(codes, n, M, 1.0, bucket, steps, d_g, _to_dev(y), 1.0)
+    assert np.array_equal(out.cpu().numpy(), ref)
+    # in place, as the running sum of the server loop
+    S = _to_dev(y.copy())
+    ndq.ndq_nested_decode(codes, n, M, 1.0, bucket, steps, d_g, S, 1.0, S, True)
+    ref_S = y.copy()
+    oracle.nested_decode(codes_ref, n, M, bucket, steps_ref, d_o, y, 1.0, out=ref_S)
+    assert np.array_equal(S.cpu().numpy(), ref_S)
+    # the fused server loop has its own fast pass / repeat logic per row of eight elements.  Side
+    # information some 10^5 steps away from the origin widens the doubtful zone around a tie to
+    # a few per cent of the unit, so that most rows are repeated with the division
+    big = (rng.uniform(-4.0e5, 4.0e5, n)).astype(F)
+    dq_ref, dq_steps = oracle.dq_encode(big, 0.0, 16, bucket, d_o)
+    first = oracle.dq_decode(dq_ref, n, 16, bucket, dq_steps, d_o)
+    approx = (first.astype(np.float64) + v - m) / M
+    doubtful = np.abs(np.abs(approx - np.rint(approx)) - 0.5) < 2.0 ** -21 * (np.abs(approx) + 1)
+    assert doubtful[: n // 512 * 512].reshape(-1, 512).any(axis=1).sum() >= 2     # a row: 64 lanes x 8 elements
+    ref_chain = first.copy()
+    oracle.nested_decode(codes_ref, n, M, bucket, steps_ref, d_o, first, 1.0, out=ref_chain)
+    dev = _gpu()
+    got = ndq.ndq_decode_chain(
+        [(torch.from_numpy(dq_ref).to(dev), torch.from_numpy(dq_steps).to(dev), ndq.NDQ_WORKER_DQ, 16, d_g),
+         (codes, steps, ndq.NDQ_WORKER_NESTED, M, d_g)], n, bucket, 1.0)
+    assert np.array_equal(got.cpu().numpy(), ref_chain)
+    # with shrinkage the reciprocal path is the same code
+    ref_a = oracle.nested_decode(codes_ref, n, M, bucket, steps_ref, d_o, y, 1.0, alpha=0.75)
+    out_a = ndq.ndq_nested_decode(codes, n, M, 0.75, bucket, steps, d_g, _to_dev(y), 1.0)
+    assert np.array_equal(out_a.cpu().numpy(), ref_a)
+
+
 def test_nested_equals_dqsg_inside_guaranteed_region_on_gpu():
     """|g - y| < (M-1) Delta / 2  =>  the nested reconstruction is the DQSG one."""
     n, M, levels = 1 << 18, 4, 64
