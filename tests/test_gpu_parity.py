@@ -6,6 +6,8 @@ the oracle's (the arithmetic is one subtraction and one multiplication in
 binary32 on values |q - v| <= 8.5 for the level counts used, so either
 operation order stays inside that bound; in practice the two agree exactly).
 """
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -967,15 +969,16 @@ def test_extreme_magnitudes_denormals_and_signed_zeros(dtype):
 
 def test_randomized_differential_against_oracle():
     """300 seeded random draws of (n, dtype, bucket, levels, M, alpha, preset, offset,
-    accumulate form): every entry point against the oracle, bit for bit."""
-    rng = np.random.default_rng(20240611)
+    accumulate form): every entry point against the oracle, bit for bit.  (NDQ_FUZZ_SEED and
+    NDQ_FUZZ_CASES in the environment run other draws, or more of them.)"""
+    rng = np.random.default_rng(int(os.environ.get("NDQ_FUZZ_SEED", "20240611")))
     dev = _gpu()
-    for case in range(300):
+    for case in range(int(os.environ.get("NDQ_FUZZ_CASES", "300"))):
         n = int(rng.choice([rng.integers(1, 300), rng.integers(300, 5000), rng.integers(5000, 40000)]))
         dtype = "bf16" if rng.random() < 0.5 else "f32"
-        bucket = int(rng.choice([0, 64, 128, 1024, 2048, 4096, 4160, 8192]))
+        bucket = int(rng.choice([0, 64, 128, 512, 1024, 2048, 4096, 4160, 8192, 16384]))
         levels = int(rng.choice([2, 3, 4, 5, 7, 8, 15, 16, 17, 64, 100, 255, 256]))
-        M = int(rng.choice([2, 3, 4, 5, 8, 16, 31, 256]))
+        M = int(rng.choice([2, 3, 4, 5, 6, 7, 8, 12, 16, 31, 65, 256]))
         alpha = float(rng.choice([1.0, 1.0, 0.9, 0.5]))
         offset = int(rng.choice([0, 8, 4096, (1 << 33) + 64])) if bucket == 0 else \
             int(rng.choice([0, 1, 7, 1 << 22])) * bucket
