@@ -970,11 +970,13 @@ def test_extreme_magnitudes_denormals_and_signed_zeros(dtype):
 def test_randomized_differential_against_oracle():
     """300 seeded random draws of (n, dtype, bucket, levels, M, alpha, preset, offset,
     accumulate form): every entry point against the oracle, bit for bit.  (NDQ_FUZZ_SEED and
-    NDQ_FUZZ_CASES in the environment run other draws, or more of them.)"""
+    NDQ_FUZZ_CASES in the environment run other draws, or more of them; NDQ_FUZZ_MAX_N longer
+    vectors.)"""
     rng = np.random.default_rng(int(os.environ.get("NDQ_FUZZ_SEED", "20240611")))
     dev = _gpu()
     for case in range(int(os.environ.get("NDQ_FUZZ_CASES", "300"))):
-        n = int(rng.choice([rng.integers(1, 300), rng.integers(300, 5000), rng.integers(5000, 40000)]))
+        n = int(rng.choice([rng.integers(1, 300), rng.integers(300, 5000),
+                            rng.integers(5000, int(os.environ.get("NDQ_FUZZ_MAX_N", "40000")))]))
         dtype = "bf16" if rng.random() < 0.5 else "f32"
         bucket = int(rng.choice([0, 64, 128, 512, 1024, 2048, 4096, 4160, 8192, 16384]))
         levels = int(rng.choice([2, 3, 4, 5, 7, 8, 15, 16, 17, 64, 100, 255, 256]))
