@@ -72,6 +72,10 @@ def lib():
         L.oracle_nested_code.restype = u32
         L.oracle_coset_index.argtypes = [u32, f32, f32, f32, u32]
         L.oracle_coset_index.restype = C.c_int32
+        L.oracle_coset_k.argtypes = [u32, f32, f32, f32, u32]
+        L.oracle_coset_k.restype = f32
+        L.oracle_coset_value.argtypes = [f32, u32, u32, f32, f32]
+        L.oracle_coset_value.restype = f32
         L.oracle_index_value.argtypes = [C.c_int32, f32, f32]
         L.oracle_index_value.restype = f32
         L.oracle_nested_code_alpha.argtypes = [f32, f32, f32, f32, u32]
@@ -192,6 +196,15 @@ def nested_code(g, inv_delta, v, M):
 
 def coset_index(m, y, inv_delta, v, M):
     return lib().oracle_coset_index(m, y, inv_delta, v, M)
+
+
+def coset_k(m, y, inv_delta, v, M):
+    """k of the coset representative m + M k (a binary32 integer value, unbounded)."""
+    return lib().oracle_coset_k(m, y, inv_delta, v, M)
+
+
+def coset_value(k, m, M, delta, v):
+    return lib().oracle_coset_value(k, m, M, delta, v)
 
 
 def index_value(q, delta, v):

@@ -150,18 +150,37 @@ uint32_t oracle_nested_code(float g, float inv_delta, float v, uint32_t M)
     return (uint32_t)m;
 }
 
-int32_t oracle_coset_index(uint32_t m, float y, float inv_delta, float v, uint32_t M)
+float oracle_coset_k(uint32_t m, float y, float inv_delta, float v, uint32_t M)
 {
     /* eq. (8), alpha = 1, s = m*Delta_1:
      *   x^ = y + r - Q2(r),  r = s - u - y
      *      = (m*Delta_1 - u) - Delta_2 * round((m*Delta_1 - u - y)/Delta_2)
      * i.e. the point (m + M*k)*Delta_1 - u of the coset nearest to y.  In index
-     * units: k = round((y/Delta_1 + v - m)/M). */
+     * units: k = round((y/Delta_1 + v - m)/M).  Eq. (8) puts no bound on k. */
     float c = fmaf(y, inv_delta, v);
-    float k = round_half_even((c - (float)m) / (float)M);
-    if (k > 4194304.0f) k = 4194304.0f;
-    if (k < -4194304.0f) k = -4194304.0f;
-    return (int32_t)m + (int32_t)M * (int32_t)k;
+    return round_half_even((c - (float)m) / (float)M);
+}
+
+int32_t oracle_coset_index(uint32_t m, float y, float inv_delta, float v, uint32_t M)
+{
+    /* q^ = m + M*k as a 32-bit integer, for the callers that count decode errors
+     * (saturated where it does not fit: side information 2^31 steps away) */
+    float k = oracle_coset_k(m, y, inv_delta, v, M);
+    if (!(k > -8388608.0f * 256.0f)) return INT32_MIN;
+    if (!(k < 8388608.0f * 256.0f)) return INT32_MAX;
+    int64_t q = (int64_t)m + (int64_t)M * (int64_t)k;
+    if (q > INT32_MAX) q = INT32_MAX;
+    if (q < INT32_MIN) q = INT32_MIN;
+    return (int32_t)q;
+}
+
+float oracle_coset_value(float k, uint32_t m, uint32_t M, float delta, float v)
+{
+    /* Alg. 2 server: Delta_1 * (q^ - v) with q^ = m + M*k brought to binary32 by one
+     * rounding of its exact value (what fmaf returns), however large k is */
+    float q = fmaf(k, (float)M, (float)m);
+    float centred = q - v;
+    return delta * centred;
 }
 
 /* ------------------------------------------------------------------------- */
@@ -182,8 +201,8 @@ float oracle_nested_value_alpha(uint32_t m, float y, float delta, float alpha, f
      * nearest to alpha*y/Delta_1 + v, hence
      *   x^ = y + alpha*(r - Q2(r)) = (1 - alpha^2)*y + alpha*Delta_1*(q^ - v). */
     float a = alpha * oracle_inv_step(delta);
-    int32_t q = oracle_coset_index(m, y, a, v, M);
-    float lattice = oracle_index_value(q, delta, v);
+    float k = oracle_coset_k(m, y, a, v, M);
+    float lattice = oracle_coset_value(k, m, M, delta, v);
     float beta = (float)(1.0 - (double)alpha * (double)alpha);
     float scaled = alpha * lattice;
     return fmaf(beta, y, scaled);

@@ -79,7 +79,9 @@ uint32_t oracle_nested_code(float g, float inv_delta, float v, uint32_t M);
 
 /* eq. (8) with alpha = 1: the integer congruent to m (mod M) nearest to
  * y/Delta + v; the decoded value is Delta * (that integer - v). */
+float oracle_coset_k(uint32_t m, float y, float inv_delta, float v, uint32_t M);
 int32_t oracle_coset_index(uint32_t m, float y, float inv_delta, float v, uint32_t M);
+float oracle_coset_value(float k, uint32_t m, uint32_t M, float delta, float v);
 float oracle_index_value(int32_t q, float delta, float v);
 
 /* eqs. (7)-(8) with a shrinkage factor 0 < alpha <= 1 (Sec. 3.2; Thm 4):

@@ -256,7 +256,9 @@ constexpr uint32_t kFieldAsFloatMaxBits = 5;   // four fields of a group stay in
 
 // Coset decoder of eq. (8), alpha = 1: the integer congruent to m (mod M) nearest
 // to y/Delta + v, returned as a float.  m + M*k is formed by one fma: exact while
-// below 2^24 and otherwise rounded once, exactly like converting the integer.
+// below 2^24 and otherwise rounded once, exactly like converting the exact
+// integer; eq. (8) puts no bound on k and neither does this.
+//
 // How coset_index_f divides by M.  kDivExact: the correctly rounded quotient, as
 // the decoder is defined.  kDivFast: the product with the rounded reciprocal,
 // which differs from that quotient by less than 2^-22 |quotient| and therefore
@@ -283,7 +285,6 @@ __device__ __forceinline__ float coset_index_f(float m_f, float y, float inv, fl
     } else {
         k = __builtin_rintf(diff / qp.M_f);
     }
-    k = __builtin_fminf(__builtin_fmaxf(k, -4194304.0f), 4194304.0f);
     return __builtin_fmaf(k, qp.M_f, m_f);
 }
 

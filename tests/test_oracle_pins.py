@@ -583,6 +583,47 @@ def test_mod_M_code_and_coset_search_equal_the_printed_equations(M):
     assert checked > 3500
 
 
+def _int_to_binary32(q):
+    """A Python integer rounded once, to nearest even, to binary32 (integer arithmetic only)."""
+    n = abs(q)
+    if n >= 1 << 24:
+        shift = n.bit_length() - 24
+        mant, rem, half = n >> shift, n & ((1 << shift) - 1), 1 << (shift - 1)
+        if rem > half or (rem == half and (mant & 1)):
+            mant += 1
+        n = mant << shift
+    return F(math.copysign(float(n), q)) if n else F(0.0)
+
+
+def test_coset_index_far_from_the_origin_is_still_a_nearest_coset_point():
+    """Eq. (8) bounds neither the side information nor k: with y up to 2^100 steps away the
+    representative m + M k (formed here on exact integers) is no farther from y/Delta + v than
+    half a coarse step plus the rounding of the two binary32 operations that lead to k
+    (exact rationals), the value is Delta times (that integer rounded ONCE to binary32, minus
+    the dither), and the 32-bit form agrees where it fits and saturates beyond."""
+    from fractions import Fraction
+    rng = np.random.default_rng(77)
+    ties_seen = 0
+    for _ in range(6000):
+        M = int(rng.integers(2, 257))
+        m = int(rng.integers(0, M))
+        v = F((int(rng.integers(0, 65536)) + 0.5) / 65536 - 0.5)
+        inv = F(2.0 ** rng.uniform(-3, 12))
+        y = F(rng.choice([-1, 1]) * 2.0 ** rng.uniform(0, 100) / float(inv))
+        k = oracle.coset_k(m, y, inv, v, M)
+        assert k == math.floor(k)
+        q = m + M * int(k)
+        target = Fraction(float(y)) * Fraction(float(inv)) + Fraction(float(v))
+        assert abs(Fraction(q) - target) <= Fraction(M, 2) + abs(target) * Fraction(1, 2 ** 21) + 1
+        assert oracle.coset_index(m, y, inv, v, M) == max(-2 ** 31, min(2 ** 31 - 1, q))
+        delta = F(0.37)
+        q32 = _int_to_binary32(q)
+        assert oracle.coset_value(k, m, M, delta, v) == F(delta * F(q32 - v))
+        # the cases a two-step rounding (through binary64) gets wrong: M k alone is a tie
+        ties_seen += int(_int_to_binary32(M * int(k)) != q32)
+    assert ties_seen > 5
+
+
 def test_coset_index_is_the_nearest_coset_point_brute_force():
     """Exhaustive: over every residue m, a grid of side information y and of
     dither values, the decoder picks arg-min_k |y - ((m + M k) Delta - u)|."""
