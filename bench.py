@@ -82,9 +82,9 @@ OPS = {
     # code -> float (mask, fma) + subtract dither + scale (+ add when accumulating)
     "dq_decode_store": lambda bf16: OPS_PHILOX + OPS_DITHER + 4,
     "dq_decode_accumulate": lambda bf16: OPS_PHILOX + OPS_DITHER + 5,
-    # code -> float (2), side scale, fma, subtract, divide by M, rint (2), clamp (2),
-    # fma, subtract dither, scale, add to the running sum
-    "nested_decode": lambda bf16: OPS_PHILOX + OPS_DITHER + 15,
+    # code -> float (2), side scale, fma, subtract, divide by M, rint (2), fma,
+    # subtract dither, scale, add to the running sum
+    "nested_decode": lambda bf16: OPS_PHILOX + OPS_DITHER + 13,
 }
 
 
