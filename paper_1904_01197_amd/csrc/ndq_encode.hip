@@ -4,8 +4,9 @@
 // Every kernel of the library is a streaming pass: one wave owns one tile of
 // consecutive elements, issues all of its 16-byte loads up front, regenerates
 // the dither with Philox in registers and writes coalesced vectors.  Nothing
-// is a contraction, so no MFMA; LDS is used only to transpose the small packed
-// codes into stream order.
+// is a contraction, so no MFMA; LDS only transposes the small packed codes into
+// stream order and, for buckets of two or four tiles, carries the tile maxima
+// between the waves of a workgroup.
 #include <hip/hip_runtime.h>
 
 #include "ndq.h"
@@ -42,13 +43,23 @@ template <int DT> struct TileRegs { typename Elem<DT>::Row row[EncRows<DT>::R]; 
 // Issues all 16-byte loads of a tile back to back.  FULL: every element of the
 // tile is valid, no guards; otherwise elements past the end read as zero.
 template <int DT, bool FULL>
-__device__ __forceinline__ void load_tile(const EncodeArgs& a, const TileRef& t, int lane, TileRegs<DT>& regs)
+__device__ __forceinline__ void load_tile(const void* g, const TileRef& t, int lane, TileRegs<DT>& regs)
 {
     using T = Elem<DT>;
-    const typename T::scalar* tile = (const typename T::scalar*)a.g + t.start;
+    const typename T::scalar* tile = (const typename T::scalar*)g + t.start;
 #pragma unroll
     for (int r = 0; r < EncRows<DT>::R; ++r)
         regs.row[r] = load_row<DT, FULL>(tile, (uint32_t)(r * kWave + lane) * kLaneElems, t.len);
+}
+
+// folds the lane's share of a tile into its running max |g|
+template <int DT>
+__device__ __forceinline__ typename Elem<DT>::maxacc lane_max(typename Elem<DT>::maxacc m,
+                                                               const TileRegs<DT>& regs)
+{
+#pragma unroll
+    for (int r = 0; r < EncRows<DT>::R; ++r) m = Elem<DT>::max_update(m, regs.row[r]);
+    return m;
 }
 
 // max |g| over the tile a wave holds (Sec. 3.1 eq. (2)), the same in every lane
@@ -56,10 +67,7 @@ template <int DT>
 __device__ __forceinline__ float tile_max(const TileRegs<DT>& regs)
 {
     using T = Elem<DT>;
-    typename T::maxacc m = T::max_init();
-#pragma unroll
-    for (int r = 0; r < EncRows<DT>::R; ++r) m = T::max_update(m, regs.row[r]);
-    return wave_max(T::max_final(m));
+    return wave_max(T::max_final(lane_max<DT>(T::max_init(), regs)));
 }
 
 // One wave encodes the tile it holds: finds the step, quantizes, and leaves the
@@ -219,8 +227,8 @@ void encode_kernel(EncodeArgs a)
         // also one whose tile is empty.
         __shared__ float part[kWavesPerBlock];
         TileRegs<DT> regs;
-        if (t.len == TILE) load_tile<DT, true>(a, t, lane, regs);
-        else if (t.len != 0) load_tile<DT, false>(a, t, lane, regs);
+        if (t.len == TILE) load_tile<DT, true>(a.g, t, lane, regs);
+        else if (t.len != 0) load_tile<DT, false>(a.g, t, lane, regs);
         float kappa = 0.0f;
         if (t.len != 0) kappa = tile_max<DT>(regs);
         if (lane == 0) part[wave] = kappa;
@@ -235,12 +243,12 @@ void encode_kernel(EncodeArgs a)
             encode_tile<DT, MODE, true, false, false>(a, t, tile_id, regs, kappa, writes_step, stage, lane);
     } else if (t.len == TILE) {
         TileRegs<DT> regs;
-        load_tile<DT, true>(a, t, lane, regs);
+        load_tile<DT, true>(a.g, t, lane, regs);
         const float kappa = (FUSED && !MULTI) ? tile_max<DT>(regs) : 0.0f;
         encode_tile<DT, MODE, FUSED, true, MULTI>(a, t, tile_id, regs, kappa, true, stage, lane);
     } else if (t.len != 0) {
         TileRegs<DT> regs;
-        load_tile<DT, false>(a, t, lane, regs);
+        load_tile<DT, false>(a.g, t, lane, regs);
         const float kappa = (FUSED && !MULTI) ? tile_max<DT>(regs) : 0.0f;
         encode_tile<DT, MODE, FUSED, false, MULTI>(a, t, tile_id, regs, kappa, true, stage, lane);
     }
@@ -275,22 +283,10 @@ __global__ __launch_bounds__(kBlock) void absmax_kernel(const void* g, Tiling tl
         blockIdx.x * kWavesPerBlock + __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     const TileRef t = locate_tile(tl, tile_id, TILE);
     if (t.len == 0) return;
-    const typename T::scalar* tile = (const typename T::scalar*)g + t.start;
-    constexpr int ROWS = EncRows<DT>::R;
-    typename T::Row raw[ROWS];
-    if (t.len == TILE) {
-#pragma unroll
-        for (int r = 0; r < ROWS; ++r)
-            raw[r] = load_row<DT, true>(tile, (uint32_t)(r * kWave + lane) * kLaneElems, t.len);
-    } else {
-#pragma unroll
-        for (int r = 0; r < ROWS; ++r)
-            raw[r] = load_row<DT, false>(tile, (uint32_t)(r * kWave + lane) * kLaneElems, t.len);
-    }
-    typename T::maxacc acc = T::max_init();
-#pragma unroll
-    for (int r = 0; r < ROWS; ++r) acc = T::max_update(acc, raw[r]);
-    const float m = wave_max(T::max_final(acc));
+    TileRegs<DT> regs;
+    if (t.len == TILE) load_tile<DT, true>(g, t, lane, regs);
+    else load_tile<DT, false>(g, t, lane, regs);
+    const float m = tile_max<DT>(regs);
     // non-negative floats order like their bit patterns
     if (lane == 0) atomicMax(kappa_bits + t.bucket, __float_as_uint(m));
 }
@@ -316,19 +312,10 @@ __global__ __launch_bounds__(kBlock) void absmax_span_kernel(const void* g, Tili
     for (uint32_t j = first; j < tl.tiles_per_bucket; j += stride) {
         const TileRef t = locate_tile(tl, bucket * tl.tiles_per_bucket + j, TILE);
         if (t.len == 0) break;   // past the end of the vector: so are this wave's later tiles
-        const typename T::scalar* tile = (const typename T::scalar*)g + t.start;
-        typename T::Row raw[ROWS];
-        if (t.len == TILE) {
-#pragma unroll
-            for (int r = 0; r < ROWS; ++r)
-                raw[r] = load_row<DT, true>(tile, (uint32_t)(r * kWave + lane) * kLaneElems, t.len);
-        } else {
-#pragma unroll
-            for (int r = 0; r < ROWS; ++r)
-                raw[r] = load_row<DT, false>(tile, (uint32_t)(r * kWave + lane) * kLaneElems, t.len);
-        }
-#pragma unroll
-        for (int r = 0; r < ROWS; ++r) acc = T::max_update(acc, raw[r]);
+        TileRegs<DT> regs;
+        if (t.len == TILE) load_tile<DT, true>(g, t, lane, regs);
+        else load_tile<DT, false>(g, t, lane, regs);
+        acc = lane_max<DT>(acc, regs);
     }
     const float m = wave_max(T::max_final(acc));
     if (lane == 0) part[wave] = m;
