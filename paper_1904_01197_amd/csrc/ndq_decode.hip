@@ -182,7 +182,7 @@ struct ChainArgs {
     int apply_scale;
     float scale;
     uint32_t row_buckets; // 1: a bucket is one row of a tile (tiling is by tile, a step per row)
-    uint32_t num_buckets;
+    uint32_t num_buckets; // with row_buckets: steps per worker (rows past them decode with step 0)
 };
 
 // What is prefetched per worker: the step and, per row, the words holding the
@@ -628,7 +628,7 @@ int ndq_decode_chain(const ndq_worker* workers, uint32_t W, size_t n, uint32_t b
     ChainArgs a;
     // buckets of exactly one row share a tile, each row with its own step
     a.row_buckets = (kChainRows > 1 && bucket == kWave * kLaneElems) ? 1u : 0u;
-    a.num_buckets = (uint32_t)ndq_num_buckets(n, bucket);
+    a.num_buckets = a.row_buckets ? (uint32_t)ndq_num_buckets(n, bucket) : 0u;   // n < 2^40: fits
     int rc = make_tiling(n, a.row_buckets ? kChainTile : bucket, kChainTile, &a.tl);
     if (rc != NDQ_OK) return rc;
     a.out = out;
