@@ -309,6 +309,32 @@ def test_exact_rounding_ties_go_to_the_even_index_on_the_gpu_too(bucket):
     assert codes.cpu().numpy().tobytes() == c_ref.tobytes()
     assert np.array_equal(ndq.ndq_dq_decode(codes, n, 5, bucket, steps, d_g).cpu().numpy(),
                           oracle.dq_decode(c_ref, n, 5, bucket, s_ref, d_o))
+    # DQSG with other odd level counts (max-norm (L-1)/2: step exactly 1; -q_min odd and even),
+    # every element a tie, the extreme ones sitting half a step inside the outermost level
+    for levels in (3, 7, 9, 33):
+        kap = (levels - 1) // 2
+        halves = np.arange(-kap, kap) + 0.5
+        gl = (rng.choice(halves, n) - v).astype(F)
+        assert np.array_equal(gl.astype(np.float64) + v, np.round(gl.astype(np.float64) + v - 0.5) + 0.5)
+        gl[::2048] = F(kap)
+        gl[-1] = F(-kap)
+        c_ref, s_ref = oracle.dq_encode(gl, 0.0, levels, bucket, d_o)
+        assert np.all(s_ref == F(1.0))
+        codes, steps = ndq.ndq_dq_encode(_to_dev(gl), 0.0, levels, bucket, d_g)
+        assert np.array_equal(steps.cpu().numpy(), s_ref)
+        assert codes.cpu().numpy().tobytes() == c_ref.tobytes(), levels
+        unpacked = oracle.unpack(c_ref, n, oracle.code_bits(levels))
+        assert unpacked.min() == 0 and unpacked.max() == levels - 1          # both outermost levels occur
+        # a third of the elements at +-max|g| under every dither value, and the same with a
+        # max-norm whose step and reciprocal both round (the closest the index comes to overload)
+        for kappa in (F(kap), F(kap) * F(1.2345678)):
+            gx = (rng.uniform(-1.0, 1.0, n) * float(kappa)).astype(F)
+            gx[::3] = kappa
+            gx[1::3] = -kappa
+            c_ref, s_ref = oracle.dq_encode(gx, 0.0, levels, bucket, d_o)
+            codes, steps = ndq.ndq_dq_encode(_to_dev(gx), 0.0, levels, bucket, d_g)
+            assert np.array_equal(steps.cpu().numpy(), s_ref)
+            assert codes.cpu().numpy().tobytes() == c_ref.tobytes(), (levels, float(kappa))
 
 
 @pytest.mark.parametrize("M", [3, 5, 6, 7, 12])
