@@ -230,6 +230,9 @@ def main():
         calls.append((enc_key, enc, algorithmic_bytes("encode", n, bits, K, s_in), n * enc_ops))
         decs.append((dec_key, dec, algorithmic_bytes(dkind, n, bits, K, s_in),
                      n * OPS[dkind](bf16)))
+    enc_bytes = sum(c[2] for c in calls)
+    serial_bytes = enc_bytes + sum(d[2] for d in decs) + (8 * n if wl.out_scale != 1.0 else 0)
+    fused_bytes = enc_bytes + chain_bytes
     if args.schedule == "fused":
         calls.append(("decode_chain_w%d" % wl.W,
                       lambda: pipeline.decode_chain_fused(wl, n, bufs, ds), chain_bytes, chain_ops))
@@ -404,7 +407,12 @@ def main():
         "roofline": roofline,
         "cpu_baseline": cpu,
         "kernels": kernels,
-        "other_schedule": {"schedule": other, "ms_per_step": round(other_ms, 4)},
+        "other_schedule": {
+            "schedule": other, "ms_per_step": round(other_ms, 4),
+            "value": round(grad_bytes / (other_ms * 1e-3) / 1e9, 2),
+            "step_algorithmic_bytes": serial_bytes if other == "serial" else fused_bytes,
+            "step_hbm_frac_of_peak": round((serial_bytes if other == "serial" else fused_bytes)
+                                           / (other_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
         "input_generation_s": round(gen_s, 1),
         "extras": extras,
     }
