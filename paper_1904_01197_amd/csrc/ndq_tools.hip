@@ -92,17 +92,102 @@ __global__ __launch_bounds__(kHistBlock) void histogram_kernel(const uint32_t* _
     }
 }
 
+// 1- and 2-bit codes: a thread takes 16 bytes (128 or 64 codes) at a time, eight
+// such loads in flight, and counts with population counts.  Few, large workgroups
+// (at most kSmallBlocks of kSmallThreads), because every workgroup ends with one
+// atomic per bin on the same few addresses and those serialize.  A thread sees at
+// most n / 2^18 + 1024 codes (n < 2^40), a wave 64 times that: 32-bit counts up to
+// the wave's sum, 64-bit ones across waves.
+constexpr uint32_t kSmallBlocks = 256;
+constexpr uint32_t kSmallThreads = 1024;
+constexpr int kSmallInFlight = 8;
+
+__device__ __forceinline__ void count_small(uint32_t w, uint32_t bits, uint32_t& c1, uint32_t& c2, uint32_t& c3)
+{
+    if (bits == 1u) {
+        c1 += __builtin_popcount(w);
+    } else {
+        const uint32_t lo = w & 0x55555555u, hi = (w >> 1) & 0x55555555u;
+        c1 += __builtin_popcount(lo & ~hi);
+        c2 += __builtin_popcount(hi & ~lo);
+        c3 += __builtin_popcount(lo & hi);
+    }
+}
+
+__device__ __forceinline__ void count_small(const uint4& x, uint32_t bits, uint32_t& c1, uint32_t& c2, uint32_t& c3)
+{
+    count_small(x.x, bits, c1, c2, c3); count_small(x.y, bits, c1, c2, c3);
+    count_small(x.z, bits, c1, c2, c3); count_small(x.w, bits, c1, c2, c3);
+}
+
+__global__ __launch_bounds__(kSmallThreads) void histogram_small_kernel(const uint4* __restrict__ vec, uint64_t n,
+                                                                        uint32_t bits, unsigned long long* hist)
+{
+    __shared__ uint32_t part[3][kSmallThreads / 64];
+    const uint32_t tid = threadIdx.x;
+    // whole 16-byte vectors here; the last, partial one (the stream is allocated in
+    // multiples of 16 bytes) is masked to its valid bits below.  Bits masked away
+    // read as code 0, and bin 0 is n minus the other bins anyway.
+    const uint64_t vectors = (n * bits) >> 7;
+    const uint64_t stride = (uint64_t)gridDim.x * kSmallThreads;
+    uint32_t c[3] = {0u, 0u, 0u};
+    uint64_t u = (uint64_t)blockIdx.x * kSmallThreads + tid;
+    for (; u + (kSmallInFlight - 1) * stride < vectors; u += kSmallInFlight * stride) {
+        uint4 x[kSmallInFlight];
+#pragma unroll
+        for (int j = 0; j < kSmallInFlight; ++j) x[j] = vec[u + (uint64_t)j * stride];
+#pragma unroll
+        for (int j = 0; j < kSmallInFlight; ++j) count_small(x[j], bits, c[0], c[1], c[2]);
+    }
+    for (; u < vectors; u += stride) count_small(vec[u], bits, c[0], c[1], c[2]);
+    const uint32_t tail_bits = (uint32_t)((n * bits) & 127u);
+    if (blockIdx.x == 0 && tid == 0 && tail_bits != 0u) {
+        const uint4 x = vec[vectors];
+        const uint32_t w[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+        for (uint32_t j = 0; j < 4u; ++j) {
+            const uint32_t have = tail_bits > 32u * j ? tail_bits - 32u * j : 0u;
+            const uint32_t mask = have >= 32u ? 0xffffffffu : ((1u << have) - 1u);
+            count_small(w[j] & mask, bits, c[0], c[1], c[2]);
+        }
+    }
+#pragma unroll
+    for (int b = 0; b < 3; ++b) {
+        for (int off = 32; off >= 1; off >>= 1) c[b] += __shfl_down(c[b], off, 64);
+        if ((tid & 63u) == 0u) part[b][tid >> 6] = c[b];
+    }
+    __syncthreads();
+    // bins 1..3 (or bin 1) by atomics; bin 0 follows from n in entropy_kernel
+    const uint32_t nbins = 1u << bits;
+    if (tid >= 1u && tid < nbins) {
+        unsigned long long sum = 0u;
+        for (uint32_t w = 0; w < kSmallThreads / 64u; ++w) sum += part[tid - 1u][w];
+        if (sum) atomicAdd(hist + tid, sum);
+    }
+}
+
 __global__ void fill_zero64_kernel(unsigned long long* p, uint32_t count)
 {
     if (threadIdx.x < count) p[threadIdx.x] = 0ull;
 }
 
 // -sum p log2 p over at most 256 bins, binary64, fixed reduction order
-__global__ __launch_bounds__(256) void entropy_kernel(const unsigned long long* hist, uint32_t nbins,
-                                                      uint64_t n, double* entropy_out)
+// (derive_bin0: the 1- and 2-bit histogram leaves bin 0 to be filled in here as
+// what the other bins leave of n; entropy_out may then be null)
+__global__ __launch_bounds__(256) void entropy_kernel(unsigned long long* hist, uint32_t nbins,
+                                                      uint64_t n, double* entropy_out, int derive_bin0)
 {
     __shared__ double term[256];
     const uint32_t tid = threadIdx.x;
+    if (derive_bin0) {
+        if (tid == 0) {
+            unsigned long long rest = n;
+            for (uint32_t b = 1; b < nbins; ++b) rest -= hist[b];
+            hist[0] = rest;
+        }
+        __syncthreads();
+        if (!entropy_out) return;
+    }
     double t = 0.0;
     if (tid < nbins && n) {
         const unsigned long long h = hist[tid];
@@ -125,73 +210,124 @@ __global__ __launch_bounds__(256) void entropy_kernel(const unsigned long long* 
 // per 32-bit word as the number sum_j c_j L^j.  Transcoders between the
 // fixed-width stream and the dense one.  A thread owns 8 dense words = 8k
 // indices = k*bits whole bytes of the fixed-width stream, so no two threads
-// touch the same byte.
+// share a byte.
 // ---------------------------------------------------------------------------
 struct DenseArgs {
     unsigned char* fixed;     // fixed-width stream (read by pack, written by unpack)
     uint32_t* dense;          // dense stream (written by pack, read by unpack)
     uint64_t n;               // indices
-    uint64_t fixed_valid;     // ceil(n*bits/8): bytes of the fixed stream that hold indices
     uint64_t fixed_total;     // its padded size
     uint64_t dense_valid;     // ceil(n/k) words that hold indices
     uint64_t dense_total;     // padded size in words
     uint32_t levels, k, bits;
+    // division of a 32-bit number by `levels` through one high multiply (division by
+    // an invariant integer, round-up method): with l = ceil(log2 levels) and
+    // magic = floor(2^32 (2^l - levels) / levels) + 1, for every 32-bit x
+    // x / levels = (t + ((x - t) >> 1)) >> (l - 1), t = high word of x * magic
+    uint32_t magic, shift;
 };
 
-__global__ __launch_bounds__(256) void dense_pack_kernel(DenseArgs a)
+__device__ __forceinline__ uint32_t divide_by_levels(uint32_t x, const DenseArgs& a)
 {
-    const uint64_t t = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const uint64_t w0 = t * 8u;
-    if (w0 >= a.dense_total) return;
-    uint64_t byte = t * a.k * a.bits;
+    const uint32_t t = __umulhi(x, a.magic);
+    return (t + ((x - t) >> 1)) >> a.shift;
+}
+
+// Both transcoders stage a workgroup's share of the two streams in LDS: a thread's
+// bytes lie k*bits (at most kDenseThreadBytes) apart from its neighbour's, so direct
+// byte accesses would each be a memory transaction of their own; the workgroup's
+// share is contiguous and moves as whole 32-bit words instead.
+constexpr uint32_t kDenseThreadBytes = 40;     // max of k * bits over levels 2..256
+constexpr uint32_t kDenseBlock = 256;
+constexpr uint32_t kDenseWordsPerThread = 8;
+
+struct DenseStage {
+    uint32_t dense[kDenseBlock * kDenseWordsPerThread];
+    uint32_t fixed[kDenseBlock * kDenseThreadBytes / 4];
+};
+
+// bytes of the fixed-width stream that belong to this workgroup (a multiple of 4:
+// its first byte is a multiple of 256 and the stream's size one of 16)
+__device__ __forceinline__ uint32_t dense_block_bytes(const DenseArgs& a, uint64_t block_byte0)
+{
+    const uint64_t share = (uint64_t)kDenseBlock * a.k * a.bits;
+    if (block_byte0 >= a.fixed_total) return 0u;
+    const uint64_t left = a.fixed_total - block_byte0;
+    return (uint32_t)(left < share ? left : share);
+}
+
+__global__ __launch_bounds__(kDenseBlock) void dense_pack_kernel(DenseArgs a)
+{
+    __shared__ DenseStage st;
+    const uint32_t tid = threadIdx.x;
+    const uint32_t thread_bytes = a.k * a.bits;
+    const uint64_t block_byte0 = (uint64_t)blockIdx.x * kDenseBlock * thread_bytes;
+    const uint64_t block_w0 = (uint64_t)blockIdx.x * kDenseBlock * kDenseWordsPerThread;
+    const uint32_t words_in = dense_block_bytes(a, block_byte0) / 4u;
+    const uint32_t* fixed32 = reinterpret_cast<const uint32_t*>(a.fixed + block_byte0);
+    for (uint32_t i = tid; i < kDenseBlock * thread_bytes / 4u; i += kDenseBlock)
+        st.fixed[i] = i < words_in ? fixed32[i] : 0u;
+    __syncthreads();
+    const unsigned char* mine = reinterpret_cast<const unsigned char*>(st.fixed) + tid * thread_bytes;
     const uint32_t mask = (1u << a.bits) - 1u;
-    uint32_t buf = 0u, have = 0u;
-    for (uint32_t j = 0; j < 8u; ++j) {
-        const uint64_t w = w0 + j;
-        if (w >= a.dense_total) break;
-        uint64_t value = 0u, weight = 1u;
+    uint32_t buf = 0u, have = 0u, byte = 0u;
+    for (uint32_t j = 0; j < kDenseWordsPerThread; ++j) {
+        const uint64_t w = block_w0 + tid * kDenseWordsPerThread + j;
+        // sum_j c_j L^j <= L^k - 1 < 2^32; the weight may wrap after the last digit, unused
+        uint32_t value = 0u, weight = 1u;
         for (uint32_t d = 0; d < a.k; ++d) {
             if (have < a.bits) {
-                const uint32_t b = byte < a.fixed_valid ? a.fixed[byte] : 0u;
-                ++byte;
-                buf |= b << have;
+                buf |= (uint32_t)mine[byte++] << have;
                 have += 8u;
             }
             uint32_t c = buf & mask;
             buf >>= a.bits;
             have -= a.bits;
-            if (w * a.k + d >= a.n) c = 0u;
+            if (w * a.k + d >= a.n) c = 0u;      // also hides whatever the padding holds
             value += c * weight;
             weight *= a.levels;
         }
-        a.dense[w] = (uint32_t)value;
+        st.dense[tid * kDenseWordsPerThread + j] = value;
     }
+    __syncthreads();
+    for (uint32_t i = tid; i < kDenseBlock * kDenseWordsPerThread; i += kDenseBlock)
+        if (block_w0 + i < a.dense_total) a.dense[block_w0 + i] = st.dense[i];
 }
 
-__global__ __launch_bounds__(256) void dense_unpack_kernel(DenseArgs a)
+__global__ __launch_bounds__(kDenseBlock) void dense_unpack_kernel(DenseArgs a)
 {
-    const uint64_t t = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    uint64_t byte = t * a.k * a.bits;
-    if (byte >= a.fixed_total) return;
-    const uint64_t w0 = t * 8u;
-    uint32_t buf = 0u, have = 0u;
-    for (uint32_t j = 0; j < 8u; ++j) {
-        const uint64_t w = w0 + j;
-        uint32_t value = w < a.dense_valid ? a.dense[w] : 0u;
+    __shared__ DenseStage st;
+    const uint32_t tid = threadIdx.x;
+    const uint32_t thread_bytes = a.k * a.bits;
+    const uint64_t block_byte0 = (uint64_t)blockIdx.x * kDenseBlock * thread_bytes;
+    const uint64_t block_w0 = (uint64_t)blockIdx.x * kDenseBlock * kDenseWordsPerThread;
+    for (uint32_t i = tid; i < kDenseBlock * kDenseWordsPerThread; i += kDenseBlock)
+        st.dense[i] = block_w0 + i < a.dense_valid ? a.dense[block_w0 + i] : 0u;
+    __syncthreads();
+    unsigned char* mine = reinterpret_cast<unsigned char*>(st.fixed) + tid * thread_bytes;
+    uint32_t buf = 0u, have = 0u, byte = 0u;
+    for (uint32_t j = 0; j < kDenseWordsPerThread; ++j) {
+        const uint64_t w = block_w0 + tid * kDenseWordsPerThread + j;
+        uint32_t value = st.dense[tid * kDenseWordsPerThread + j];
         for (uint32_t d = 0; d < a.k; ++d) {
-            uint32_t c = value % a.levels;
-            value /= a.levels;
+            const uint32_t q = divide_by_levels(value, a);
+            uint32_t c = value - q * a.levels;
+            value = q;
             if (w * a.k + d >= a.n) c = 0u;
             buf |= c << have;
             have += a.bits;
             if (have >= 8u) {
-                if (byte < a.fixed_total) a.fixed[byte] = (unsigned char)buf;
-                ++byte;
+                mine[byte++] = (unsigned char)buf;
                 buf >>= 8;
                 have -= 8u;
             }
         }
     }
+    // 8 k bits per thread are whole bytes: nothing is left in buf
+    __syncthreads();
+    const uint32_t words_out = dense_block_bytes(a, block_byte0) / 4u;
+    uint32_t* fixed32 = reinterpret_cast<uint32_t*>(a.fixed + block_byte0);
+    for (uint32_t i = tid; i < words_out; i += kDenseBlock) fixed32[i] = st.fixed[i];
 }
 
 // ---------------------------------------------------------------------------
@@ -270,7 +406,15 @@ int ndq_code_entropy(const void* codes, size_t n, uint32_t bits, uint64_t* hist_
     const uint32_t nbins = 1u << bits;
     hipLaunchKernelGGL(fill_zero64_kernel, dim3(1), dim3(256), 0, s, (unsigned long long*)hist_out, nbins);
     if (launched() != NDQ_OK) return NDQ_ELAUNCH;
-    if (n != 0) {
+    if (n != 0 && bits <= 2u) {
+        const uint64_t vectors = ((uint64_t)n * bits) >> 7;
+        uint64_t blocks = (vectors + kSmallInFlight * kSmallThreads - 1) / (kSmallInFlight * kSmallThreads);
+        if (blocks > kSmallBlocks) blocks = kSmallBlocks;
+        if (blocks == 0u) blocks = 1u;
+        hipLaunchKernelGGL(histogram_small_kernel, dim3((uint32_t)blocks), dim3(kSmallThreads), 0, s,
+                           (const uint4*)codes, (uint64_t)n, bits, (unsigned long long*)hist_out);
+        if (launched() != NDQ_OK) return NDQ_ELAUNCH;
+    } else if (n != 0) {
         const uint64_t units = (n + 31u) >> 5;
         uint64_t blocks = (units + kHistBlock - 1) / kHistBlock;
         if (blocks > 4096u) blocks = 4096u;
@@ -278,9 +422,10 @@ int ndq_code_entropy(const void* codes, size_t n, uint32_t bits, uint64_t* hist_
                            (const uint32_t*)codes, (uint64_t)n, bits, (unsigned long long*)hist_out);
         if (launched() != NDQ_OK) return NDQ_ELAUNCH;
     }
-    if (entropy_out) {
-        hipLaunchKernelGGL(entropy_kernel, dim3(1), dim3(256), 0, s,
-                           (const unsigned long long*)hist_out, nbins, (uint64_t)n, entropy_out);
+    const int derive_bin0 = n != 0 && bits <= 2u;
+    if (entropy_out || derive_bin0) {
+        hipLaunchKernelGGL(entropy_kernel, dim3(1), dim3(256), 0, s, (unsigned long long*)hist_out, nbins,
+                           (uint64_t)n, entropy_out, derive_bin0);
         if (launched() != NDQ_OK) return NDQ_ELAUNCH;
     }
     return NDQ_OK;
@@ -319,7 +464,8 @@ static int dense_common(const void* fixed, const void* dense, size_t n, uint32_t
     a.n = n;
     a.levels = levels;
     a.bits = code_bits(levels);
-    a.fixed_valid = ((uint64_t)n * a.bits + 7u) / 8u;
+    a.shift = a.bits - 1u;      // bits = ceil(log2 levels) >= 1
+    a.magic = (uint32_t)((((uint64_t)1 << 32) * (((uint64_t)1 << a.bits) - levels)) / levels + 1u);
     a.fixed_total = packed_bytes(n, a.bits);
     a.dense_valid = ((uint64_t)n + a.k - 1u) / a.k;
     a.dense_total = ndq_dense_bytes(n, levels) / 4u;
@@ -328,8 +474,9 @@ static int dense_common(const void* fixed, const void* dense, size_t n, uint32_t
                                   : (a.fixed_total + per_thread_bytes - 1u) / per_thread_bytes;
     const uint64_t blocks = (threads + 255u) / 256u;
     if (blocks >= ((uint64_t)1 << 31)) return NDQ_EUNSUPPORTED;
-    if (pack) hipLaunchKernelGGL(dense_pack_kernel, dim3((uint32_t)blocks), dim3(256), 0, (hipStream_t)stream, a);
-    else hipLaunchKernelGGL(dense_unpack_kernel, dim3((uint32_t)blocks), dim3(256), 0, (hipStream_t)stream, a);
+    if (per_thread_bytes > kDenseThreadBytes) return NDQ_EUNSUPPORTED;   // cannot happen for levels <= 256
+    if (pack) hipLaunchKernelGGL(dense_pack_kernel, dim3((uint32_t)blocks), dim3(kDenseBlock), 0, (hipStream_t)stream, a);
+    else hipLaunchKernelGGL(dense_unpack_kernel, dim3((uint32_t)blocks), dim3(kDenseBlock), 0, (hipStream_t)stream, a);
     return launched();
 }
 

@@ -733,6 +733,23 @@ def test_code_histogram_and_entropy_match_oracle(bits):
         assert abs(float(ent.item()) - ref_e) <= 1e-9, (bits, n)
 
 
+@pytest.mark.parametrize("bits", [1, 2, 3, 8])
+def test_code_histogram_ignores_what_lies_in_the_padding(bits):
+    """Bits of the stream beyond code n-1 are not counted, whatever they hold."""
+    dev = _gpu()
+    for n in (1, 5, 63, 64, 65, 127, 129, 1000, 70001, 1 << 20):
+        rng = np.random.default_rng(100 * n + bits)
+        codes = rng.integers(0, 1 << bits, size=n, dtype=np.uint32)
+        packed = oracle.pack(codes, bits).copy()
+        ref_h = oracle.code_histogram(packed, n, bits)
+        used = n * bits
+        tail = np.unpackbits(packed, bitorder="little")
+        tail[used:] = 1
+        dirty = np.packbits(tail, bitorder="little")
+        hist, _ = ndq.ndq_code_entropy(torch.from_numpy(dirty).to(dev), n, bits)
+        assert np.array_equal(hist.cpu().numpy().astype(np.uint64), ref_h), (bits, n)
+
+
 def test_entropy_of_the_benchmark_code_streams():
     """Entropy of the actual DQSG / nested index streams of config 5 (reduced size):
     GPU histogram against the oracle's, bit-exact."""
@@ -768,6 +785,11 @@ def test_dense_stream_matches_oracle(levels):
         fixed_d = torch.from_numpy(fixed).to(dev)
         dense = ndq.ndq_dense_pack(fixed_d, n, levels)
         assert dense.cpu().numpy().tobytes() == ref.tobytes(), (levels, n)
+        # what lies beyond code n-1 in the fixed-width stream does not reach the dense one
+        stream_bits = np.unpackbits(fixed, bitorder="little")
+        stream_bits[n * bits:] = 1
+        dirty = torch.from_numpy(np.packbits(stream_bits, bitorder="little")).to(dev)
+        assert ndq.ndq_dense_pack(dirty, n, levels).cpu().numpy().tobytes() == ref.tobytes(), (levels, n)
         back = torch.full((fixed.size,), 0xAB, dtype=torch.uint8, device=dev)
         ndq.ndq_dense_unpack(dense, n, levels, back)
         assert back.cpu().numpy().tobytes() == fixed.tobytes(), (levels, n)
