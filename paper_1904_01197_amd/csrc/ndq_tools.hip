@@ -14,81 +14,84 @@ namespace ndq {
 // ---------------------------------------------------------------------------
 // Histogram and entropy of an index stream (Sec. 4: the bit rate after entropy
 // coding is reported through the entropy of the transmitted indices).
-// A thread reads units of 32 codes (= `bits` consecutive 32-bit words) with a
-// small bit reader.  Counting: 1-bit and 2-bit streams by population count in
-// registers; up to 16 bins in a private LDS column per thread (no conflicts);
-// wider codes with LDS atomics on one histogram per workgroup.
+// Few, large workgroups in both kernels: every workgroup ends with one atomic per
+// bin on the same few addresses, and those serialize.
+//
+// Codes of 3 to 8 bits: a thread reads units of 32 codes (= BITS consecutive
+// 32-bit words, the next unit already in flight) and takes the codes out with
+// shifts known at compile time.  Counting: 32 copies of the workgroup's histogram
+// in LDS, a lane adding to copy (lane mod 32) -- the word index is
+// code * 32 + copy, so the 32 lanes that LDS serves together always fall into 32
+// different banks, whatever the distribution of the codes (index streams are
+// heavily peaked); the two halves of a wave are served one after the other anyway.
 // ---------------------------------------------------------------------------
-constexpr int kHistBlock = 256;
+constexpr uint32_t kHistThreads = 1024;
+constexpr uint32_t kHistBlocks = 256;
+constexpr uint32_t kHistCopies = 32;
 
-__global__ __launch_bounds__(kHistBlock) void histogram_kernel(const uint32_t* __restrict__ words,
-                                                               uint64_t n, uint32_t bits,
-                                                               unsigned long long* hist)
+template <int BITS>
+__device__ __forceinline__ void load_unit(const uint32_t* __restrict__ words, uint64_t u, uint32_t (&w)[BITS])
 {
-    __shared__ uint32_t cols[16][kHistBlock];   // bits <= 4: one column per thread
-    __shared__ uint32_t wide[256];              // bits  > 4: shared, atomic
+    const uint32_t* p = words + u * BITS;
+    if constexpr (BITS % 4 == 0) {      // 16-byte aligned: the stream is, and so is every unit
+#pragma unroll
+        for (int k = 0; k < BITS / 4; ++k) {
+            const uint4 x = reinterpret_cast<const uint4*>(p)[k];
+            w[4 * k] = x.x; w[4 * k + 1] = x.y; w[4 * k + 2] = x.z; w[4 * k + 3] = x.w;
+        }
+    } else {
+#pragma unroll
+        for (int k = 0; k < BITS; ++k) w[k] = p[k];
+    }
+}
+
+template <int BITS>
+__global__ __launch_bounds__(kHistThreads) void histogram_kernel(const uint32_t* __restrict__ words, uint64_t n,
+                                                                 unsigned long long* hist)
+{
+    constexpr uint32_t NB = 1u << BITS;
+    constexpr uint32_t MASK = NB - 1u;
+    __shared__ uint32_t cnt[NB * kHistCopies];
     const uint32_t tid = threadIdx.x;
-    const uint32_t nbins = 1u << bits;
-    for (uint32_t b = 0; b < 16; ++b) cols[b][tid] = 0u;
-    wide[tid] = 0u;
+    for (uint32_t i = tid; i < NB * kHistCopies; i += kHistThreads) cnt[i] = 0u;
     __syncthreads();
 
-    const uint64_t units = (n + 31u) >> 5;
-    const uint32_t mask = nbins - 1u;
-    uint32_t c1 = 0u, c2 = 0u, c3 = 0u, seen = 0u;   // registers for the 1- and 2-bit paths
-    for (uint64_t u = (uint64_t)blockIdx.x * kHistBlock + tid; u < units;
-         u += (uint64_t)gridDim.x * kHistBlock) {
-        const uint32_t valid = (u + 1u == units) ? (uint32_t)(n - (u << 5)) : 32u;
-        const uint32_t* p = words + u * bits;
-        if (bits == 1u) {
-            uint32_t w = p[0];
-            if (valid < 32u) w &= (1u << valid) - 1u;
-            c1 += __builtin_popcount(w);
-            seen += valid;
-        } else if (bits == 2u) {
+    const uint32_t copy = tid & (kHistCopies - 1u);
+    const uint64_t units = n >> 5;                  // whole units; the last n mod 32 codes below
+    const uint64_t stride = (uint64_t)gridDim.x * kHistThreads;
+    uint64_t u = (uint64_t)blockIdx.x * kHistThreads + tid;
+    uint32_t w[BITS], ahead[BITS];
+    if (u < units) load_unit<BITS>(words, u, w);
+    while (u < units) {
+        const uint64_t un = u + stride;
+        if (un < units) load_unit<BITS>(words, un, ahead);
 #pragma unroll
-            for (uint32_t j = 0; j < 2; ++j) {
-                const uint32_t have = valid > 16u * j ? (valid - 16u * j < 16u ? valid - 16u * j : 16u) : 0u;
-                uint32_t w = have ? p[j] : 0u;
-                uint32_t field = have == 16u ? 0x55555555u : ((1u << (2u * have)) - 1u) & 0x55555555u;
-                const uint32_t lo = w & field, hi = (w >> 1) & field;
-                c1 += __builtin_popcount(lo & ~hi);
-                c2 += __builtin_popcount(hi & ~lo);
-                c3 += __builtin_popcount(lo & hi);
-                seen += have;
-            }
-        } else {
-            uint64_t buf = 0u;
-            uint32_t have = 0u, next = 0u;
-            for (uint32_t j = 0; j < valid; ++j) {
-                if (have < bits) {
-                    buf |= (uint64_t)p[next++] << have;
-                    have += 32u;
-                }
-                const uint32_t code = (uint32_t)buf & mask;
-                buf >>= bits;
-                have -= bits;
-                if (bits <= 4u) cols[code][tid] += 1u;      // private column: no race
-                else atomicAdd(&wide[code], 1u);
-            }
+        for (int j = 0; j < 32; ++j) {
+            const int bit = j * BITS, k = bit >> 5, sh = bit & 31;
+            uint32_t code = w[k] >> sh;
+            if (sh + BITS > 32) code |= w[k + 1] << (32 - sh);
+            atomicAdd(&cnt[(code & MASK) * kHistCopies + copy], 1u);     // result unused: a plain LDS add
         }
+#pragma unroll
+        for (int k = 0; k < BITS; ++k) w[k] = ahead[k];
+        u = un;
     }
-    if (bits == 1u) {
-        cols[1][tid] = c1; cols[0][tid] = seen - c1;
-    } else if (bits == 2u) {
-        cols[1][tid] = c1; cols[2][tid] = c2; cols[3][tid] = c3; cols[0][tid] = seen - c1 - c2 - c3;
+    const uint32_t rest = (uint32_t)(n & 31u);
+    if (blockIdx.x == 0 && tid < rest) {
+        // one code per thread; a code that crosses into the next word is a valid code,
+        // so that word lies inside the stream
+        const uint64_t bit = ((units << 5) + tid) * BITS;
+        const uint64_t k = bit >> 5;
+        const uint32_t sh = (uint32_t)(bit & 31u);
+        uint32_t code = words[k] >> sh;
+        if (sh + BITS > 32u) code |= words[k + 1] << (32u - sh);
+        atomicAdd(&cnt[(code & MASK) * kHistCopies + copy], 1u);
     }
     __syncthreads();
-    if (bits <= 4u) {
-        // 16 threads per bin add up the bin's 256 columns, then one atomic per bin and block
-        const uint32_t bin = tid >> 4, part = tid & 15u;
-        uint32_t sum = 0u;
-        for (uint32_t k = 0; k < kHistBlock / 16; ++k) sum += cols[bin][part * (kHistBlock / 16) + k];
-#pragma unroll
-        for (int sft = 8; sft >= 1; sft >>= 1) sum += __shfl_xor(sum, sft, 16);
-        if (part == 0u && bin < nbins && sum) atomicAdd(hist + bin, (unsigned long long)sum);
-    } else if (tid < nbins && wide[tid]) {
-        atomicAdd(hist + tid, (unsigned long long)wide[tid]);
+    for (uint32_t b = tid; b < NB; b += kHistThreads) {
+        unsigned long long sum = 0u;
+        for (uint32_t c = 0; c < kHistCopies; ++c) sum += cnt[b * kHistCopies + ((c + b) & (kHistCopies - 1u))];
+        if (sum) atomicAdd(hist + b, sum);
     }
 }
 
@@ -415,11 +418,21 @@ int ndq_code_entropy(const void* codes, size_t n, uint32_t bits, uint64_t* hist_
                            (const uint4*)codes, (uint64_t)n, bits, (unsigned long long*)hist_out);
         if (launched() != NDQ_OK) return NDQ_ELAUNCH;
     } else if (n != 0) {
-        const uint64_t units = (n + 31u) >> 5;
-        uint64_t blocks = (units + kHistBlock - 1) / kHistBlock;
-        if (blocks > 4096u) blocks = 4096u;
-        hipLaunchKernelGGL(histogram_kernel, dim3((uint32_t)blocks), dim3(kHistBlock), 0, s,
-                           (const uint32_t*)codes, (uint64_t)n, bits, (unsigned long long*)hist_out);
+        const uint64_t units = (uint64_t)n >> 5;
+        uint64_t blocks = (units + kHistThreads - 1) / kHistThreads;
+        if (blocks > kHistBlocks) blocks = kHistBlocks;
+        if (blocks == 0u) blocks = 1u;
+        const dim3 grid((uint32_t)blocks), block(kHistThreads);
+        const uint32_t* words = (const uint32_t*)codes;
+        unsigned long long* h = (unsigned long long*)hist_out;
+        switch (bits) {
+        case 3: hipLaunchKernelGGL(histogram_kernel<3>, grid, block, 0, s, words, (uint64_t)n, h); break;
+        case 4: hipLaunchKernelGGL(histogram_kernel<4>, grid, block, 0, s, words, (uint64_t)n, h); break;
+        case 5: hipLaunchKernelGGL(histogram_kernel<5>, grid, block, 0, s, words, (uint64_t)n, h); break;
+        case 6: hipLaunchKernelGGL(histogram_kernel<6>, grid, block, 0, s, words, (uint64_t)n, h); break;
+        case 7: hipLaunchKernelGGL(histogram_kernel<7>, grid, block, 0, s, words, (uint64_t)n, h); break;
+        default: hipLaunchKernelGGL(histogram_kernel<8>, grid, block, 0, s, words, (uint64_t)n, h); break;
+        }
         if (launched() != NDQ_OK) return NDQ_ELAUNCH;
     }
     const int derive_bin0 = n != 0 && bits <= 2u;
