@@ -872,6 +872,39 @@ def test_chain_with_shrinkage_and_parameter_selection():
     assert np.array_equal(out.cpu().numpy(), oracle.aggregate([S], 0.25))
 
 
+def test_nesting_ratio_chosen_from_the_device_estimate_keeps_decode_errors_under_the_target():
+    """Thm 4 end to end on the device: sigma_z^2 from ndq_sqdiff, the smallest
+    nesting ratio whose bound meets the target, then nested encode and decode with
+    the other worker's gradient as side information.  The fraction of elements whose
+    coarse bin is resolved wrongly stays under the target; right ones are within half
+    a fine step of the input and wrong ones off by multiples of M steps."""
+    n, delta, target = 1 << 22, 0.002, 1e-3
+    rng = np.random.default_rng(2024)
+    common = (rng.standard_normal(n) * 0.02).astype(F)
+    g = (common + rng.standard_normal(n) * 0.003).astype(F)
+    y_d, g_d = _to_dev(common), _to_dev(g)
+    var_z = float(ndq.ndq_sqdiff(g_d, y_d).item()) / n
+    assert abs(var_z - 9e-6) < 2e-7
+    M = ndq.ndq_nesting_ratio_for_error(delta, 1.0, var_z, target)
+    assert 2 < M <= 256
+    assert ndq.ndq_decode_error_bound(delta, M, 1.0, var_z) <= target
+    assert ndq.ndq_decode_error_bound(delta, M - 1, 1.0, var_z) > target
+    d = ndq.ndq_dither(5, 1, 1, 0)
+    rates = {}
+    for ratio in (M, max(2, M // 16)):
+        codes, steps = ndq.ndq_nested_encode(g_d, delta, 16, ratio, 1.0, 0, d)
+        out = torch.empty(n, dtype=torch.float32, device=y_d.device)
+        ndq.ndq_nested_decode(codes, n, ratio, 1.0, 0, steps, d, y_d, 1.0, out, False)
+        err = (out.double() - g_d.double()).abs().cpu().numpy() / delta
+        wrong = err > 0.75
+        assert np.all(err[~wrong] <= 0.5 + 1e-3)
+        off = err[wrong] / ratio
+        assert np.all(np.abs(off - np.rint(off)) <= 0.5 / ratio + 1e-3) and np.all(np.rint(off) >= 1)
+        rates[ratio] = wrong.mean()
+    assert rates[M] <= target
+    assert rates[max(2, M // 16)] > rates[M]          # a much smaller ratio does fail visibly
+
+
 @pytest.mark.parametrize("n", [0, 1, 3, 4, 5, 1023, 262144, 1000003])
 def test_sqdiff_matches_oracle(n):
     rng = np.random.default_rng(n)
