@@ -283,6 +283,37 @@ def test_bucketed_steps_are_two_kappa_over_levels_minus_one():
     assert np.all(np.abs(ghat - g)[interior] <= st[interior] * (0.5 + 2.0 ** -18))
 
 
+def test_partitioning_lowers_the_excess_variance_as_sec_3_1_says():
+    """Sec. 3.1, Lemma 2's proof and the partitioned bound after it: given g, the
+    quantization adds E||g~ - g||^2 = sum over sub-vectors of (their length) *
+    kappa_b^2 * Delta^2 / 12 (Delta the normalised step 2/(L-1)); for Gaussian
+    gradient noise this is at most Delta^2/6 * (2 ln(sqrt2 n/K) n sigma^2 +
+    n |mu|_inf^2), and it shrinks as the number K of sub-vectors grows."""
+    rng = np.random.default_rng(31)
+    n, levels, sigma = 1 << 16, 5, 0.01
+    mu = (0.004 * np.sin(np.arange(n) / 700.0)).astype(np.float64)
+    g = (mu + sigma * rng.standard_normal(n)).astype(F)
+    dn = 2.0 / (levels - 1)
+    measured = []
+    for K in (1, 16, 256):
+        bucket = 0 if K == 1 else n // K
+        excess = 0.0
+        draws = 6
+        for t in range(draws):
+            d = oracle.dither(3, t, 0)
+            codes, steps = oracle.dq_encode(g, 0.0, levels, bucket, d)
+            ghat = oracle.dq_decode(codes, n, levels, bucket, steps, d)
+            excess += float(np.sum((ghat.astype(np.float64) - g.astype(np.float64)) ** 2)) / draws
+        kappa = oracle.absmax(g, bucket).astype(np.float64)
+        exact = float(np.sum(kappa ** 2)) * (n // K) * dn ** 2 / 12.0
+        assert abs(excess - exact) <= 0.02 * exact, (K, excess, exact)
+        bound = dn ** 2 / 6.0 * (2.0 * math.log(math.sqrt(2.0) * n / K) * n * sigma ** 2
+                                 + n * float(np.abs(mu).max()) ** 2)
+        assert excess <= bound, (K, excess, bound)
+        measured.append(excess)
+    assert measured[0] > measured[1] > measured[2]
+
+
 def test_vanishing_bucket_is_sent_as_zero():
     assert oracle.step_from_kappa(F(1e-38), 4) == 0
     assert oracle.step_from_kappa(F(0), 4) == 0
