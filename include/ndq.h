@@ -229,7 +229,9 @@ int ndq_dense_unpack(const void* dense, size_t n, uint32_t levels, void* codes_o
 /* Histogram and empirical entropy of a packed code stream (Sec. 4: the bits left
  * after entropy coding are reported through the entropy of the transmitted
  * indices).  hist_out: 2^bits uint64 (device, 8-byte aligned), hist_out[c] = number
- * of the n codes equal to c; padding bits are not counted.  entropy_out: one
+ * of the n codes equal to c.  codes: the ndq_packed_bytes(n, bits) bytes of the
+ * stream (device, 16-byte aligned; all of them may be read); what the padding
+ * holds is not counted and need not be zero.  entropy_out: one
  * double (device) = -sum_c p_c log2 p_c in bits per code, p_c = hist_out[c]/n
  * (0 when n == 0); may be NULL to get the histogram only.  bits in [1,8].
  * Unlike the other calls this one also runs for n == 0 (it clears its outputs). */
