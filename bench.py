@@ -330,6 +330,16 @@ def main():
         extra("code_entropy_b%d" % b0, lambda: ndq.ndq_code_entropy(bufs.codes[0], n, b0, hist, ent),
               pk0, "histogram + entropy of worker 0's index stream")
         entropy0 = float(ent.item())
+        # bits per gradient element that each worker sends (Sec. 4, the kind of number in
+        # Table 2, here on the synthetic workload): fixed-width codes, and what an ideal
+        # entropy coder would leave of them; both with the 32-bit step of every bucket
+        sent = []
+        for w, (kind_w, arg_w) in enumerate(wl.plan):
+            b_w = ndq.ndq_code_bits(arg_w)
+            hist_w = torch.empty(1 << b_w, dtype=torch.int64, device="cuda")
+            ndq.ndq_code_entropy(bufs.codes[w], n, b_w, hist_w, ent)
+            sent.append({"worker": w, "kind": kind_w, "fixed_width_bits": round(b_w + 32.0 * K / n, 4),
+                         "entropy_bits": round(float(ent.item()) + 32.0 * K / n, 4)})
         lv = 3
         c3, s3 = ndq.ndq_dq_encode(dev[0], 0.0, lv, wl.bucket, ds[0])
         dense = torch.empty(ndq.ndq_dense_bytes(n, lv), dtype=torch.uint8, device="cuda")
@@ -361,6 +371,10 @@ def main():
               "mean of four separately decoded gradients")
         del parts
         extras.append({"index_entropy_bits_worker0": round(entropy0, 4), "fixed_width_bits": b0})
+        extras.append({"bits_per_element_sent": sent,
+                       "mean_fixed_width_bits": round(sum(x["fixed_width_bits"] for x in sent) / wl.W, 4),
+                       "mean_entropy_bits": round(sum(x["entropy_bits"] for x in sent) / wl.W, 4),
+                       "uncompressed_bits": 32})
         del scratch, other_f32
 
     # ---- practical memory roof: a plain copy (ndq_aggregate, one input, scale 1) ----
