@@ -177,6 +177,20 @@ size_t ndq_sqdiff_workspace(void);
 int ndq_sqdiff(const float* a, const float* b, size_t n, double* workspace, double* out,
                void* stream);
 
+/* ndq_sqdiff for callers that cannot allocate device memory (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): the same
+ * kernels, arguments, result bits and errors, but the partial sums live in
+ * ndq_sqdiff_workspace() = 8192 bytes of device memory that the library itself
+ * holds in a static array, on every GPU it runs on, until the process ends.  The
+ * call allocates and frees nothing.  n >= 2^40 is refused with NDQ_EUNSUPPORTED
+ * (the fixed grid and the array are sized for vectors below that).  The first
+ * call on a device looks up the array's address on that device (no allocation;
+ * make that call outside a graph capture); NDQ_ELAUNCH if the runtime refuses.
+ * All calls on one GPU share the array -- every call overwrites all of it before
+ * reading it, so nothing needs clearing, but two calls that overlap in time on
+ * one GPU (different streams) race; calls on one stream are safe. */
+int ndq_sqdiff_static(const float* a, const float* b, size_t n, double* out, void* stream);
+
 /* Server side of Algorithm 1, last step: out_i = scale * sum_w gs[w][i], summed
  * in ascending w.  gs: HOST array of W device pointers (1 <= W <= 1024), each n
  * floats; out may be one of the inputs only if W <= 32. */

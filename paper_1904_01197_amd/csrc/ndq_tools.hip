@@ -5,6 +5,8 @@
 
 #include <math.h>
 
+#include <mutex>
+
 #include "ndq.h"
 #include "ndq_device.hpp"
 #include "ndq_host.hpp"
@@ -383,6 +385,47 @@ __global__ __launch_bounds__(256) void sqdiff_final_kernel(const double* partial
     if (threadIdx.x == 0) out[0] = total;
 }
 
+// Partial sums of ndq_sqdiff_static: one per workgroup of the first pass, in
+// memory the library owns (8 KB on every GPU it runs on, until the process ends).
+// In host code this name is only a handle for hipGetSymbolAddress; the kernels get
+// the per-device address kept in g_scratch_ptr.
+static __device__ __align__(256) double scratch[kSqBlocks];
+
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mutex;
+static double* g_scratch_ptr[kMaxDevices];   // address of `scratch` on each device, looked up once
+
+// Address of `scratch` on the current device (null: the runtime refused).
+static double* scratch_on_current_device()
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+        g_scratch_ptr[dev] = (double*)p;
+    }
+    return g_scratch_ptr[dev];
+}
+
+// Argument checks and the two launches shared by ndq_sqdiff and ndq_sqdiff_static.
+static int sqdiff_common(const float* a, const float* b, size_t n, double* partial, double* out,
+                         void* stream)
+{
+    if (!out) return NDQ_EINVAL;
+    if (n != 0 && (!a || !b)) return NDQ_EINVAL;
+    if (n >= kMaxN) return NDQ_EUNSUPPORTED;
+    if (((uintptr_t)partial & 7u) || ((uintptr_t)out & 7u)) return NDQ_EALIGN;
+    if (n != 0 && (!aligned16(a) || !aligned16(b))) return NDQ_EALIGN;
+    hipStream_t s = (hipStream_t)stream;
+    hipLaunchKernelGGL(sqdiff_partial_kernel, dim3(kSqBlocks), dim3(256), 0, s, a, b, (uint64_t)n,
+                       partial);
+    if (launched() != NDQ_OK) return NDQ_ELAUNCH;
+    hipLaunchKernelGGL(sqdiff_final_kernel, dim3(1), dim3(256), 0, s, (const double*)partial, out);
+    return launched();
+}
+
 }  // namespace ndq
 
 extern "C" {
@@ -535,18 +578,16 @@ size_t ndq_sqdiff_workspace(void) { return ndq::kSqBlocks * sizeof(double); }
 int ndq_sqdiff(const float* a, const float* b, size_t n, double* workspace, double* out,
                void* stream)
 {
-    using namespace ndq;
-    if (!workspace || !out) return NDQ_EINVAL;
-    if (n != 0 && (!a || !b)) return NDQ_EINVAL;
-    if (n >= kMaxN) return NDQ_EUNSUPPORTED;
-    if (((uintptr_t)workspace & 7u) || ((uintptr_t)out & 7u)) return NDQ_EALIGN;
-    if (n != 0 && (!aligned16(a) || !aligned16(b))) return NDQ_EALIGN;
-    hipStream_t s = (hipStream_t)stream;
-    hipLaunchKernelGGL(sqdiff_partial_kernel, dim3(kSqBlocks), dim3(256), 0, s, a, b, (uint64_t)n,
-                       workspace);
-    if (launched() != NDQ_OK) return NDQ_ELAUNCH;
-    hipLaunchKernelGGL(sqdiff_final_kernel, dim3(1), dim3(256), 0, s, (const double*)workspace, out);
-    return launched();
+    if (!workspace) return NDQ_EINVAL;
+    return ndq::sqdiff_common(a, b, n, workspace, out, stream);
+}
+
+int ndq_sqdiff_static(const float* a, const float* b, size_t n, double* out, void* stream)
+{
+    if (n >= ndq::kMaxN) return NDQ_EUNSUPPORTED;   // beyond what the fixed grid is sized for
+    double* partial = ndq::scratch_on_current_device();
+    if (!partial) return NDQ_ELAUNCH;
+    return ndq::sqdiff_common(a, b, n, partial, out, stream);
 }
 
 const char* ndq_strerror(int rc)

@@ -21,7 +21,8 @@ EXPORTS = ("ndq_code_bits", "ndq_packed_bytes", "ndq_num_buckets", "ndq_absmax",
            "ndq_dq_decode", "ndq_dq_decode_half", "ndq_nested_encode", "ndq_nested_decode", "ndq_aggregate",
            "ndq_decode_chain", "ndq_code_entropy", "ndq_dense_group", "ndq_dense_bytes",
            "ndq_dense_pack", "ndq_dense_unpack", "ndq_alpha_for_equal_variance",
-           "ndq_decode_error_bound", "ndq_nesting_ratio_for_error", "ndq_sqdiff_workspace", "ndq_sqdiff", "ndq_strerror")
+           "ndq_decode_error_bound", "ndq_nesting_ratio_for_error", "ndq_sqdiff_workspace", "ndq_sqdiff", "ndq_sqdiff_static",
+           "ndq_strerror")
 
 
 class ndq_dither(C.Structure):
@@ -84,6 +85,7 @@ def lib():
         L.ndq_nesting_ratio_for_error.restype = u32
         L.ndq_sqdiff_workspace.argtypes, L.ndq_sqdiff_workspace.restype = [], sz
         L.ndq_sqdiff.argtypes, L.ndq_sqdiff.restype = [vp, vp, sz, vp, vp, vp], ci
+        L.ndq_sqdiff_static.argtypes, L.ndq_sqdiff_static.restype = [vp, vp, sz, vp, vp], ci
         L.ndq_dense_group.argtypes, L.ndq_dense_group.restype = [u32], u32
         L.ndq_dense_bytes.argtypes, L.ndq_dense_bytes.restype = [sz, u32], sz
         L.ndq_dense_pack.argtypes, L.ndq_dense_pack.restype = [vp, sz, u32, vp, vp], ci
@@ -316,4 +318,16 @@ def ndq_sqdiff(a, b, workspace=None, out=None):
         out = torch.empty(1, dtype=torch.float64, device=a.device)
     _check(lib().ndq_sqdiff(_dev(a, "a"), _dev(b, "b"), a.numel(), _dev(workspace, "workspace"),
                             _dev(out, "out"), _stream()), "ndq_sqdiff")
+    return out
+
+
+def ndq_sqdiff_static(a, b, out):
+    """ndq_sqdiff with the library's own static partial-sum array: allocates nothing,
+    so `out` (1-element float64 tensor) must be passed in."""
+    if a.dtype != torch.float32 or b.dtype != torch.float32 or a.numel() != b.numel():
+        raise ValueError("a and b must be float32 of equal length")
+    if out.dtype != torch.float64 or out.numel() < 1:
+        raise ValueError("out must hold one float64")
+    _check(lib().ndq_sqdiff_static(_dev(a, "a"), _dev(b, "b"), a.numel(), _dev(out, "out"),
+                                   _stream()), "ndq_sqdiff_static")
     return out
