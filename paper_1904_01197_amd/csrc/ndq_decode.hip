@@ -183,6 +183,7 @@ struct ChainArgs {
     float scale;
     uint32_t row_buckets; // 1: a bucket is one row of a tile (tiling is by tile, a step per row)
     uint32_t num_buckets; // with row_buckets: steps per worker (rows past them decode with step 0)
+    uint32_t tile_begin;  // chain_kernel: first tile of this launch; chain_stream_kernel: tiles it owns
 };
 
 // What is prefetched per worker: the step and, per row, the words holding the
@@ -423,10 +424,171 @@ void chain_kernel(ChainArgs a)
 {
     const int lane = threadIdx.x & (kWave - 1);
     const uint32_t tile_id =
-        blockIdx.x * kWavesPerBlock + __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+        a.tile_begin + blockIdx.x * kWavesPerBlock + __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     const TileRef t = locate_tile(a.tl, tile_id, kChainTile);
     if (t.len == kChainTile) chain_tile<true, ROWB, ANYM>(a, t, lane);
     else if (t.len != 0) chain_tile<false, ROWB, ANYM>(a, t, lane);
+}
+
+// ---------------------------------------------------------------------------
+// Streaming chain decoder for the common plans: a first DQSG worker, then
+// workers that are all alike -- all DQSG, or all nested with a power-of-two
+// nesting ratio and no shrinkage -- with code widths of 1, 2 or 4 bits, and a
+// vector cut into whole tiles.  One instantiation of the fold serves every
+// worker after the first, so the sixteen running sums of a lane stay in the same
+// registers from the first worker to the store (the general kernel dispatches on
+// mode and width after every worker and moves them around each time).  Waves are
+// persistent: a wave walks over tiles wave, wave + W, ... and fetches the next
+// worker's, and at the end the next tile's, code words while it folds the
+// current worker in.
+//
+// Arithmetic per element of a nested worker, bit for bit that of chain_row with
+// kNestedPow2 (every scaling below is by a power of two, which commutes with
+// rounding; k and m/M + k are exact or rounded exactly like m + M k):
+//   m' = m / M (from the packed field, exact)      y = S * side_scale
+//   c  = fma(y, 1/Delta, v)                        k = rint(fma(c, 1/M, -m'))
+//   q' = k + m'                                    S = S + Delta * fma(q', M, -v)
+// ---------------------------------------------------------------------------
+#ifndef NDQ_CHAIN_STREAM_WAVES
+#define NDQ_CHAIN_STREAM_WAVES 6
+#endif
+constexpr int kChainStreamWaves = NDQ_CHAIN_STREAM_WAVES;
+
+// per-worker parameters as the kernel reads them: through the constant address
+// space, indexed by the loop variable (scalar loads, no copy of the arguments)
+typedef const __attribute__((address_space(4))) ChainArgs* ChainArgsPtr;
+
+struct ChainCodes { uint32_t w[kChainRows]; float step; };
+
+// a lane's eight codes of a row: `WIDTH` bytes at a multiple of WIDTH (full tiles)
+template <int WIDTH>
+__device__ __forceinline__ void stream_fetch(const unsigned char* codes, const float* steps, uint64_t start,
+                                             uint32_t bucket, int lane, ChainCodes& f)
+{
+    const unsigned char* mine = codes + (start >> 3) * WIDTH + (uint32_t)lane * WIDTH;
+#pragma unroll
+    for (int r = 0; r < kChainRows; ++r) {
+        const unsigned char* p = mine + (uint32_t)(r * kWave) * WIDTH;
+        f.w[r] = WIDTH == 1 ? (uint32_t)*p : WIDTH == 2 ? (uint32_t)*(const uint16_t*)p : *(const uint32_t*)p;
+    }
+    f.step = steps[bucket];
+}
+
+template <int MODE, int WIDTH, bool FIRST>
+__device__ __forceinline__ void stream_fold(const DitherStream& ds, uint64_t block0, float q_min_f,
+                                            float side_scale, const ChainCodes& f, int lane,
+                                            float (&S)[kChainRows][8])
+{
+    constexpr int NF = WIDTH == 4 ? 4 : 8;
+    // a power-of-two nesting ratio is 2^(code width): M and 1/M are compile-time constants
+    constexpr float M_f = (float)(1u << WIDTH), inv_M_f = 1.0f / M_f;
+    // DQSG: the index q = c + q_min; nested: m' = c / M (scale and offset divided by M)
+    FieldAsFloat<NF> field((uint32_t)WIDTH, MODE == kDq ? q_min_f : 0.0f);
+    if (MODE != kDq) {
+#pragma unroll
+        for (int j = 0; j < NF; ++j) { field.scale[j] *= inv_M_f; field.offset[j] *= inv_M_f; }
+    }
+    const float step = f.step, inv = inv_step(step);
+#pragma unroll
+    for (int r = 0; r < kChainRows; ++r) {
+        const uint32_t o = (uint32_t)(r * kWave + lane) * kLaneElems;
+        float v[8];
+        dither8(ds, block0 + (o >> 3), v);
+        const uint32_t lo = f.w[r], hi = WIDTH == 4 ? f.w[r] >> 16 : f.w[r];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const float c_f = NF == 8 ? field.get(lo, k) : field.get(k < 4 ? lo : hi, k & 3);
+            float val;
+            if (MODE == kDq) {
+                val = index_value(c_f, step, v[k]);
+            } else {
+                const float y = S[r][k] * side_scale;
+                const float c = __builtin_fmaf(y, inv, v[k]);
+                const float kk = __builtin_rintf(__builtin_fmaf(c, inv_M_f, -c_f));
+                const float qs = kk + c_f;
+                const float centred = __builtin_fmaf(qs, M_f, -v[k]);
+                val = step * centred;
+            }
+            S[r][k] = FIRST ? val : S[r][k] + val;
+        }
+    }
+}
+
+template <int RMODE, int W0, int WR>
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(kChainStreamWaves, kChainStreamWaves)))
+void chain_stream_kernel(ChainArgs a_by_value)
+{
+    const ChainArgsPtr a = (ChainArgsPtr)__builtin_amdgcn_kernarg_segment_ptr();
+    const int lane = threadIdx.x & (kWave - 1);
+    const uint32_t stride = gridDim.x * kWavesPerBlock;
+    const uint32_t first = blockIdx.x * kWavesPerBlock + __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const uint32_t tiles = a->tile_begin;                  // whole tiles: ids 0 .. tiles-1
+    const uint32_t W = a->W;
+    const uint32_t tpb = a->tl.tiles_per_bucket;
+    const bool one_bucket = a->tl.bucket_len == a->tl.n;   // bucket == 0
+    float* out_base = a->out;
+    const float scale = a->scale;
+    const bool apply_scale = __builtin_amdgcn_readfirstlane(a->apply_scale) != 0;
+    if (first >= tiles) return;
+    const uint32_t my_tiles = (tiles - first + stride - 1u) / stride;
+    uint32_t done = 0;
+    if (my_tiles > 1u) __builtin_amdgcn_s_setprio(3);
+
+    ChainCodes cur;
+    stream_fetch<W0>(a->w[0].codes, a->w[0].steps, (uint64_t)first * kChainTile, one_bucket ? 0u : first / tpb, lane, cur);
+    for (uint32_t tile = first; tile < tiles; tile += stride) {
+        const uint64_t start = (uint64_t)tile * kChainTile;
+        const uint32_t bucket = one_bucket ? 0u : tile / tpb;
+        float S[kChainRows][8];
+        ChainCodes nxt;
+        // first worker: DQSG, starts the sum; meanwhile the second worker's codes (or the next tile's)
+        if (W > 1u) {
+            stream_fetch<WR>(a->w[1].codes, a->w[1].steps, start, bucket, lane, nxt);
+        } else {
+            const uint32_t nt = tile + stride < tiles ? tile + stride : tile;
+            ChainCodes tmp;
+            stream_fetch<W0>(a->w[0].codes, a->w[0].steps, (uint64_t)nt * kChainTile, one_bucket ? 0u : nt / tpb, lane, tmp);
+            nxt = tmp;
+        }
+        {
+            const DitherStream ds = {a->w[0].ds.key0, a->w[0].ds.key1, a->w[0].ds.step, a->w[0].ds.worker};
+            stream_fold<kDq, W0, true>(ds, (a->w[0].index0 + start) >> 3, (float)a->w[0].q_min, 0.0f, cur, lane, S);
+        }
+        cur = nxt;
+        for (uint32_t w = 1; w < W; ++w) {
+            // the codes of worker w are in `cur`; fetch worker w+1's, or the first worker's of the next tile
+            if (w + 1u < W) {
+                stream_fetch<WR>(a->w[w + 1u].codes, a->w[w + 1u].steps, start, bucket, lane, nxt);
+            } else {
+                const uint32_t nt = tile + stride < tiles ? tile + stride : tile;
+                ChainCodes tmp;
+                stream_fetch<W0>(a->w[0].codes, a->w[0].steps, (uint64_t)nt * kChainTile, one_bucket ? 0u : nt / tpb, lane, tmp);
+                nxt = tmp;
+            }
+            const DitherStream ds = {a->w[w].ds.key0, a->w[w].ds.key1, a->w[w].ds.step, a->w[w].ds.worker};
+            stream_fold<RMODE, WR, false>(ds, (a->w[w].index0 + start) >> 3, (float)a->w[w].q_min,
+                                          a->w[w].side_scale, cur, lane, S);
+            cur = nxt;
+        }
+        float* out = out_base + start;
+#pragma unroll
+        for (int r = 0; r < kChainRows; ++r) {
+            const uint32_t o = (uint32_t)(r * kWave + lane) * kLaneElems;
+            if (apply_scale) {       // wave-uniform
+#pragma unroll
+                for (int k = 0; k < 8; ++k) S[r][k] = scale * S[r][k];
+            }
+            store_streaming(out + o, S[r][0], S[r][1], S[r][2], S[r][3]);
+            store_streaming(out + o + 4, S[r][4], S[r][5], S[r][6], S[r][7]);
+        }
+        // the arbiter serves the oldest wave of a SIMD first: lower a wave's priority as it
+        // gets ahead, so that the waves of a SIMD finish together
+        ++done;
+        const uint32_t quarter = my_tiles > 1u ? 4u * done / my_tiles : 0u;
+        if (quarter == 1u) __builtin_amdgcn_s_setprio(2);
+        else if (quarter == 2u) __builtin_amdgcn_s_setprio(1);
+        else if (quarter >= 3u) __builtin_amdgcn_s_setprio(0);
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -539,6 +701,65 @@ static int decode_common(const void* codes, size_t n, uint32_t levels, uint32_t 
     if (is_pow2(M) && alpha == 1.0f) return run_decode<kNestedPow2>(a, n, bucket, acc, s);
     if (is_pow2(M)) return run_decode<kNestedPow2Shrink>(a, n, bucket, acc, s);
     return run_decode<kNestedAnyM>(a, n, bucket, acc, s);
+}
+
+template <int RMODE, int W0, int WR>
+static int launch_chain_stream(const ChainArgs& a, hipStream_t s)
+{
+    // Long vectors: persistent waves, kChainStreamWaves on every SIMD, every wave with the same
+    // number of tiles (give or take one).  Otherwise one tile per wave: with only a few tiles
+    // per wave a fixed share would leave SIMDs idle at the end.
+    const uint32_t tiles = a.tile_begin, slots = 1024u * kChainStreamWaves;
+    const uint32_t blocks = tiles >= stream_tuning().chain_min_tiles_per_wave * slots ? persistent_blocks(tiles, slots)
+                                                                                       : blocks_for(tiles);
+    hipLaunchKernelGGL((chain_stream_kernel<RMODE, W0, WR>), dim3(blocks), dim3(kBlock), 0, s, a);
+    return launched();
+}
+
+template <int RMODE, int W0>
+static int launch_chain_stream_w(const ChainArgs& a, uint32_t wr, hipStream_t s)
+{
+    if (wr == 1u) return launch_chain_stream<RMODE, W0, 1>(a, s);
+    if (wr == 2u) return launch_chain_stream<RMODE, W0, 2>(a, s);
+    return launch_chain_stream<RMODE, W0, 4>(a, s);
+}
+
+// Runs the streaming kernel when the plan and the tiling allow it (then the ragged
+// last tile, if any, goes to the general kernel); returns 1 when it does not apply.
+static int try_chain_stream(ChainArgs a, uint32_t bucket, hipStream_t s)
+{
+    if (a.row_buckets || a.continue_sum) return 1;
+    if (!(bucket == 0u || bucket % kChainTile == 0u)) return 1;
+    const uint32_t w0 = a.w[0].bits;
+    if (a.w[0].mode != kDq || !(w0 == 1u || w0 == 2u || w0 == 4u)) return 1;
+    uint32_t rmode = kDq, wr = w0;
+    if (a.W > 1u) {
+        rmode = a.w[1].mode;
+        wr = a.w[1].bits;
+        if (rmode != kDq && rmode != kNestedPow2) return 1;
+        if (!(wr == 1u || wr == 2u || wr == 4u)) return 1;
+        for (uint32_t j = 2; j < a.W; ++j)
+            if (a.w[j].mode != rmode || a.w[j].bits != wr) return 1;
+    }
+    const uint32_t full = (uint32_t)(a.tl.n / kChainTile);
+    if (full == 0u) return 1;
+    ChainArgs b = a;
+    b.tile_begin = full;
+    int rc;
+    if (rmode == kDq) {
+        rc = w0 == 1u ? launch_chain_stream_w<kDq, 1>(b, wr, s) : w0 == 2u ? launch_chain_stream_w<kDq, 2>(b, wr, s)
+                                                                            : launch_chain_stream_w<kDq, 4>(b, wr, s);
+    } else {
+        rc = w0 == 1u ? launch_chain_stream_w<kNestedPow2, 1>(b, wr, s)
+                      : w0 == 2u ? launch_chain_stream_w<kNestedPow2, 2>(b, wr, s)
+                                 : launch_chain_stream_w<kNestedPow2, 4>(b, wr, s);
+    }
+    if (rc != NDQ_OK) return rc;
+    if ((uint64_t)full * kChainTile < a.tl.n) {              // ragged last tile
+        hipLaunchKernelGGL((chain_kernel<false, false>), dim3(1), dim3(kBlock), 0, s, b);
+        return launched();
+    }
+    return NDQ_OK;
 }
 
 }  // namespace ndq
@@ -662,8 +883,15 @@ int ndq_decode_chain(const ndq_worker* workers, uint32_t W, size_t n, uint32_t b
         }
         bool any_m = false;
         for (uint32_t j = 0; j < a.W; ++j) any_m = any_m || a.w[j].mode == kNestedAnyM;
-        const dim3 grid(blocks_for(a.tl.total_tiles)), block(kBlock);
         hipStream_t hs = (hipStream_t)stream;
+        a.tile_begin = 0u;
+#ifndef NDQ_NO_STREAM_CHAIN
+        if (W <= kChainMax) {
+            const int rc_stream = try_chain_stream(a, bucket, hs);
+            if (rc_stream != 1) return rc_stream;
+        }
+#endif
+        const dim3 grid(blocks_for(a.tl.total_tiles)), block(kBlock);
         if (a.row_buckets && any_m) hipLaunchKernelGGL((chain_kernel<true, true>), grid, block, 0, hs, a);
         else if (a.row_buckets) hipLaunchKernelGGL((chain_kernel<true, false>), grid, block, 0, hs, a);
         else if (any_m) hipLaunchKernelGGL((chain_kernel<false, true>), grid, block, 0, hs, a);

@@ -75,14 +75,14 @@ __device__ __forceinline__ float tile_max(const TileRegs<DT>& regs)
 // step comes from `kappa`, the max-norm of the tile's bucket, found in registers.
 // MULTI (with FUSED): the bucket is a whole number of rows and several buckets
 // share the tile, each with its own step.
-template <int DT, int MODE, bool FUSED, bool FULL, bool MULTI>
+template <int DT, int MODE, bool FUSED, bool FULL, bool MULTI, int BITSW = 0>
 __device__ __forceinline__ void encode_tile(const EncodeArgs& a, const TileRef& t, uint32_t tile_id,
                                             const TileRegs<DT>& regs, float kappa, bool writes_step,
                                             unsigned char* stage, int lane)
 {
     using T = Elem<DT>;
     constexpr int ROWS = EncRows<DT>::R;
-    const uint32_t bits = a.qp.bits;
+    const uint32_t bits = BITSW ? (uint32_t)BITSW : a.qp.bits;   // BITSW: the code width, known at compile time
     const typename T::Row (&raw)[ROWS] = regs.row;
 
     // 1/step per row (alpha/step for a nested worker that shrinks), wave-uniform
@@ -116,10 +116,12 @@ __device__ __forceinline__ void encode_tile(const EncodeArgs& a, const TileRef& 
         float step;
         if (FUSED) {
             step = step_from_kappa(kappa, a.qp.levels);
-            if (lane == 0 && writes_step) a.steps[t.bucket] = step;
+            if (BITSW != 0 && FULL) a.steps[t.bucket] = step;     // every lane, the same value: no branch around the store
+            else if (lane == 0 && writes_step) a.steps[t.bucket] = step;
         } else if (a.preset_step > 0.0f) {
             step = a.preset_step;
-            if (tile_id == 0 && lane == 0) a.steps[0] = step;
+            // (the streaming kernel writes the preset step itself, outside its tile loop)
+            if (!(BITSW != 0 && FULL) && tile_id == 0 && lane == 0) a.steps[0] = step;
         } else {
             step = a.steps[t.bucket];
         }
@@ -264,6 +266,147 @@ void encode_kernel(EncodeArgs a)
     }
 }
 
+// Orders a wave's own LDS traffic: what its lanes wrote before is visible to all
+// of its lanes after (a wave's LDS instructions execute in order; the fences keep
+// the compiler from moving accesses across).
+__device__ __forceinline__ void wave_lds_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// Copies a tile's packed codes from the wave's stage to the stream, 8 bytes per lane.
+__device__ __forceinline__ void stage_to_stream(const EncodeArgs& a, const TileRef& t, uint32_t bits,
+                                                const unsigned char* stage, int lane)
+{
+    const uint64_t byte0 = (t.start >> 3) * bits;                 // tile start is a multiple of 64
+    const bool last = t.start + t.len == a.tl.n;
+    const uint64_t nbytes = last ? a.total_bytes - byte0 : (uint64_t)(t.len >> 3) * bits;
+    const uint32_t units = (uint32_t)(nbytes >> 3);
+    uint64_t* dst = (uint64_t*)(a.codes + byte0);
+    const uint64_t* src = (const uint64_t*)stage;
+    for (uint32_t u = lane; u < units; u += kWave) dst[u] = src[u];
+}
+
+// The same for a full tile that is not the vector's last, with the code width known
+// at compile time: a fixed number of store instructions, so that the compiler can
+// count the memory operations in flight between a tile's loads and its use.
+template <int DT, int BITSW>
+__device__ __forceinline__ void stage_to_stream_full(const EncodeArgs& a, const TileRef& t,
+                                                     const unsigned char* stage, int lane)
+{
+    constexpr uint32_t units = EncTile<DT>::N / 64u * BITSW;       // 8-byte units: 32 (binary32, 1 bit) or a multiple of 64
+    uint64_t* dst = (uint64_t*)(a.codes + (t.start >> 3) * BITSW);
+    const uint64_t* src = (const uint64_t*)stage;
+    if constexpr (units % kWave == 0u) {
+#pragma unroll
+        for (uint32_t u = 0; u < units; u += kWave) dst[u + lane] = src[u + lane];
+    } else {
+        static_assert(units < (uint32_t)kWave, "a partial store only for less than one unit per lane");
+        if ((uint32_t)lane < units) dst[lane] = src[lane];
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Streaming encoder for vectors made of whole tiles (bucket == tile with the
+// max-norm found in registers, or one step for the whole vector): every wave
+// walks over the tiles wave, wave + W, wave + 2W, ... (W = waves in the grid) and
+// keeps the NEXT tile's loads in flight in a second set of registers while it
+// quantizes the current one.  No wave is ever new: the instruction arbiter serves
+// older waves first, so in a one-tile-per-wave grid a new wave crawls through its
+// address arithmetic, its loads and its max-norm behind seven busy neighbours,
+// and the SIMD idles whenever those neighbours run out at the same time.
+// ---------------------------------------------------------------------------
+#ifndef NDQ_STREAM_WAVES
+#define NDQ_STREAM_WAVES 4
+#endif
+constexpr int kStreamWaves = NDQ_STREAM_WAVES;   // per SIMD: two tiles of registers per wave
+
+template <int DT>
+__device__ __forceinline__ TileRef stream_tile_ref(const EncodeArgs& a, uint32_t tile_id, bool fused)
+{
+    TileRef t;
+    t.start = (uint64_t)tile_id * EncTile<DT>::N;
+    t.len = EncTile<DT>::N;
+    t.bucket = fused ? tile_id : 0u;
+    return t;
+}
+
+template <int DT, int MODE, bool FUSED, int BITSW>
+__device__ __forceinline__ void stream_one(const EncodeArgs& a, uint32_t tile_id, const TileRegs<DT>& regs,
+                                           unsigned char* stage, int lane)
+{
+    const TileRef t = stream_tile_ref<DT>(a, tile_id, FUSED);
+    const float kappa = FUSED ? tile_max<DT>(regs) : 0.0f;
+    wave_lds_sync();     // the previous tile's copy-out has read the stage
+    encode_tile<DT, MODE, FUSED, true, false, BITSW>(a, t, tile_id, regs, kappa, true, stage, lane);
+    wave_lds_sync();
+    stage_to_stream_full<DT, BITSW>(a, t, stage, lane);
+}
+
+template <int DT, int MODE, bool FUSED, int BITSW>
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(kStreamWaves, kStreamWaves)))
+void encode_stream_kernel(EncodeArgs a, uint32_t full_tiles)
+{
+    constexpr uint32_t TILE = EncTile<DT>::N;
+    __shared__ __align__(16) unsigned char stage_all[kWavesPerBlock][TILE + 8];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    unsigned char* stage = stage_all[wave];
+    const uint32_t stride = gridDim.x * kWavesPerBlock;
+    const uint32_t first = blockIdx.x * kWavesPerBlock + wave;
+    if (!FUSED && a.preset_step > 0.0f && first == 0u && lane == 0) a.steps[0] = a.preset_step;
+    if (first < full_tiles) {
+        // Two register sets, ra and rb.  Every pass issues exactly eight loads before it
+        // waits for the other set, also the last one (then eight loads of the vector's
+        // first 16 bytes per row, all lanes alike: one cache line, no traffic to speak of),
+        // so that the count of loads in flight at every wait is known at compile time and
+        // a wait for the current tile never covers the prefetch.
+        TileRegs<DT> ra, rb;
+        uint32_t cur = first;
+        // The arbiter serves the oldest wave of a SIMD first, so left alone the waves of a
+        // SIMD finish one after the other and the last one runs alone, at a third of the
+        // SIMD's rate.  Lower a wave's priority as it gets ahead: they finish together.
+        const uint32_t my_tiles = (full_tiles - first + stride - 1) / stride;
+        uint32_t done = 0;
+        __builtin_amdgcn_s_setprio(3);
+#define NDQ_FAIR_STEP() do { ++done; const uint32_t q = 4u * done / my_tiles; \
+            if (q == 1u) __builtin_amdgcn_s_setprio(2); else if (q == 2u) __builtin_amdgcn_s_setprio(1); \
+            else if (q >= 3u) __builtin_amdgcn_s_setprio(0); } while (0)
+        load_tile<DT, true>(a.g, stream_tile_ref<DT>(a, cur, FUSED), lane, ra);
+        for (;;) {
+            uint32_t nxt = cur + stride;
+            bool more = nxt < full_tiles;
+            load_tile<DT, true>(a.g, stream_tile_ref<DT>(a, more ? nxt : 0u, FUSED), more ? lane : 0, rb);
+            stream_one<DT, MODE, FUSED, BITSW>(a, cur, ra, stage, lane);
+            if (!more) break;
+            NDQ_FAIR_STEP();
+            cur = nxt;
+            nxt = cur + stride;
+            more = nxt < full_tiles;
+            load_tile<DT, true>(a.g, stream_tile_ref<DT>(a, more ? nxt : 0u, FUSED), more ? lane : 0, ra);
+            stream_one<DT, MODE, FUSED, BITSW>(a, cur, rb, stage, lane);
+            if (!more) break;
+            NDQ_FAIR_STEP();
+            cur = nxt;
+        }
+    }
+    // the ragged last tile, if there is one, by the wave whose turn it would be
+    if (full_tiles < a.tl.total_tiles && full_tiles % stride == first) {
+        const TileRef t = locate_tile(a.tl, full_tiles, TILE);
+        if (t.len != 0) {
+            TileRegs<DT> regs;
+            load_tile<DT, false>(a.g, t, lane, regs);
+            const float kappa = FUSED ? tile_max<DT>(regs) : 0.0f;
+            wave_lds_sync();
+            encode_tile<DT, MODE, FUSED, false, false, BITSW>(a, t, full_tiles, regs, kappa, true, stage, lane);
+            wave_lds_sync();
+            stage_to_stream(a, t, BITSW ? (uint32_t)BITSW : a.qp.bits, stage, lane);
+        }
+    }
+}
+
 // ---------------------------------------------------------------------------
 // Max-norm per bucket (two-pass path and ndq_absmax)
 // ---------------------------------------------------------------------------
@@ -359,9 +502,58 @@ static int run_absmax(const void* g, const Tiling& tl, uint64_t K, float* kappa,
     return launched();
 }
 
-template <int DT, int MODE>
-static int run_encode(const EncodeArgs& a, bool fused, bool multi, hipStream_t s)
+// Waves of the streaming kernel: kStreamWaves on each of the 1,024 SIMDs.
+constexpr uint32_t kStreamSlots = 1024u * kStreamWaves;
+
+template <int DT, int MODE, bool FUSED, int BITSW>
+static int launch_stream(const EncodeArgs& a, uint32_t full_tiles, hipStream_t s)
 {
+    const uint32_t blocks = persistent_blocks(full_tiles, kStreamSlots);
+    hipLaunchKernelGGL((encode_stream_kernel<DT, MODE, FUSED, BITSW>), dim3(blocks), dim3(kBlock), 0, s, a, full_tiles);
+    return launched();
+}
+
+// The streaming kernel serves vectors cut into whole tiles (a ragged last one aside):
+// bucket == tile (fused max-norm) or one step for the whole vector (preset, or found by
+// the max-norm pass), in the quantizer modes and code widths of the common
+// configurations.  Returns 1 when it does not apply.
+template <int DT, int MODE>
+static int try_stream(const EncodeArgs& a, bool fused, bool multi, uint32_t bucket, hipStream_t s)
+{
+    constexpr uint32_t TILE = EncTile<DT>::N;
+    if constexpr (MODE != kDqNarrow && MODE != kNestedPow2Bounded && MODE != kNestedPow2) {
+        return 1;
+    } else {
+    if (multi || a.waves_log2 != 0u) return 1;
+    if (!(bucket == TILE || bucket == 0u)) return 1;
+    if (fused != (bucket == TILE)) return 1;
+    const uint32_t full_tiles = (uint32_t)(a.tl.n / TILE);
+    // shorter vectors: with only a few tiles per wave a fixed share leaves SIMDs idle at the end
+    if (full_tiles == 0u || full_tiles < stream_tuning().enc_min_tiles_per_wave * kStreamSlots) return 1;
+    const uint32_t bits = a.qp.bits;
+    if (bits != 1u && bits != 2u && bits != 4u) return 1;
+    if (fused) {
+        if constexpr (MODE == kNestedPow2) {
+            return 1;      // a preset step comes with bucket == 0
+        } else {
+            if (bits == 1u) return launch_stream<DT, MODE, true, 1>(a, full_tiles, s);
+            if (bits == 2u) return launch_stream<DT, MODE, true, 2>(a, full_tiles, s);
+            return launch_stream<DT, MODE, true, 4>(a, full_tiles, s);
+        }
+    }
+    if (bits == 1u) return launch_stream<DT, MODE, false, 1>(a, full_tiles, s);
+    if (bits == 2u) return launch_stream<DT, MODE, false, 2>(a, full_tiles, s);
+    return launch_stream<DT, MODE, false, 4>(a, full_tiles, s);
+    }
+}
+
+template <int DT, int MODE>
+static int run_encode(const EncodeArgs& a, bool fused, bool multi, uint32_t bucket, hipStream_t s)
+{
+#ifndef NDQ_NO_STREAM_ENCODER
+    const int rc = try_stream<DT, MODE>(a, fused, multi, bucket, s);
+    if (rc != 1) return rc;
+#endif
     const dim3 grid(blocks_for(a.tl.total_tiles)), block(kBlock);
     if (a.waves_log2 != 0u) hipLaunchKernelGGL((encode_kernel<DT, MODE, true, false, true>), grid, block, 0, s, a);
     else if (multi) hipLaunchKernelGGL((encode_kernel<DT, MODE, true, true, false>), grid, block, 0, s, a);
@@ -428,19 +620,19 @@ static int encode_common(const void* g, ndq_dtype dt, size_t n, float delta, uin
                                                                                        : kNestedAnyMBounded)
                                             : (a.preset_step > 0.0f ? kNestedPow2 : kNestedPow2Bounded));
     if (dt == NDQ_F32) {
-        if (mode == kDqNarrow) return run_encode<0, kDqNarrow>(a, fused, multi, s);
-        if (mode == kDq) return run_encode<0, kDq>(a, fused, multi, s);
-        if (mode == kNestedPow2) return run_encode<0, kNestedPow2>(a, fused, multi, s);
-        if (mode == kNestedPow2Bounded) return run_encode<0, kNestedPow2Bounded>(a, fused, multi, s);
-        if (mode == kNestedAnyMBounded) return run_encode<0, kNestedAnyMBounded>(a, fused, multi, s);
-        return run_encode<0, kNestedAnyM>(a, fused, multi, s);
+        if (mode == kDqNarrow) return run_encode<0, kDqNarrow>(a, fused, multi, bucket, s);
+        if (mode == kDq) return run_encode<0, kDq>(a, fused, multi, bucket, s);
+        if (mode == kNestedPow2) return run_encode<0, kNestedPow2>(a, fused, multi, bucket, s);
+        if (mode == kNestedPow2Bounded) return run_encode<0, kNestedPow2Bounded>(a, fused, multi, bucket, s);
+        if (mode == kNestedAnyMBounded) return run_encode<0, kNestedAnyMBounded>(a, fused, multi, bucket, s);
+        return run_encode<0, kNestedAnyM>(a, fused, multi, bucket, s);
     }
-    if (mode == kDqNarrow) return run_encode<1, kDqNarrow>(a, fused, multi, s);
-    if (mode == kDq) return run_encode<1, kDq>(a, fused, multi, s);
-    if (mode == kNestedPow2) return run_encode<1, kNestedPow2>(a, fused, multi, s);
-    if (mode == kNestedPow2Bounded) return run_encode<1, kNestedPow2Bounded>(a, fused, multi, s);
-    if (mode == kNestedAnyMBounded) return run_encode<1, kNestedAnyMBounded>(a, fused, multi, s);
-    return run_encode<1, kNestedAnyM>(a, fused, multi, s);
+    if (mode == kDqNarrow) return run_encode<1, kDqNarrow>(a, fused, multi, bucket, s);
+    if (mode == kDq) return run_encode<1, kDq>(a, fused, multi, bucket, s);
+    if (mode == kNestedPow2) return run_encode<1, kNestedPow2>(a, fused, multi, bucket, s);
+    if (mode == kNestedPow2Bounded) return run_encode<1, kNestedPow2Bounded>(a, fused, multi, bucket, s);
+    if (mode == kNestedAnyMBounded) return run_encode<1, kNestedAnyMBounded>(a, fused, multi, bucket, s);
+    return run_encode<1, kNestedAnyM>(a, fused, multi, bucket, s);
 }
 
 }  // namespace ndq

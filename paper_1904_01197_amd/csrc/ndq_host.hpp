@@ -4,6 +4,7 @@
 
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <stdlib.h>
 
 #include "ndq.h"
 #include "ndq_device.hpp"
@@ -76,5 +77,40 @@ inline DitherStream make_stream(const ndq_dither* d)
 inline int launched() { return hipGetLastError() == hipSuccess ? NDQ_OK : NDQ_ELAUNCH; }
 
 inline uint32_t blocks_for(uint32_t tiles) { return (tiles + kWavesPerBlock - 1) / kWavesPerBlock; }
+
+// When the persistent ("streaming") kernels take over from the one-tile-per-wave
+// ones: a vector needs at least `min_tiles_per_wave` tiles for every wave the
+// persistent grid would hold, or its fixed shares leave SIMDs idle at the end.
+// Two environment variables, read once per process, override the defaults; they
+// exist for tuning and so that tests can drive the persistent kernels with short
+// vectors:
+//   NDQ_STREAM_MIN_TILES_PER_WAVE   threshold for both kernels (0: always persistent)
+//   NDQ_STREAM_MAX_BLOCKS           cap on the persistent grid, in workgroups (0: none)
+struct StreamTuning {
+    uint32_t enc_min_tiles_per_wave, chain_min_tiles_per_wave, max_blocks;
+};
+
+inline const StreamTuning& stream_tuning()
+{
+    static const StreamTuning t = [] {
+        StreamTuning v = {8u, 12u, 0u};
+        if (const char* e = getenv("NDQ_STREAM_MIN_TILES_PER_WAVE")) {
+            v.enc_min_tiles_per_wave = v.chain_min_tiles_per_wave = (uint32_t)strtoul(e, nullptr, 10);
+        }
+        if (const char* e = getenv("NDQ_STREAM_MAX_BLOCKS")) v.max_blocks = (uint32_t)strtoul(e, nullptr, 10);
+        return v;
+    }();
+    return t;
+}
+
+// Grid of a persistent kernel: at most `slots` waves, every wave the same number of
+// tiles, give or take one.
+inline uint32_t persistent_blocks(uint32_t tiles, uint32_t slots)
+{
+    const uint32_t cap = stream_tuning().max_blocks;
+    if (cap != 0u && cap * kWavesPerBlock < slots) slots = cap * kWavesPerBlock;
+    const uint32_t per_wave = (tiles + slots - 1u) / slots;
+    return blocks_for((tiles + per_wave - 1u) / per_wave);
+}
 
 }  // namespace ndq
