@@ -6,7 +6,7 @@ already resident in HBM: every worker's encode (scale, dither, quantize, pack),
 then the server's decode chain with side information and running-sum
 aggregation.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 5] [--no-cpu]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 5] [--no-cpu] [--prewarm-ms T]
 """
 import argparse
 import json
@@ -33,10 +33,14 @@ def parse_args():
     ap.add_argument("--cpu-sample", type=int, default=1 << 27,
                     help="elements per worker the oracle is timed on")
     ap.add_argument("--kernel-reps", type=int, default=50)
-    ap.add_argument("--schedule", choices=["serial", "overlap", "fused"], default="fused",
-                    help="serial: one library call per worker and direction, one stream; "
-                         "overlap: the same calls, encoders and decoders on two streams; "
+    ap.add_argument("--schedule", choices=["serial", "fused"], default="fused",
+                    help="serial: one library call per worker and direction; "
                          "fused: all encodes, then the whole server loop in one call")
+    ap.add_argument("--prewarm-ms", type=float, default=300.0,
+                    help="untimed steps run for this long before the warm-up steps: the chip's clocks "
+                         "settle only some tens of milliseconds after load begins (reported as prewarm_ms)")
+    ap.add_argument("--cpu-threads", type=int, default=0,
+                    help="threads of the all-cores oracle leg (default: min(16, host cores))")
     ap.add_argument("--graph", action="store_true",
                     help="record the step into a HIP graph once and replay it for the timed steps")
     ap.add_argument("--extras", action="store_true",
@@ -50,41 +54,45 @@ def parse_args():
     return ap.parse_args()
 
 
-# VALU roof.  A gfx950 SIMD retires a wave64 instruction of the simple classes
-# (fp32 add/mul/fma, integer add, logic) in 2 cycles and one of the other classes
-# (conversions, shifts and bit-fields, min/max/med3, rounding, 32-bit integer
-# multiplies) in 4: 256 CUs x 4 SIMDs x 32 lanes x 2.4 GHz = 78.6 T full-rate
-# lane-operations/s, which is the published 157.3 TFLOP/s fp32 figure at 2 flops
-# per fma.  Work is counted in full-rate equivalents: a half-rate operation is 2.
+# VALU roof: 256 CUs x 4 SIMDs x 32 lanes x 2.4 GHz = 78.6 T lane-operations/s for the
+# instructions a SIMD retires at full rate (fp32 add/mul/fma, integer add, logic) --
+# the published 157.3 TFLOP/s fp32 vector figure at 2 flops per fma.  Conversions,
+# left shifts and bit-fields, min/max/med3, rounding and integer multiplies retire at
+# half that rate (profiles/gfx950_valu_issue_rates.txt has the measurement).
 VALU_PEAK_TOPS = 256 * 4 * 32 * 2.4e9 / 1e12
 
-# Algorithmic lane-operations per element in full-rate equivalents, counted from
-# the arithmetic the header states on a machine with a 32x32->64 multiply, a
-# three-input logic op and fma (what gfx950 has); work that is uniform across a
-# wave (key schedule, step, 1/step) is not counted.
-OPS_PHILOX = (20 * 2 + 20 * 1) / 8.0   # 10 rounds x (2 multiplies (half rate) + 2 xor3) per 8 elements
-OPS_DITHER = 2 + 1                      # convert the 16-bit half (half rate), fma onto the mid-point grid
+# Algorithmic lane-operations per element: the arithmetic the header states on a
+# machine with a 32x32->64 multiply, a three-input logic op and fma; work that is
+# uniform across a wave (key schedule, step, 1/step) is not counted.  Each entry is
+# (operations counted once each, the same in full-rate equivalents: a half-rate
+# operation counts 2).  roofline.frac uses the first; the second is reported as
+# frac_weighted and credits nothing but says how busy the issue ports are.
+OPS_PHILOX = (40 / 8.0, (20 * 2 + 20 * 1) / 8.0)   # 10 rounds x (2 multiplies + 2 xor3) per 8 elements
+OPS_DITHER = (2.0, 3.0)                            # convert the 16-bit half (half rate), fma
 
 
 def _ops_encode(bf16, nested_pow2_own_step):
-    widen = 1.5 if bf16 else 0.0        # low half: shift (2), high half: mask (1)
-    absmax = 1.0 if bf16 else 2.0       # packed 16-bit max per 2 elements / max(|.|)
-    if nested_pow2_own_step:            # fma, magic-constant add, funnel shift (2)
-        quant = 1 + 1 + 2
-    else:                               # fma, rint (2), clip (2), pack fma, convert per 4 codes
-        quant = 1 + 2 + 2 + 1 + 0.5
-    return OPS_PHILOX + OPS_DITHER + widen + absmax + quant
+    widen = (1.0, 1.5) if bf16 else (0.0, 0.0)      # low half: shift (half rate), high half: mask
+    absmax = (1.0, 1.5) if bf16 else (2.0, 3.0)     # bf16: and + packed 16-bit max per 2 elements; fp32: |.|, max
+    if nested_pow2_own_step:                        # fma, magic-constant add, funnel shift (half rate)
+        quant = (3.0, 4.0)
+    else:                                           # fma, rint, clip (both half rate), pack fma, convert per 4 codes
+        quant = (4.25, 6.5)
+    return tuple(OPS_PHILOX[i] + OPS_DITHER[i] + widen[i] + absmax[i] + quant[i] for i in (0, 1))
+
+
+def _plus(base, once, weighted):
+    return (base[0][0] + base[1][0] + once, base[0][1] + base[1][1] + weighted)
 
 
 OPS = {
     "dq_encode": lambda bf16: _ops_encode(bf16, False),
     "nested_encode": lambda bf16: _ops_encode(bf16, True),
-    # code -> float (mask, fma) + subtract dither + scale (+ add when accumulating)
-    "dq_decode_store": lambda bf16: OPS_PHILOX + OPS_DITHER + 4,
-    "dq_decode_accumulate": lambda bf16: OPS_PHILOX + OPS_DITHER + 5,
-    # code -> float (2), side scale, fma, subtract, divide by M, rint (2), fma,
-    # subtract dither, scale, add to the running sum
-    "nested_decode": lambda bf16: OPS_PHILOX + OPS_DITHER + 13,
+    # code -> float (mask, fma), subtract dither, scale (+ add when accumulating)
+    "dq_decode_store": lambda bf16: _plus((OPS_PHILOX, OPS_DITHER), 4, 4),
+    "dq_decode_accumulate": lambda bf16: _plus((OPS_PHILOX, OPS_DITHER), 5, 5),
+    # code -> m/M (mask, fma), side scale, fma, fma, rint (half rate), add, fma, scale, add to the sum
+    "nested_decode": lambda bf16: _plus((OPS_PHILOX, OPS_DITHER), 10, 11),
 }
 
 
@@ -102,17 +110,33 @@ def algorithmic_bytes(kind, n, bits, K, s_in):
     raise ValueError(kind)
 
 
+def kernel_source_hash():
+    """sha256 over the kernel sources: a counter summary under profiles/ names the hash it
+    was taken with, and its traffic figure is only passed on while the sources still match."""
+    import hashlib
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_1904_01197_amd", "csrc")
+    for name in sorted(os.listdir(csrc)):
+        if name.startswith("ndq_") and name.endswith((".hip", ".hpp")):
+            h.update(name.encode())
+            h.update(open(os.path.join(csrc, name), "rb").read())
+    return h.hexdigest()[:16]
+
+
 def measured_traffic(kernel_key):
-    """HBM bytes per launch from the committed rocprofv3 counter summary, if any."""
+    """(HBM bytes per launch from the committed rocprofv3 counter summary, its provenance) --
+    (None, reason) when there is none or it was taken with other kernel sources."""
     path = os.path.join(ROOT, "profiles", "cfg5_hbm_traffic_pmc.txt")
     if not os.path.exists(path):
-        return None
-    pat = re.compile(r"^%s\s+traffic_bytes_per_launch\s*=\s*([0-9.eE+]+)" % re.escape(kernel_key))
-    for line in open(path):
-        m = pat.match(line.strip())
-        if m:
-            return float(m.group(1))
-    return None
+        return None, "no counter summary committed"
+    text = open(path).read()
+    m = re.search(r"^kernel_source_sha256_16\s*=\s*([0-9a-f]+)", text, re.M)
+    if not m or m.group(1) != kernel_source_hash():
+        return None, "profiles/cfg5_hbm_traffic_pmc.txt was taken with other kernel sources"
+    m2 = re.search(r"^%s\s+traffic_bytes_per_launch\s*=\s*([0-9.eE+]+)" % re.escape(kernel_key), text, re.M)
+    if not m2:
+        return None, "kernel not in profiles/cfg5_hbm_traffic_pmc.txt"
+    return float(m2.group(1)), "profiles/cfg5_hbm_traffic_pmc.txt (sources %s)" % m.group(1)
 
 
 def main():
@@ -159,18 +183,12 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    # ---- whole path: W warm-up steps, then exactly K timed steps ----------------
-    if args.schedule == "overlap":
-        ts = pipeline.TwoStreams(wl.W)
-        one_step = lambda: pipeline.step_overlapped(wl, dev, bufs, ds, ts, preset)
-    elif args.schedule == "fused":
+    # ---- whole path: time-based pre-warm, W warm-up steps, then exactly K timed steps ----
+    if args.schedule == "fused":
         one_step = lambda: pipeline.step_fused(wl, dev, bufs, ds, preset)
     else:
         one_step = lambda: pipeline.step(wl, dev, bufs, ds, preset)
     if args.graph:
-        if args.schedule == "overlap":
-            print("bench.py: --graph records one stream; use it with serial or fused", file=sys.stderr)
-            sys.exit(2)
         eager_step = one_step
         cap = torch.cuda.Stream()
         cap.wait_stream(torch.cuda.current_stream())
@@ -182,6 +200,17 @@ def main():
         with torch.cuda.graph(hip_graph, stream=cap):
             eager_step()
         one_step = hip_graph.replay
+    # The first few milliseconds after idle run at boost clocks, the next tens of
+    # milliseconds well below the settled rate: a short timed region right after idle
+    # measures the power controller, not the kernels.
+    t_pre = time.perf_counter()
+    prewarm_steps = 0
+    while (time.perf_counter() - t_pre) * 1e3 < args.prewarm_ms:
+        for _ in range(8):
+            one_step()
+        torch.cuda.synchronize()
+        prewarm_steps += 8
+    prewarm_ms = (time.perf_counter() - t_pre) * 1e3
     for _ in range(args.warmup):
         one_step()
     torch.cuda.synchronize()
@@ -193,13 +222,22 @@ def main():
     ms_per_step = elapsed * 1e3 / args.steps
     grad_bytes = wl.W * n * s_in
     value = grad_bytes / (ms_per_step * 1e-3) / 1e9
+    # the same steps once more with an event on the launch stream around each: the median
+    step_marks = [torch.cuda.Event(enable_timing=True) for _ in range(max(args.steps, 20) + 1)]
+    step_marks[0].record()
+    for i in range(1, len(step_marks)):
+        one_step()
+        step_marks[i].record()
+    torch.cuda.synchronize()
+    step_ms = sorted(step_marks[i].elapsed_time(step_marks[i + 1]) for i in range(len(step_marks) - 1))
+    ms_per_step_event_median = step_ms[len(step_ms) // 2]
 
     # ---- per-kernel durations, in place: events on the launch stream around
     # every library call of the step, averaged over --kernel-reps further steps ----
     bf16 = wl.dtype == "bf16"
     calls = []   # (kernel key, function, algorithmic bytes, algorithmic lane-ops)
     count = 0
-    chain_bytes, chain_ops = 4 * n, 0
+    chain_bytes, chain_ops = 4 * n, (0.0, 0.0)
     decs = []
     for w, (kind, arg) in enumerate(wl.plan):
         bits = ndq.ndq_code_bits(arg)
@@ -223,13 +261,13 @@ def main():
                     bufs.total, True))
         count += 1
         chain_bytes += (n * bits + 7) // 8 + 4 * K
-        chain_ops += n * OPS[dkind](bf16)
+        dec_ops = tuple(n * x for x in OPS[dkind](bf16))
+        chain_ops = (chain_ops[0] + dec_ops[0], chain_ops[1] + dec_ops[1])
         own_step = wl.bucket != 0 or preset == 0.0
-        enc_ops = OPS["nested_encode" if (kind != "dq" and arg & (arg - 1) == 0 and own_step)
-                      else "dq_encode"](bf16)
-        calls.append((enc_key, enc, algorithmic_bytes("encode", n, bits, K, s_in), n * enc_ops))
-        decs.append((dec_key, dec, algorithmic_bytes(dkind, n, bits, K, s_in),
-                     n * OPS[dkind](bf16)))
+        enc_ops = tuple(n * x for x in OPS["nested_encode" if (kind != "dq" and arg & (arg - 1) == 0 and own_step)
+                                           else "dq_encode"](bf16))
+        calls.append((enc_key, enc, algorithmic_bytes("encode", n, bits, K, s_in), enc_ops))
+        decs.append((dec_key, dec, algorithmic_bytes(dkind, n, bits, K, s_in), dec_ops))
     enc_bytes = sum(c[2] for c in calls)
     serial_bytes = enc_bytes + sum(d[2] for d in decs) + (8 * n if wl.out_scale != 1.0 else 0)
     fused_bytes = enc_bytes + chain_bytes
@@ -241,7 +279,7 @@ def main():
         if wl.out_scale != 1.0:
             calls.append(("aggregate_scale",
                           lambda: ndq.ndq_aggregate([bufs.total], wl.out_scale, bufs.total),
-                          8 * n, n))
+                          8 * n, (float(n), float(n))))
     reps = args.kernel_reps
     marks = [[torch.cuda.Event(enable_timing=True) for _ in range(len(calls) + 1)]
              for _ in range(reps)]
@@ -261,7 +299,8 @@ def main():
             rec["launches_per_step"] += 1
         else:
             rec = {"kernel": key, "launches_per_step": 1, "_ms_sum": ms,
-                   "algorithmic_bytes": nbytes, "algorithmic_lane_ops": nops}
+                   "algorithmic_bytes": nbytes, "algorithmic_lane_ops": nops[0],
+                   "algorithmic_lane_ops_weighted": nops[1]}
             seen[key] = rec
             kernels.append(rec)
     for rec in kernels:
@@ -269,6 +308,8 @@ def main():
         rec["avg_ms"] = round(ms, 5)
         rec["GBps"] = round(rec["algorithmic_bytes"] / (ms * 1e-3) / 1e9, 1)
         rec["Tops"] = round(rec["algorithmic_lane_ops"] / (ms * 1e-3) / 1e12, 2)
+        rec["hbm_frac"] = round(rec["algorithmic_bytes"] / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
+        rec["alu_frac"] = round(rec["algorithmic_lane_ops"] / (ms * 1e-3) / 1e12 / VALU_PEAK_TOPS, 4)
 
     def timed(fn, reps):
         fn()
@@ -285,6 +326,8 @@ def main():
     sec = dominant["avg_ms"] * 1e-3
     hbm_frac = dominant["algorithmic_bytes"] / sec / 1e9 / HBM_PEAK_GBS
     alu_frac = dominant["algorithmic_lane_ops"] / sec / 1e12 / VALU_PEAK_TOPS
+    alu_frac_weighted = dominant["algorithmic_lane_ops_weighted"] / sec / 1e12 / VALU_PEAK_TOPS
+    traffic, traffic_from = measured_traffic(dominant["kernel"])
     if hbm_frac >= alu_frac:
         roofline = {"bound": "hbm", "kernel": dominant["kernel"],
                     "achieved": round(hbm_frac * HBM_PEAK_GBS, 1), "peak": HBM_PEAK_GBS,
@@ -292,12 +335,15 @@ def main():
     else:
         roofline = {"bound": "alu", "kernel": dominant["kernel"],
                     "achieved": round(alu_frac * VALU_PEAK_TOPS, 2),
-                    "peak": round(VALU_PEAK_TOPS, 2), "unit": "Tlane-op/s (full-rate equivalents)",
+                    "peak": round(VALU_PEAK_TOPS, 2), "unit": "Tlane-op/s (each operation of the method counted once)",
                     "frac": round(alu_frac, 4)}
-    roofline.update({"traffic": measured_traffic(dominant["kernel"]),
+    roofline.update({"traffic": traffic, "traffic_from": traffic_from,
                      "algorithmic_bytes_per_launch": dominant["algorithmic_bytes"],
                      "algorithmic_lane_ops_per_launch": dominant["algorithmic_lane_ops"],
                      "hbm_frac": round(hbm_frac, 4), "alu_frac": round(alu_frac, 4),
+                     "alu_frac_weighted": round(alu_frac_weighted, 4),
+                     "alu_frac_weighted_note": "half-rate instructions counted as 2 full-rate ones: how busy the "
+                                               "issue ports are, not a credit",
                      "avg_launch_ms": dominant["avg_ms"]})
     step_bytes = sum(r["algorithmic_bytes"] * r["launches_per_step"] for r in kernels)
 
@@ -384,8 +430,8 @@ def main():
     copy_gbps = 8.0 * m / (copy_ms * 1e-3) / 1e9
     del spare
 
-    # ---- CPU baseline: the oracle, as it stands, on a bounded sample ------------
-    cpu = None
+    # ---- CPU baseline: the oracle, as it stands -- and the whole step checked against it ----
+    cpu, parity, diagnostics = None, None, None
     if not args.no_cpu:
         import oracle
         from oracle import pipeline as opipe
@@ -394,6 +440,13 @@ def main():
         seeds = [workloads.dither_seed(wl, w) for w in range(wl.W)]
         ds_o = opipe.dithers(wl.W, seeds)
         oracle.lib()
+        # what the GPU path leaves after one more step of the timed schedule
+        one_step()
+        torch.cuda.synchronize()
+        got_out = bufs.total.cpu().numpy()
+        got_codes = [c.cpu().numpy() for c in bufs.codes]
+        got_steps = [x.cpu().numpy() for x in bufs.steps]
+        # (i) one thread, one call per worker and direction over the sample
         c0 = time.perf_counter()
         codes, steps, _ = opipe.encode_all(wl.plan, wl.fine_levels, wl.bucket, wl.shared_step, sl,
                                            ds_o, preset)
@@ -404,11 +457,49 @@ def main():
                "sample": "first %d elements per worker of the same %d-worker workload "
                          "(encode all + decode chain), %.1f s single-thread C oracle on a "
                          "%d-core host" % (ns, wl.W, cpu_s, os.cpu_count() or 0)}
+        ref_codes, ref_steps, ref_out, n_cmp = codes, steps, ref, ns
+        # (ii) the same oracle on bucket-aligned slices, as many at a time as the host has cores for
+        if wl.bucket > 0 and not wl.shared_step:
+            threads = args.cpu_threads or min(16, os.cpu_count() or 1)
+            c0 = time.perf_counter()
+            ref_codes, ref_steps, ref_out = opipe.step_sliced(wl.plan, wl.fine_levels, wl.bucket, host, seeds,
+                                                              wl.out_scale, threads=threads)
+            all_s = time.perf_counter() - c0
+            n_cmp = n
+            cpu["all_cores"] = {"value": round(grad_bytes / all_s / 1e9, 5), "unit": "GB/s", "cores": threads,
+                                "host_cores": os.cpu_count() or 0,
+                                "sample": "all %d elements per worker, %.1f s, %d threads on bucket-aligned "
+                                          "slices (the same C functions; they release the interpreter lock)"
+                                          % (n, all_s, threads)}
+            same = all(a[:x.size].tobytes() == x.tobytes() for a, x in zip(ref_codes, codes)) and \
+                np.array_equal(ref_out[:ns], ref)
+            cpu["all_cores"]["equals_single_thread_result_on_its_sample"] = bool(same)
+            _, _, _, diagnostics = opipe.step_sliced(wl.plan, wl.fine_levels, wl.bucket, host, seeds, wl.out_scale,
+                                                     threads=threads, diagnostics=True)
+        # whole-step parity: every code byte, every step, every output of the n_cmp elements compared
+        codes_ok = all(g[:(n_cmp * ndq.ndq_code_bits(arg) + 7) // 8].tobytes() ==
+                       r[:(n_cmp * ndq.ndq_code_bits(arg) + 7) // 8].tobytes()
+                       for g, r, (_, arg) in zip(got_codes, ref_codes, wl.plan))
+        kb = ndq.ndq_num_buckets(n_cmp, wl.bucket)
+        steps_ok = all(np.array_equal(g[:kb], r[:kb]) for g, r in zip(got_steps, ref_steps))
+        diff = np.abs(got_out[:n_cmp].astype(np.float64) - ref_out[:n_cmp].astype(np.float64))
+        step_sum = sum(r[:kb].astype(np.float64) for r in ref_steps)
+        tol = (np.repeat(step_sum, wl.bucket)[:n_cmp] if wl.bucket else step_sum[0]) * 2.0 ** -20
+        parity = {"parity_checked": True, "elements_compared_per_worker": int(n_cmp),
+                  "codes_bit_exact": bool(codes_ok), "steps_bit_exact": bool(steps_ok),
+                  "max_abs_diff_over_step": float(diff.max()) if n_cmp else 0.0,
+                  "outputs_within_2^-20_step": bool(np.all(diff <= tol)),
+                  "outputs_bit_exact": bool(np.array_equal(got_out[:n_cmp], ref_out[:n_cmp]))}
+        if not (codes_ok and steps_ok and parity["outputs_within_2^-20_step"]):
+            print("bench.py: the GPU path disagrees with the oracle: %r" % parity, file=sys.stderr)
+            sys.exit(3)
 
     out = {
         "metric": "encode+decode+aggregate GB/s of gradient (and % of MI355X HBM peak) at n=2^27",
         "value": round(value, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "ms_per_step_event_median": round(ms_per_step_event_median, 4),
+        "prewarm_ms": round(prewarm_ms, 1), "prewarm_steps": prewarm_steps, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": wl.name, "W": wl.W, "n_per_worker": n, "input_dtype": wl.dtype,
                    "bucket": wl.bucket, "schedule": args.schedule, "hip_graph": bool(args.graph), "plan": ["%s%d" % p for p in wl.plan],
@@ -420,7 +511,11 @@ def main():
         "step_frac_of_device_copy": round(step_bytes / (ms_per_step * 1e-3) / 1e9 / copy_gbps, 4),
         "roofline": roofline,
         "cpu_baseline": cpu,
+        "parity": parity,
+        "clip_fraction": diagnostics["clip_fraction"] if diagnostics else None,
+        "coset_error_fraction": diagnostics["coset_error_fraction"] if diagnostics else None,
         "kernels": kernels,
+        "kernel_ms_sum_per_step": round(sum(r["avg_ms"] * r["launches_per_step"] for r in kernels), 4),
         "other_schedule": {
             "schedule": other, "ms_per_step": round(other_ms, 4),
             "value": round(grad_bytes / (other_ms * 1e-3) / 1e9, 2),
