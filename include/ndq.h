@@ -18,8 +18,13 @@
  *   - The library never allocates, frees, retains or synchronises.  A call only
  *     enqueues kernels on `stream` (a hipStream_t passed as void*; NULL = the
  *     default stream) and returns.
- *   - Return value: 0 on success, a negative ndq_status on error; on error
- *     nothing has been enqueued.  n == 0 is a successful no-op.
+ *   - Return value: 0 on success, a negative ndq_status on error.  Arguments are
+ *     checked before anything is launched: with NDQ_EINVAL, NDQ_EALIGN or
+ *     NDQ_EUNSUPPORTED nothing has been enqueued.  NDQ_ELAUNCH comes from the
+ *     runtime's launch call itself; calls made of several kernels (a max-norm
+ *     pass before the encoder, ndq_code_entropy, ndq_sqdiff, more than 32 workers
+ *     in ndq_decode_chain / ndq_aggregate) may then already have enqueued their
+ *     first kernels, and the outputs are unspecified.  n == 0 is a successful no-op.
  *   - g, codes, out and side must be 16-byte aligned; steps 4-byte aligned.
  *     bucket must be 0 or a multiple of 64; d->offset a multiple of 8 (and of
  *     bucket when a slice of a bucketed vector is processed).
@@ -87,10 +92,13 @@ typedef struct {
  * (Sec. 3.2, last paragraph: log2(Delta_2/Delta_1) bits per nested value.) */
 uint32_t ndq_code_bits(uint32_t levels_or_M);
 
-/* Size in bytes of a packed code stream: ceil(n*bits/8) rounded up to 16. */
+/* Size in bytes of a packed code stream: ceil(n*bits/8) rounded up to 16 (the
+ * message of Algorithm 1's worker step "send q_p": n indices of `bits` bits). */
 size_t ndq_packed_bytes(size_t n, uint32_t bits);
 
-/* Number of scale factors: 1 if bucket == 0, else ceil(n/bucket). */
+/* Number of scale factors: 1 if bucket == 0, else ceil(n/bucket) (Sec. 3.1, the
+ * paragraph after Lemma 2: the gradient is partitioned into sub-vectors, each
+ * quantized with its own scale factor; `bucket` is the sub-vector length). */
 size_t ndq_num_buckets(size_t n, uint32_t bucket);
 
 /* Max-norm scale factors kappa_b = max |g_i| per bucket (Sec. 3.1 eq. (2): the

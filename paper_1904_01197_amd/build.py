@@ -49,6 +49,25 @@ def build_library(force=True, verbose=False, so=None):
     return so
 
 
+# Stand-alone measurement programs (no part of the library): the instruction issue rates
+# the kernels' instruction choices and the benchmark's "alu" roof rest on, and the
+# streaming bandwidth the memory system gives the encoders' traffic.
+PROBES = ("valu_issue_probe", "hbm_stream_probe")
+
+
+def build_probes(verbose=False):
+    """Compiles the probes next to the library; returns their paths."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    out = []
+    for name in PROBES:
+        exe = os.path.join(HERE, name)
+        _run([hipcc, "-O3", "--offload-arch=gfx950", "-std=c++17", "-Wno-unused-command-line-argument",
+              "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+              "-o", exe, os.path.join(CSRC, name + ".hip")], verbose)
+        out.append(exe)
+    return out
+
+
 def ensure_built():
     """Builds the library only if no built one is there (a fresh checkout)."""
     if not os.path.exists(SO):
@@ -58,3 +77,4 @@ def ensure_built():
 
 if __name__ == "__main__":
     print(build_library(force=True, verbose=True))
+    print("\n".join(build_probes(verbose=True)))

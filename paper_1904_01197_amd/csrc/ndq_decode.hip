@@ -474,6 +474,24 @@ __device__ __forceinline__ void stream_fetch(const unsigned char* codes, const f
     f.step = steps[bucket];
 }
 
+// The same for the vector's ragged last tile of `len` elements: a lane fetches its bytes
+// only if its first code exists (they then lie inside the stream, whose size is padded to
+// a multiple of 16 bytes: (o/8 + 1) * WIDTH <= the padded size of the tile's codes).
+template <int WIDTH>
+__device__ __forceinline__ void stream_fetch_ragged(const unsigned char* codes, const float* steps, uint64_t start,
+                                                    uint32_t len, uint32_t bucket, int lane, ChainCodes& f)
+{
+    const unsigned char* mine = codes + (start >> 3) * WIDTH + (uint32_t)lane * WIDTH;
+#pragma unroll
+    for (int r = 0; r < kChainRows; ++r) {
+        const unsigned char* p = mine + (uint32_t)(r * kWave) * WIDTH;
+        f.w[r] = 0u;
+        if ((uint32_t)(r * kWave + lane) * kLaneElems < len)
+            f.w[r] = WIDTH == 1 ? (uint32_t)*p : WIDTH == 2 ? (uint32_t)*(const uint16_t*)p : *(const uint32_t*)p;
+    }
+    f.step = steps[bucket];
+}
+
 template <int MODE, int WIDTH, bool FIRST>
 __device__ __forceinline__ void stream_fold(const DitherStream& ds, uint64_t block0, float q_min_f,
                                             float side_scale, const ChainCodes& f, int lane,
@@ -514,7 +532,45 @@ __device__ __forceinline__ void stream_fold(const DitherStream& ds, uint64_t blo
     }
 }
 
+// The ragged last tile with the same folds: lanes past the end decode zeros and store nothing.
 template <int RMODE, int W0, int WR>
+__device__ __forceinline__ void stream_ragged_tile(ChainArgsPtr a, uint64_t start, uint32_t len, uint32_t bucket,
+                                                   int lane)
+{
+    const uint32_t W = a->W;
+    float S[kChainRows][8];
+    ChainCodes cur, nxt;
+    stream_fetch_ragged<W0>(a->w[0].codes, a->w[0].steps, start, len, bucket, lane, cur);
+    nxt = cur;
+    if (W > 1u) stream_fetch_ragged<WR>(a->w[1].codes, a->w[1].steps, start, len, bucket, lane, nxt);
+    {
+        const DitherStream ds = {a->w[0].ds.key0, a->w[0].ds.key1, a->w[0].ds.step, a->w[0].ds.worker};
+        stream_fold<kDq, W0, true>(ds, (a->w[0].index0 + start) >> 3, (float)a->w[0].q_min, 0.0f, cur, lane, S);
+    }
+    cur = nxt;
+    for (uint32_t w = 1; w < W; ++w) {
+        if (w + 1u < W) stream_fetch_ragged<WR>(a->w[w + 1u].codes, a->w[w + 1u].steps, start, len, bucket, lane, nxt);
+        const DitherStream ds = {a->w[w].ds.key0, a->w[w].ds.key1, a->w[w].ds.step, a->w[w].ds.worker};
+        stream_fold<RMODE, WR, false>(ds, (a->w[w].index0 + start) >> 3, (float)a->w[w].q_min, a->w[w].side_scale,
+                                      cur, lane, S);
+        cur = nxt;
+    }
+    float* out = a->out + start;
+    const float scale = a->scale;
+    const bool apply_scale = a->apply_scale != 0;
+#pragma unroll
+    for (int r = 0; r < kChainRows; ++r) {
+        const uint32_t o = (uint32_t)(r * kWave + lane) * kLaneElems;
+#pragma unroll
+        for (uint32_t k = 0; k < 8; ++k)
+            if (o + k < len) out[o + k] = apply_scale ? scale * S[r][k] : S[r][k];
+    }
+}
+
+// RAGGED: the vector ends in a ragged tile.  An instantiation of its own, because the mere
+// presence of that code in the kernel measured 6 % on the main loop (config 5, which has
+// no ragged tile: 215 against 203 us) although the loop's instructions are the same.
+template <int RMODE, int W0, int WR, bool RAGGED>
 __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(kChainStreamWaves, kChainStreamWaves)))
 void chain_stream_kernel(ChainArgs a_by_value)
 {
@@ -529,6 +585,12 @@ void chain_stream_kernel(ChainArgs a_by_value)
     float* out_base = a->out;
     const float scale = a->scale;
     const bool apply_scale = __builtin_amdgcn_readfirstlane(a->apply_scale) != 0;
+    // The ragged last tile goes first, to a wave that has no whole tile if the grid has one
+    // (one tile per wave), else to wave 0: at the start every SIMD is full and hides its
+    // latencies; as a kernel of its own, or at the end, it would run alone at a fifth of the rate.
+    const uint64_t whole = (uint64_t)tiles * kChainTile;
+    if (RAGGED && whole < a->tl.n && first == (stride > tiles ? tiles : 0u))
+        stream_ragged_tile<RMODE, W0, WR>(a, whole, (uint32_t)(a->tl.n - whole), one_bucket ? 0u : tiles / tpb, lane);
     if (first >= tiles) return;
     const uint32_t my_tiles = (tiles - first + stride - 1u) / stride;
     uint32_t done = 0;
@@ -643,9 +705,7 @@ static int run_decode3(DecodeArgs a, uint64_t n, uint32_t bucket, hipStream_t s)
 {
     const int rc = make_tiling(n, bucket, DecTile<DecRows<MODE, ACC>::R>::N, &a.tl);
     if (rc != NDQ_OK) return rc;
-    hipLaunchKernelGGL((decode_kernel<MODE, ACC, STRADDLE>), dim3(blocks_for(a.tl.total_tiles)),
-                       dim3(kBlock), 0, s, a);
-    return launched();
+    return launch((decode_kernel<MODE, ACC, STRADDLE>), dim3(blocks_for(a.tl.total_tiles)), dim3(kBlock), s, a);
 }
 
 template <int MODE, bool STRADDLE>
@@ -710,10 +770,12 @@ static int launch_chain_stream(const ChainArgs& a, hipStream_t s)
     // number of tiles (give or take one).  Otherwise one tile per wave: with only a few tiles
     // per wave a fixed share would leave SIMDs idle at the end.
     const uint32_t tiles = a.tile_begin, slots = 1024u * kChainStreamWaves;
-    const uint32_t blocks = tiles >= stream_tuning().chain_min_tiles_per_wave * slots ? persistent_blocks(tiles, slots)
-                                                                                       : blocks_for(tiles);
-    hipLaunchKernelGGL((chain_stream_kernel<RMODE, W0, WR>), dim3(blocks), dim3(kBlock), 0, s, a);
-    return launched();
+    const bool ragged = (uint64_t)tiles * kChainTile < a.tl.n;     // one more wave takes the ragged last tile
+    const uint32_t blocks = tiles >= stream_tuning().chain_min_tiles_per_wave * slots
+                                ? persistent_blocks(tiles, slots)
+                                : blocks_for(tiles + (ragged ? 1u : 0u));
+    if (ragged) return launch((chain_stream_kernel<RMODE, W0, WR, true>), dim3(blocks), dim3(kBlock), s, a);
+    return launch((chain_stream_kernel<RMODE, W0, WR, false>), dim3(blocks), dim3(kBlock), s, a);
 }
 
 template <int RMODE, int W0>
@@ -724,8 +786,8 @@ static int launch_chain_stream_w(const ChainArgs& a, uint32_t wr, hipStream_t s)
     return launch_chain_stream<RMODE, W0, 4>(a, s);
 }
 
-// Runs the streaming kernel when the plan and the tiling allow it (then the ragged
-// last tile, if any, goes to the general kernel); returns 1 when it does not apply.
+// Runs the streaming kernel when the plan and the tiling allow it; returns 1 when it
+// does not apply.
 static int try_chain_stream(ChainArgs a, uint32_t bucket, hipStream_t s)
 {
     if (a.row_buckets || a.continue_sum) return 1;
@@ -754,12 +816,7 @@ static int try_chain_stream(ChainArgs a, uint32_t bucket, hipStream_t s)
                       : w0 == 2u ? launch_chain_stream_w<kNestedPow2, 2>(b, wr, s)
                                  : launch_chain_stream_w<kNestedPow2, 4>(b, wr, s);
     }
-    if (rc != NDQ_OK) return rc;
-    if ((uint64_t)full * kChainTile < a.tl.n) {              // ragged last tile
-        hipLaunchKernelGGL((chain_kernel<false, false>), dim3(1), dim3(kBlock), 0, s, b);
-        return launched();
-    }
-    return NDQ_OK;
+    return rc;
 }
 
 }  // namespace ndq
@@ -817,9 +874,8 @@ int ndq_aggregate(const float* const* gs, uint32_t W, size_t n, float scale, flo
         a.continue_sum = w0 != 0u;
         a.finish = w0 + kAggMax >= W;
         a.scale = scale;
-        hipLaunchKernelGGL(aggregate_kernel, dim3((uint32_t)blocks), dim3(kBlock), 0,
-                           (hipStream_t)stream, a);
-        if (launched() != NDQ_OK) return NDQ_ELAUNCH;
+        if (launch(aggregate_kernel, dim3((uint32_t)blocks), dim3(kBlock), (hipStream_t)stream, a) != NDQ_OK)
+            return NDQ_ELAUNCH;
     }
     return NDQ_OK;
 }
@@ -892,11 +948,12 @@ int ndq_decode_chain(const ndq_worker* workers, uint32_t W, size_t n, uint32_t b
         }
 #endif
         const dim3 grid(blocks_for(a.tl.total_tiles)), block(kBlock);
-        if (a.row_buckets && any_m) hipLaunchKernelGGL((chain_kernel<true, true>), grid, block, 0, hs, a);
-        else if (a.row_buckets) hipLaunchKernelGGL((chain_kernel<true, false>), grid, block, 0, hs, a);
-        else if (any_m) hipLaunchKernelGGL((chain_kernel<false, true>), grid, block, 0, hs, a);
-        else hipLaunchKernelGGL((chain_kernel<false, false>), grid, block, 0, hs, a);
-        if (launched() != NDQ_OK) return NDQ_ELAUNCH;
+        int rc_launch;
+        if (a.row_buckets && any_m) rc_launch = launch((chain_kernel<true, true>), grid, block, hs, a);
+        else if (a.row_buckets) rc_launch = launch((chain_kernel<true, false>), grid, block, hs, a);
+        else if (any_m) rc_launch = launch((chain_kernel<false, true>), grid, block, hs, a);
+        else rc_launch = launch((chain_kernel<false, false>), grid, block, hs, a);
+        if (rc_launch != NDQ_OK) return NDQ_ELAUNCH;
     }
     return NDQ_OK;
 }

@@ -483,9 +483,8 @@ __global__ void steps_from_kappa_kernel(float* steps, uint64_t K, uint32_t level
 template <int DT>
 static int run_absmax(const void* g, const Tiling& tl, uint64_t K, float* kappa, hipStream_t s)
 {
-    hipLaunchKernelGGL(fill_zero_kernel, dim3((uint32_t)((K + 255) / 256)), dim3(256), 0, s,
-                       (uint32_t*)kappa, K);
-    if (launched() != NDQ_OK) return NDQ_ELAUNCH;
+    if (launch(fill_zero_kernel, dim3((uint32_t)((K + 255) / 256)), dim3(256), s, (uint32_t*)kappa, K) != NDQ_OK)
+        return NDQ_ELAUNCH;
     // many tiles per bucket: a few hundred tiles per workgroup, about 4096 workgroups in all
     constexpr uint32_t kSpanMinTiles = 64, kSpanTarget = 4096;
     if (tl.tiles_per_bucket >= kSpanMinTiles && K <= kSpanTarget) {
@@ -493,13 +492,10 @@ static int run_absmax(const void* g, const Tiling& tl, uint64_t K, float* kappa,
         const uint32_t most = tl.tiles_per_bucket / (2 * kWavesPerBlock);   // at least two tiles per wave
         if (per_bucket > most) per_bucket = most;
         if (per_bucket < 1) per_bucket = 1;
-        hipLaunchKernelGGL(absmax_span_kernel<DT>, dim3((uint32_t)K * per_bucket), dim3(kBlock), 0, s, g, tl,
-                           (uint32_t*)kappa, per_bucket);
-        return launched();
+        return launch(absmax_span_kernel<DT>, dim3((uint32_t)K * per_bucket), dim3(kBlock), s, g, tl,
+                      (uint32_t*)kappa, per_bucket);
     }
-    hipLaunchKernelGGL(absmax_kernel<DT>, dim3(blocks_for(tl.total_tiles)), dim3(kBlock), 0, s, g, tl,
-                       (uint32_t*)kappa);
-    return launched();
+    return launch(absmax_kernel<DT>, dim3(blocks_for(tl.total_tiles)), dim3(kBlock), s, g, tl, (uint32_t*)kappa);
 }
 
 // Waves of the streaming kernel: kStreamWaves on each of the 1,024 SIMDs.
@@ -509,8 +505,7 @@ template <int DT, int MODE, bool FUSED, int BITSW>
 static int launch_stream(const EncodeArgs& a, uint32_t full_tiles, hipStream_t s)
 {
     const uint32_t blocks = persistent_blocks(full_tiles, kStreamSlots);
-    hipLaunchKernelGGL((encode_stream_kernel<DT, MODE, FUSED, BITSW>), dim3(blocks), dim3(kBlock), 0, s, a, full_tiles);
-    return launched();
+    return launch((encode_stream_kernel<DT, MODE, FUSED, BITSW>), dim3(blocks), dim3(kBlock), s, a, full_tiles);
 }
 
 // The streaming kernel serves vectors cut into whole tiles (a ragged last one aside):
@@ -555,11 +550,10 @@ static int run_encode(const EncodeArgs& a, bool fused, bool multi, uint32_t buck
     if (rc != 1) return rc;
 #endif
     const dim3 grid(blocks_for(a.tl.total_tiles)), block(kBlock);
-    if (a.waves_log2 != 0u) hipLaunchKernelGGL((encode_kernel<DT, MODE, true, false, true>), grid, block, 0, s, a);
-    else if (multi) hipLaunchKernelGGL((encode_kernel<DT, MODE, true, true, false>), grid, block, 0, s, a);
-    else if (fused) hipLaunchKernelGGL((encode_kernel<DT, MODE, true, false, false>), grid, block, 0, s, a);
-    else hipLaunchKernelGGL((encode_kernel<DT, MODE, false, false, false>), grid, block, 0, s, a);
-    return launched();
+    if (a.waves_log2 != 0u) return launch((encode_kernel<DT, MODE, true, false, true>), grid, block, s, a);
+    if (multi) return launch((encode_kernel<DT, MODE, true, true, false>), grid, block, s, a);
+    if (fused) return launch((encode_kernel<DT, MODE, true, false, false>), grid, block, s, a);
+    return launch((encode_kernel<DT, MODE, false, false, false>), grid, block, s, a);
 }
 
 static int encode_common(const void* g, ndq_dtype dt, size_t n, float delta, uint32_t levels,
@@ -607,9 +601,9 @@ static int encode_common(const void* g, ndq_dtype dt, size_t n, float delta, uin
         rc = dt == NDQ_F32 ? run_absmax<0>(g, a.tl, K, steps_out, s)
                            : run_absmax<1>(g, a.tl, K, steps_out, s);
         if (rc != NDQ_OK) return rc;
-        hipLaunchKernelGGL(steps_from_kappa_kernel, dim3((uint32_t)((K + 255) / 256)), dim3(256), 0,
-                           s, steps_out, K, levels);
-        if (launched() != NDQ_OK) return NDQ_ELAUNCH;
+        if (launch(steps_from_kappa_kernel, dim3((uint32_t)((K + 255) / 256)), dim3(256), s, steps_out, K,
+                   levels) != NDQ_OK)
+            return NDQ_ELAUNCH;
     }
 #ifndef NDQ_NARROW_MAX_BITS
 #define NDQ_NARROW_MAX_BITS 6u
@@ -650,8 +644,7 @@ int ndq_absmax(const void* g, ndq_dtype dt, size_t n, uint32_t bucket, float* ka
     hipStream_t s = (hipStream_t)stream;
     if (n == 0) {   // one (empty) bucket: its max-norm is 0
         if (bucket != 0u) return NDQ_OK;
-        hipLaunchKernelGGL(fill_zero_kernel, dim3(1), dim3(256), 0, s, (uint32_t*)kappa_out, (uint64_t)1);
-        return launched();
+        return launch(fill_zero_kernel, dim3(1), dim3(256), s, (uint32_t*)kappa_out, (uint64_t)1);
     }
     if (!g) return NDQ_EINVAL;
     if (!aligned16(g)) return NDQ_EALIGN;

@@ -6,6 +6,9 @@
 #include <stdint.h>
 #include <stdlib.h>
 
+#include <tuple>
+#include <utility>
+
 #include "ndq.h"
 #include "ndq_device.hpp"
 
@@ -74,7 +77,27 @@ inline DitherStream make_stream(const ndq_dither* d)
     return s;
 }
 
-inline int launched() { return hipGetLastError() == hipSuccess ? NDQ_OK : NDQ_ELAUNCH; }
+// Launches `kernel` on `stream` and reports the launch call's OWN status.  (The
+// thread's last-error slot, hipGetLastError(), is shared with every other user of
+// the runtime in the process: reading it could report, and would clear, an error
+// that is not ours.)  The arguments are converted to the kernel's parameter types
+// first, as a <<<>>> launch would.
+template <typename... Params, size_t... I>
+inline int launch_with(void (*kernel)(Params...), dim3 grid, dim3 block, hipStream_t stream,
+                       std::tuple<Params...>& held, std::index_sequence<I...>)
+{
+    void* ptrs[sizeof...(Params) ? sizeof...(Params) : 1] = {(void*)&std::get<I>(held)...};
+    return hipLaunchKernel((const void*)kernel, grid, block, ptrs, 0, stream) == hipSuccess ? NDQ_OK
+                                                                                          : NDQ_ELAUNCH;
+}
+
+template <typename... Params, typename... Args>
+inline int launch(void (*kernel)(Params...), dim3 grid, dim3 block, hipStream_t stream, Args&&... args)
+{
+    static_assert(sizeof...(Params) == sizeof...(Args), "one argument per kernel parameter");
+    std::tuple<Params...> held(static_cast<Params>(args)...);
+    return launch_with(kernel, grid, block, stream, held, std::index_sequence_for<Params...>{});
+}
 
 inline uint32_t blocks_for(uint32_t tiles) { return (tiles + kWavesPerBlock - 1) / kWavesPerBlock; }
 
@@ -103,14 +126,15 @@ inline const StreamTuning& stream_tuning()
     return t;
 }
 
-// Grid of a persistent kernel: at most `slots` waves, every wave the same number of
-// tiles, give or take one.
+// Grid of a persistent kernel: `slots` waves, i.e. the same number of workgroups on
+// every compute unit (a grid trimmed so that every wave gets exactly the same number
+// of tiles leaves some compute units one workgroup short, and the others set the time).
 inline uint32_t persistent_blocks(uint32_t tiles, uint32_t slots)
 {
     const uint32_t cap = stream_tuning().max_blocks;
-    if (cap != 0u && cap * kWavesPerBlock < slots) slots = cap * kWavesPerBlock;
-    const uint32_t per_wave = (tiles + slots - 1u) / slots;
-    return blocks_for((tiles + per_wave - 1u) / per_wave);
+    uint32_t blocks = blocks_for(tiles < slots ? tiles : slots);
+    if (cap != 0u && blocks > cap) blocks = cap;
+    return blocks;
 }
 
 }  // namespace ndq

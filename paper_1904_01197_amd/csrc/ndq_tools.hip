@@ -419,11 +419,9 @@ static int sqdiff_common(const float* a, const float* b, size_t n, double* parti
     if (((uintptr_t)partial & 7u) || ((uintptr_t)out & 7u)) return NDQ_EALIGN;
     if (n != 0 && (!aligned16(a) || !aligned16(b))) return NDQ_EALIGN;
     hipStream_t s = (hipStream_t)stream;
-    hipLaunchKernelGGL(sqdiff_partial_kernel, dim3(kSqBlocks), dim3(256), 0, s, a, b, (uint64_t)n,
-                       partial);
-    if (launched() != NDQ_OK) return NDQ_ELAUNCH;
-    hipLaunchKernelGGL(sqdiff_final_kernel, dim3(1), dim3(256), 0, s, (const double*)partial, out);
-    return launched();
+    if (launch(sqdiff_partial_kernel, dim3(kSqBlocks), dim3(256), s, a, b, (uint64_t)n, partial) != NDQ_OK)
+        return NDQ_ELAUNCH;
+    return launch(sqdiff_final_kernel, dim3(1), dim3(256), s, (const double*)partial, out);
 }
 
 }  // namespace ndq
@@ -450,16 +448,16 @@ int ndq_code_entropy(const void* codes, size_t n, uint32_t bits, uint64_t* hist_
     if (n != 0 && !aligned16(codes)) return NDQ_EALIGN;
     hipStream_t s = (hipStream_t)stream;
     const uint32_t nbins = 1u << bits;
-    hipLaunchKernelGGL(fill_zero64_kernel, dim3(1), dim3(256), 0, s, (unsigned long long*)hist_out, nbins);
-    if (launched() != NDQ_OK) return NDQ_ELAUNCH;
+    if (launch(fill_zero64_kernel, dim3(1), dim3(256), s, (unsigned long long*)hist_out, nbins) != NDQ_OK)
+        return NDQ_ELAUNCH;
     if (n != 0 && bits <= 2u) {
         const uint64_t vectors = ((uint64_t)n * bits) >> 7;
         uint64_t blocks = (vectors + kSmallInFlight * kSmallThreads - 1) / (kSmallInFlight * kSmallThreads);
         if (blocks > kSmallBlocks) blocks = kSmallBlocks;
         if (blocks == 0u) blocks = 1u;
-        hipLaunchKernelGGL(histogram_small_kernel, dim3((uint32_t)blocks), dim3(kSmallThreads), 0, s,
-                           (const uint4*)codes, (uint64_t)n, bits, (unsigned long long*)hist_out);
-        if (launched() != NDQ_OK) return NDQ_ELAUNCH;
+        if (launch(histogram_small_kernel, dim3((uint32_t)blocks), dim3(kSmallThreads), s, (const uint4*)codes,
+                   (uint64_t)n, bits, (unsigned long long*)hist_out) != NDQ_OK)
+            return NDQ_ELAUNCH;
     } else if (n != 0) {
         const uint64_t units = (uint64_t)n >> 5;
         uint64_t blocks = (units + kHistThreads - 1) / kHistThreads;
@@ -468,21 +466,22 @@ int ndq_code_entropy(const void* codes, size_t n, uint32_t bits, uint64_t* hist_
         const dim3 grid((uint32_t)blocks), block(kHistThreads);
         const uint32_t* words = (const uint32_t*)codes;
         unsigned long long* h = (unsigned long long*)hist_out;
+        int rc_hist;
         switch (bits) {
-        case 3: hipLaunchKernelGGL(histogram_kernel<3>, grid, block, 0, s, words, (uint64_t)n, h); break;
-        case 4: hipLaunchKernelGGL(histogram_kernel<4>, grid, block, 0, s, words, (uint64_t)n, h); break;
-        case 5: hipLaunchKernelGGL(histogram_kernel<5>, grid, block, 0, s, words, (uint64_t)n, h); break;
-        case 6: hipLaunchKernelGGL(histogram_kernel<6>, grid, block, 0, s, words, (uint64_t)n, h); break;
-        case 7: hipLaunchKernelGGL(histogram_kernel<7>, grid, block, 0, s, words, (uint64_t)n, h); break;
-        default: hipLaunchKernelGGL(histogram_kernel<8>, grid, block, 0, s, words, (uint64_t)n, h); break;
+        case 3: rc_hist = launch(histogram_kernel<3>, grid, block, s, words, (uint64_t)n, h); break;
+        case 4: rc_hist = launch(histogram_kernel<4>, grid, block, s, words, (uint64_t)n, h); break;
+        case 5: rc_hist = launch(histogram_kernel<5>, grid, block, s, words, (uint64_t)n, h); break;
+        case 6: rc_hist = launch(histogram_kernel<6>, grid, block, s, words, (uint64_t)n, h); break;
+        case 7: rc_hist = launch(histogram_kernel<7>, grid, block, s, words, (uint64_t)n, h); break;
+        default: rc_hist = launch(histogram_kernel<8>, grid, block, s, words, (uint64_t)n, h); break;
         }
-        if (launched() != NDQ_OK) return NDQ_ELAUNCH;
+        if (rc_hist != NDQ_OK) return NDQ_ELAUNCH;
     }
     const int derive_bin0 = n != 0 && bits <= 2u;
     if (entropy_out || derive_bin0) {
-        hipLaunchKernelGGL(entropy_kernel, dim3(1), dim3(256), 0, s, (unsigned long long*)hist_out, nbins,
-                           (uint64_t)n, entropy_out, derive_bin0);
-        if (launched() != NDQ_OK) return NDQ_ELAUNCH;
+        if (launch(entropy_kernel, dim3(1), dim3(256), s, (unsigned long long*)hist_out, nbins, (uint64_t)n,
+                   entropy_out, derive_bin0) != NDQ_OK)
+            return NDQ_ELAUNCH;
     }
     return NDQ_OK;
 }
@@ -531,9 +530,8 @@ static int dense_common(const void* fixed, const void* dense, size_t n, uint32_t
     const uint64_t blocks = (threads + 255u) / 256u;
     if (blocks >= ((uint64_t)1 << 31)) return NDQ_EUNSUPPORTED;
     if (per_thread_bytes > kDenseThreadBytes) return NDQ_EUNSUPPORTED;   // cannot happen for levels <= 256
-    if (pack) hipLaunchKernelGGL(dense_pack_kernel, dim3((uint32_t)blocks), dim3(kDenseBlock), 0, (hipStream_t)stream, a);
-    else hipLaunchKernelGGL(dense_unpack_kernel, dim3((uint32_t)blocks), dim3(kDenseBlock), 0, (hipStream_t)stream, a);
-    return launched();
+    if (pack) return launch(dense_pack_kernel, dim3((uint32_t)blocks), dim3(kDenseBlock), (hipStream_t)stream, a);
+    return launch(dense_unpack_kernel, dim3((uint32_t)blocks), dim3(kDenseBlock), (hipStream_t)stream, a);
 }
 
 int ndq_dense_pack(const void* codes, size_t n, uint32_t levels, void* dense_out, void* stream)

@@ -174,7 +174,16 @@ def ndq_nested_encode(g, delta, levels, M, alpha, bucket, d, codes_out=None, ste
     return codes_out, steps_out
 
 
+def _check_message(codes, steps, n, bits, bucket):
+    """A worker's message must be as large as the call will read."""
+    if codes.numel() * codes.element_size() < ndq_packed_bytes(n, bits):
+        raise ValueError("codes hold fewer than ndq_packed_bytes(n, bits) bytes")
+    if steps.dtype != torch.float32 or steps.numel() < ndq_num_buckets(n, bucket):
+        raise ValueError("steps must hold ndq_num_buckets(n, bucket) float32")
+
+
 def ndq_dq_decode(codes, n, levels, bucket, steps, d, out=None, accumulate=False):
+    _check_message(codes, steps, n, ndq_code_bits(levels), bucket)
     if out is None:
         if accumulate:
             raise ValueError("accumulate needs an existing out")
@@ -188,6 +197,7 @@ def ndq_dq_decode(codes, n, levels, bucket, steps, d, out=None, accumulate=False
 
 
 def ndq_dq_decode_half(codes, n, levels, bucket, steps, out=None, accumulate=False):
+    _check_message(codes, steps, n, ndq_code_bits(levels), bucket)
     if out is None:
         if accumulate:
             raise ValueError("accumulate needs an existing out")
@@ -202,11 +212,12 @@ def ndq_dq_decode_half(codes, n, levels, bucket, steps, out=None, accumulate=Fal
 
 def ndq_nested_decode(codes, n, M, alpha, bucket, steps, d, side, side_scale=1.0, out=None,
                       accumulate=False):
+    _check_message(codes, steps, n, ndq_code_bits(M), bucket)
     if out is None:
         if accumulate:
             raise ValueError("accumulate needs an existing out")
         out = torch.empty(n, dtype=torch.float32, device=codes.device)
-    if out.dtype != torch.float32 or out.numel() < n or side.dtype != torch.float32:
+    if out.dtype != torch.float32 or out.numel() < n or side.dtype != torch.float32 or side.numel() < n:
         raise ValueError("out and side must hold n float32")
     _check(lib().ndq_nested_decode(_dev(codes, "codes"), n, M, alpha, bucket, _dev(steps, "steps"),
                                    C.byref(d), _dev(side, "side"), side_scale, _dev(out, "out"),
@@ -233,6 +244,7 @@ def ndq_decode_chain(workers, n, bucket, scale=1.0, out=None):
     arr = (ndq_worker * len(workers))()
     for i, wk in enumerate(workers):
         codes, steps, kind, arg, d = wk[:5]
+        _check_message(codes, steps, n, ndq_code_bits(arg), bucket)
         arr[i].codes = _dev(codes, "codes").value
         arr[i].steps = _dev(steps, "steps").value
         arr[i].kind = kind
@@ -251,6 +263,8 @@ def ndq_decode_chain(workers, n, bucket, scale=1.0, out=None):
 def ndq_code_entropy(codes, n, bits, hist_out=None, entropy_out=None):
     """-> (histogram int64 tensor of 2^bits counts, entropy float64 tensor of 1 element)"""
     dev = codes.device
+    if n and codes.numel() * codes.element_size() < ndq_packed_bytes(n, bits):
+        raise ValueError("codes hold fewer than ndq_packed_bytes(n, bits) bytes")
     if hist_out is None:
         hist_out = torch.empty(1 << bits, dtype=torch.int64, device=dev)
     if entropy_out is None:
