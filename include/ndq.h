@@ -66,6 +66,9 @@
 extern "C" {
 #endif
 
+/* Element types of a gradient vector.  The entry points take the value as a plain
+ * int, so that a caller's out-of-range value is an NDQ_EINVAL, not an enum load
+ * outside its enumerators. */
 typedef enum { NDQ_F32 = 0, NDQ_BF16 = 1 } ndq_dtype;
 
 typedef enum {
@@ -103,8 +106,8 @@ size_t ndq_num_buckets(size_t n, uint32_t bucket);
 
 /* Max-norm scale factors kappa_b = max |g_i| per bucket (Sec. 3.1 eq. (2): the
  * scale factor kappa = ||g||_inf; Algorithm 1 worker step "kappa_p").
- * g: n elements of type dt.  kappa_out: ndq_num_buckets(n, bucket) floats. */
-int ndq_absmax(const void* g, ndq_dtype dt, size_t n, uint32_t bucket, float* kappa_out,
+ * g: n elements of type dt (an ndq_dtype value).  kappa_out: ndq_num_buckets(n, bucket) floats. */
+int ndq_absmax(const void* g, int dt, size_t n, uint32_t bucket, float* kappa_out,
                void* stream);
 
 /* Worker side of Algorithm 1 (generate dither, quantization index, send kappa and
@@ -119,7 +122,7 @@ int ndq_absmax(const void* g, ndq_dtype dt, size_t n, uint32_t bucket, float* ka
  * twice.)
  * steps_out: ndq_num_buckets(n, bucket) floats -- the transmitted scale factors
  * (Delta_b = 2 kappa_b/(L-1) travels in place of kappa_b: the same 32 bits). */
-int ndq_dq_encode(const void* g, ndq_dtype dt, size_t n, float delta, uint32_t levels,
+int ndq_dq_encode(const void* g, int dt, size_t n, float delta, uint32_t levels,
                   uint32_t bucket, const ndq_dither* d, void* codes_out, float* steps_out,
                   void* stream);
 
@@ -144,7 +147,7 @@ int ndq_dq_decode_half(const void* codes, size_t n, uint32_t levels, uint32_t bu
  * shrinkage factor of Sec. 3.2 (1 = plain nested quantization); the index is
  * rint(fma(g_i, a, v_i)) with a = alpha * (1/Delta_b) formed once per bucket.
  * codes_out: ndq_packed_bytes(n, ndq_code_bits(M)) bytes. */
-int ndq_nested_encode(const void* g, ndq_dtype dt, size_t n, float delta, uint32_t levels,
+int ndq_nested_encode(const void* g, int dt, size_t n, float delta, uint32_t levels,
                       uint32_t M, float alpha, uint32_t bucket, const ndq_dither* d,
                       void* codes_out, float* steps_out, void* stream);
 

@@ -556,7 +556,7 @@ static int run_encode(const EncodeArgs& a, bool fused, bool multi, uint32_t buck
     return launch((encode_kernel<DT, MODE, false, false, false>), grid, block, s, a);
 }
 
-static int encode_common(const void* g, ndq_dtype dt, size_t n, float delta, uint32_t levels,
+static int encode_common(const void* g, int dt, size_t n, float delta, uint32_t levels,
                          uint32_t M, bool nested, float alpha, uint32_t bucket, const ndq_dither* d,
                          void* codes_out, float* steps_out, void* stream)
 {
@@ -633,7 +633,7 @@ static int encode_common(const void* g, ndq_dtype dt, size_t n, float delta, uin
 
 extern "C" {
 
-int ndq_absmax(const void* g, ndq_dtype dt, size_t n, uint32_t bucket, float* kappa_out,
+int ndq_absmax(const void* g, int dt, size_t n, uint32_t bucket, float* kappa_out,
                void* stream)
 {
     using namespace ndq;
@@ -656,7 +656,7 @@ int ndq_absmax(const void* g, ndq_dtype dt, size_t n, uint32_t bucket, float* ka
     return dt == NDQ_F32 ? run_absmax<0>(g, tl, K, kappa_out, s) : run_absmax<1>(g, tl, K, kappa_out, s);
 }
 
-int ndq_dq_encode(const void* g, ndq_dtype dt, size_t n, float delta, uint32_t levels,
+int ndq_dq_encode(const void* g, int dt, size_t n, float delta, uint32_t levels,
                   uint32_t bucket, const ndq_dither* d, void* codes_out, float* steps_out,
                   void* stream)
 {
@@ -664,7 +664,7 @@ int ndq_dq_encode(const void* g, ndq_dtype dt, size_t n, float delta, uint32_t l
                               steps_out, stream);
 }
 
-int ndq_nested_encode(const void* g, ndq_dtype dt, size_t n, float delta, uint32_t levels,
+int ndq_nested_encode(const void* g, int dt, size_t n, float delta, uint32_t levels,
                       uint32_t M, float alpha, uint32_t bucket, const ndq_dither* d,
                       void* codes_out, float* steps_out, void* stream)
 {

@@ -544,12 +544,12 @@ def test_config5_diagnostics_clip_and_coset_error_fractions():
     assert np.array_equal(out, ref)
 
 
-def test_config5_full_size_sampled_slices():
+def test_config5_full_size_whole_vectors():
     """Config 5 at its full size (n = 2^27 per worker) in the launch configuration
     the benchmark times (all encodes, then the fused server loop) and in the
-    call-by-call one: the GPU processes the whole vectors; the oracle recomputes
-    bucket-aligned slices (first, last, and a spread of others) from the same
-    input bytes with the matching dither offset and must agree bit for bit."""
+    call-by-call one: the GPU processes the whole vectors and so does the oracle
+    (on bucket-aligned slices, sixteen at a time); every code byte, every step and
+    every one of the 2^27 outputs must agree bit for bit."""
     wl = workloads.CONFIGS[5]
     n = wl.n
     host = workloads.gradients(wl, n, threads=16)
@@ -559,22 +559,14 @@ def test_config5_full_size_sampled_slices():
     out = pipeline.step_fused(wl, dev, bufs, ds_g)
     torch.cuda.synchronize()
     seeds = [workloads.dither_seed(wl, w) for w in range(wl.W)]
-    span = 16 * wl.bucket
-    starts = [0, n - span] + [int(x) // wl.bucket * wl.bucket
-                              for x in np.linspace(span, n - 2 * span, 10)]
-    for lo in starts:
-        hi = lo + span
-        ds_o = opipe.dithers(wl.W, seeds, offset=lo)
-        sl = [h[lo:hi] for h in host]
-        c_ref, s_ref, _ = opipe.encode_all(wl.plan, wl.fine_levels, wl.bucket, False, sl, ds_o)
-        for w, (kind, arg) in enumerate(wl.plan):
-            bits = oracle.code_bits(arg)
-            got_c = bufs.codes[w][lo * bits // 8:hi * bits // 8].cpu().numpy()
-            assert got_c.tobytes() == c_ref[w][:span * bits // 8].tobytes(), (lo, w)
-            got_s = bufs.steps[w][lo // wl.bucket:hi // wl.bucket].cpu().numpy()
-            assert np.array_equal(got_s, s_ref[w]), (lo, w)
-        ref = opipe.decode_chain(wl.plan, wl.bucket, span, c_ref, s_ref, ds_o, wl.out_scale)
-        assert np.array_equal(out[lo:hi].cpu().numpy(), ref), lo
+    threads = min(16, os.cpu_count() or 1)
+    c_ref, s_ref, ref = opipe.step_sliced(wl.plan, wl.fine_levels, wl.bucket, host, seeds, wl.out_scale,
+                                          threads=threads)
+    for w in range(wl.W):
+        assert bufs.codes[w].cpu().numpy().tobytes() == c_ref[w].tobytes(), ("codes", w)
+        assert np.array_equal(bufs.steps[w].cpu().numpy(), s_ref[w]), ("steps", w)
+    assert np.array_equal(out.cpu().numpy(), ref)
+    del c_ref, s_ref, ref
     # properties that hold at any size, checked on all 2^27 elements with device-side
     # tensor arithmetic: the DQSG reconstruction error of worker 0 is within half a
     # step except where the index saturated (about 1e-4 of the elements), has mean 0

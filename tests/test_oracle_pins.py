@@ -971,3 +971,31 @@ def test_averaging_workers_reduces_quantization_noise_by_W():
     avg = oracle.aggregate(outs, 1.0 / W)
     var = np.mean((avg.astype(np.float64) - g) ** 2)
     assert abs(var / (float(s[0]) ** 2 / 12 / W) - 1) < 0.03
+
+
+def test_sliced_step_equals_the_step_over_whole_vectors():
+    """The helper that runs a bucketed iteration on bucket-aligned slices (several at a
+    time) must give the bytes of one call over everything: the path is elementwise
+    apart from the per-bucket max-norm, and the dither depends on the element index."""
+    from oracle import pipeline as opipe
+    from paper_1904_01197_amd import workloads
+    wl = workloads.CONFIGS[5]
+    n = 4096 * 37 + 4096 - 56          # a ragged last bucket
+    host = workloads.gradients(wl, n)
+    seeds = [workloads.dither_seed(wl, w) for w in range(wl.W)]
+    ds = opipe.dithers(wl.W, seeds, step=2)
+    c, s, _ = opipe.encode_all(wl.plan, wl.fine_levels, wl.bucket, False, host, ds)
+    ref, idx = opipe.decode_chain(wl.plan, wl.bucket, n, c, s, ds, wl.out_scale, True)
+    for threads, slice_buckets in ((1, 5), (3, 8), (4, 64)):
+        c2, s2, o2, diag = opipe.step_sliced(wl.plan, wl.fine_levels, wl.bucket, host, seeds, wl.out_scale,
+                                             threads=threads, slice_buckets=slice_buckets, diagnostics=True,
+                                             step=2)
+        assert all(a.tobytes() == b.tobytes() for a, b in zip(c, c2))
+        assert all(np.array_equal(a, b) for a, b in zip(s, s2))
+        assert np.array_equal(ref, o2)
+        q0 = oracle.fine_indices(host[0], wl.bucket, s[0], ds[0])
+        L = wl.plan[0][1]
+        assert diag["clip_fraction"] == [np.count_nonzero((q0 < -(L // 2)) | (q0 > -(L // 2) + L - 1)) / n]
+        wrong = [np.count_nonzero(idx[w] != oracle.fine_indices(host[w], wl.bucket, s[w], ds[w])) / n
+                 for w in range(1, wl.W)]
+        assert diag["coset_error_fraction"] == wrong
