@@ -462,8 +462,7 @@ struct ChainCodes { uint32_t w[kChainRows]; float step; };
 
 // a lane's eight codes of a row: `WIDTH` bytes at a multiple of WIDTH (full tiles)
 template <int WIDTH>
-__device__ __forceinline__ void stream_fetch(const unsigned char* codes, const float* steps, uint64_t start,
-                                             uint32_t bucket, int lane, ChainCodes& f)
+__device__ __forceinline__ void stream_fetch(const unsigned char* codes, uint64_t start, int lane, ChainCodes& f)
 {
     const unsigned char* mine = codes + (start >> 3) * WIDTH + (uint32_t)lane * WIDTH;
 #pragma unroll
@@ -471,7 +470,7 @@ __device__ __forceinline__ void stream_fetch(const unsigned char* codes, const f
         const unsigned char* p = mine + (uint32_t)(r * kWave) * WIDTH;
         f.w[r] = WIDTH == 1 ? (uint32_t)*p : WIDTH == 2 ? (uint32_t)*(const uint16_t*)p : *(const uint32_t*)p;
     }
-    f.step = steps[bucket];
+    f.step = 0.0f;     // whole tiles take their steps from the step lanes of the kernel
 }
 
 // The same for the vector's ragged last tile of `len` elements: a lane fetches its bytes
@@ -494,8 +493,8 @@ __device__ __forceinline__ void stream_fetch_ragged(const unsigned char* codes, 
 
 template <int MODE, int WIDTH, bool FIRST>
 __device__ __forceinline__ void stream_fold(const DitherStream& ds, uint64_t block0, float q_min_f,
-                                            float side_scale, const ChainCodes& f, int lane,
-                                            float (&S)[kChainRows][8])
+                                            float side_scale, const ChainCodes& f, float step, float inv,
+                                            int lane, float (&S)[kChainRows][8])
 {
     constexpr int NF = WIDTH == 4 ? 4 : 8;
     // a power-of-two nesting ratio is 2^(code width): M and 1/M are compile-time constants
@@ -506,7 +505,6 @@ __device__ __forceinline__ void stream_fold(const DitherStream& ds, uint64_t blo
 #pragma unroll
         for (int j = 0; j < NF; ++j) { field.scale[j] *= inv_M_f; field.offset[j] *= inv_M_f; }
     }
-    const float step = f.step, inv = inv_step(step);
 #pragma unroll
     for (int r = 0; r < kChainRows; ++r) {
         const uint32_t o = (uint32_t)(r * kWave + lane) * kLaneElems;
@@ -545,14 +543,15 @@ __device__ __forceinline__ void stream_ragged_tile(ChainArgsPtr a, uint64_t star
     if (W > 1u) stream_fetch_ragged<WR>(a->w[1].codes, a->w[1].steps, start, len, bucket, lane, nxt);
     {
         const DitherStream ds = {a->w[0].ds.key0, a->w[0].ds.key1, a->w[0].ds.step, a->w[0].ds.worker};
-        stream_fold<kDq, W0, true>(ds, (a->w[0].index0 + start) >> 3, (float)a->w[0].q_min, 0.0f, cur, lane, S);
+        stream_fold<kDq, W0, true>(ds, (a->w[0].index0 + start) >> 3, (float)a->w[0].q_min, 0.0f, cur, cur.step,
+                                   inv_step(cur.step), lane, S);
     }
     cur = nxt;
     for (uint32_t w = 1; w < W; ++w) {
         if (w + 1u < W) stream_fetch_ragged<WR>(a->w[w + 1u].codes, a->w[w + 1u].steps, start, len, bucket, lane, nxt);
         const DitherStream ds = {a->w[w].ds.key0, a->w[w].ds.key1, a->w[w].ds.step, a->w[w].ds.worker};
         stream_fold<RMODE, WR, false>(ds, (a->w[w].index0 + start) >> 3, (float)a->w[w].q_min, a->w[w].side_scale,
-                                      cur, lane, S);
+                                      cur, cur.step, inv_step(cur.step), lane, S);
         cur = nxt;
     }
     float* out = a->out + start;
@@ -577,7 +576,8 @@ void chain_stream_kernel(ChainArgs a_by_value)
     const ChainArgsPtr a = (ChainArgsPtr)__builtin_amdgcn_kernarg_segment_ptr();
     const int lane = threadIdx.x & (kWave - 1);
     const uint32_t stride = gridDim.x * kWavesPerBlock;
-    const uint32_t first = blockIdx.x * kWavesPerBlock + __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const uint32_t wave_in_block = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const uint32_t first = blockIdx.x * kWavesPerBlock + wave_in_block;
     const uint32_t tiles = a->tile_begin;                  // whole tiles: ids 0 .. tiles-1
     const uint32_t W = a->W;
     const uint32_t tpb = a->tl.tiles_per_bucket;
@@ -597,39 +597,55 @@ void chain_stream_kernel(ChainArgs a_by_value)
     if (my_tiles > 1u) __builtin_amdgcn_s_setprio(3);
 
     ChainCodes cur;
-    stream_fetch<W0>(a->w[0].codes, a->w[0].steps, (uint64_t)first * kChainTile, one_bucket ? 0u : first / tpb, lane, cur);
+    stream_fetch<W0>(a->w[0].codes, (uint64_t)first * kChainTile, lane, cur);
+    // Lane w looks after worker w's step: one load and ONE correctly rounded division per tile
+    // for all workers (at most 32, one per lane), instead of one per worker in every lane; a
+    // worker's step and reciprocal are then read from its lane into scalar registers.
+    const uint32_t my_worker = (uint32_t)lane < W ? (uint32_t)lane : W - 1u;
+    const float* my_steps = a->w[my_worker].steps;
+    float steps_ahead = my_steps[one_bucket ? 0u : first / tpb];
     for (uint32_t tile = first; tile < tiles; tile += stride) {
         const uint64_t start = (uint64_t)tile * kChainTile;
-        const uint32_t bucket = one_bucket ? 0u : tile / tpb;
         float S[kChainRows][8];
         ChainCodes nxt;
+        const float steps_here = steps_ahead;
+        {
+            const uint32_t nt = tile + stride < tiles ? tile + stride : tile;
+            steps_ahead = my_steps[one_bucket ? 0u : nt / tpb];
+        }
+        const float invs_here = inv_step(steps_here);
+        auto from_lane = [](float x, uint32_t w) __attribute__((always_inline)) {
+            return __uint_as_float((uint32_t)__builtin_amdgcn_readlane((int)__float_as_uint(x), (int)w));
+        };
         // first worker: DQSG, starts the sum; meanwhile the second worker's codes (or the next tile's)
         if (W > 1u) {
-            stream_fetch<WR>(a->w[1].codes, a->w[1].steps, start, bucket, lane, nxt);
+            stream_fetch<WR>(a->w[1].codes, start, lane, nxt);
         } else {
             const uint32_t nt = tile + stride < tiles ? tile + stride : tile;
             ChainCodes tmp;
-            stream_fetch<W0>(a->w[0].codes, a->w[0].steps, (uint64_t)nt * kChainTile, one_bucket ? 0u : nt / tpb, lane, tmp);
+            stream_fetch<W0>(a->w[0].codes, (uint64_t)nt * kChainTile, lane, tmp);
             nxt = tmp;
         }
         {
             const DitherStream ds = {a->w[0].ds.key0, a->w[0].ds.key1, a->w[0].ds.step, a->w[0].ds.worker};
-            stream_fold<kDq, W0, true>(ds, (a->w[0].index0 + start) >> 3, (float)a->w[0].q_min, 0.0f, cur, lane, S);
+            stream_fold<kDq, W0, true>(ds, (a->w[0].index0 + start) >> 3, (float)a->w[0].q_min, 0.0f, cur,
+                                       from_lane(steps_here, 0u), 0.0f, lane, S);
         }
         cur = nxt;
         for (uint32_t w = 1; w < W; ++w) {
             // the codes of worker w are in `cur`; fetch worker w+1's, or the first worker's of the next tile
             if (w + 1u < W) {
-                stream_fetch<WR>(a->w[w + 1u].codes, a->w[w + 1u].steps, start, bucket, lane, nxt);
+                stream_fetch<WR>(a->w[w + 1u].codes, start, lane, nxt);
             } else {
                 const uint32_t nt = tile + stride < tiles ? tile + stride : tile;
                 ChainCodes tmp;
-                stream_fetch<W0>(a->w[0].codes, a->w[0].steps, (uint64_t)nt * kChainTile, one_bucket ? 0u : nt / tpb, lane, tmp);
+                stream_fetch<W0>(a->w[0].codes, (uint64_t)nt * kChainTile, lane, tmp);
                 nxt = tmp;
             }
             const DitherStream ds = {a->w[w].ds.key0, a->w[w].ds.key1, a->w[w].ds.step, a->w[w].ds.worker};
             stream_fold<RMODE, WR, false>(ds, (a->w[w].index0 + start) >> 3, (float)a->w[w].q_min,
-                                          a->w[w].side_scale, cur, lane, S);
+                                          a->w[w].side_scale, cur, from_lane(steps_here, w), from_lane(invs_here, w),
+                                          lane, S);
             cur = nxt;
         }
         float* out = out_base + start;

@@ -456,6 +456,16 @@ __device__ __forceinline__ float wave_max(float x)
     return __uint_as_float((uint32_t)(m01 > m23 ? m01 : m23));
 }
 
+// Orders a wave's own LDS traffic: what its lanes wrote before is visible to all
+// of its lanes after (a wave's LDS instructions execute in order; the fences keep
+// the compiler from moving accesses across).
+__device__ __forceinline__ void wave_lds_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 // Tile geometry.  A vector is cut into buckets (one step each; bucket == 0: the
 // whole vector) and every bucket into tiles of at most `tile` elements, so that
 // a tile never straddles two steps.  One wave owns one tile.

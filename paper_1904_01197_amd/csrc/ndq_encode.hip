@@ -254,7 +254,7 @@ void encode_kernel(EncodeArgs a)
         const float kappa = (FUSED && !MULTI) ? tile_max<DT>(regs) : 0.0f;
         encode_tile<DT, MODE, FUSED, false, MULTI>(a, t, tile_id, regs, kappa, true, stage, lane);
     }
-    __syncthreads();
+    wave_lds_sync();     // a wave copies out only the stage it filled itself
     if (t.len != 0) {
         const uint64_t byte0 = (t.start >> 3) * bits;                 // tile start is a multiple of 64
         const bool last = t.start + t.len == a.tl.n;
@@ -264,16 +264,6 @@ void encode_kernel(EncodeArgs a)
         const uint64_t* src = (const uint64_t*)stage;
         for (uint32_t u = lane; u < units; u += kWave) dst[u] = src[u];
     }
-}
-
-// Orders a wave's own LDS traffic: what its lanes wrote before is visible to all
-// of its lanes after (a wave's LDS instructions execute in order; the fences keep
-// the compiler from moving accesses across).
-__device__ __forceinline__ void wave_lds_sync()
-{
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
 // Copies a tile's packed codes from the wave's stage to the stream, 8 bytes per lane.
