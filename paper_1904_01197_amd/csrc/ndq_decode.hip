@@ -499,17 +499,16 @@ __device__ __forceinline__ void stream_fold(const DitherStream& ds, uint64_t blo
     constexpr int NF = WIDTH == 4 ? 4 : 8;
     // a power-of-two nesting ratio is 2^(code width): M and 1/M are compile-time constants
     constexpr float M_f = (float)(1u << WIDTH), inv_M_f = 1.0f / M_f;
-    // DQSG: the index q = c + q_min; nested: m' = c / M (scale and offset divided by M)
-    FieldAsFloat<NF> field((uint32_t)WIDTH, MODE == kDq ? q_min_f : 0.0f);
-    if (MODE != kDq) {
-#pragma unroll
-        for (int j = 0; j < NF; ++j) { field.scale[j] *= inv_M_f; field.offset[j] *= inv_M_f; }
-    }
+    // DQSG: the code c itself, the index offset q_min going into the dither instead:
+    // (c + q_min) - v and c - (v - q_min) are the same exact value rounded once, and
+    // v - q_min is exact for |q_min| <= 8 (code widths up to 4 bits).  Nested: m' = c / M.
+    const FieldScaled<NF> field((uint32_t)WIDTH, MODE == kDq ? 0u : (uint32_t)WIDTH);
 #pragma unroll
     for (int r = 0; r < kChainRows; ++r) {
         const uint32_t o = (uint32_t)(r * kWave + lane) * kLaneElems;
         float v[8];
-        dither8(ds, block0 + (o >> 3), v);
+        if (MODE == kDq) dither8_shifted(ds, block0 + (o >> 3), -q_min_f, v);
+        else dither8(ds, block0 + (o >> 3), v);
         const uint32_t lo = f.w[r], hi = WIDTH == 4 ? f.w[r] >> 16 : f.w[r];
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
@@ -527,6 +526,106 @@ __device__ __forceinline__ void stream_fold(const DitherStream& ds, uint64_t blo
             }
             S[r][k] = FIRST ? val : S[r][k] + val;
         }
+    }
+}
+
+// The same fold of one row with its instructions in a fixed order, and one Philox
+// block (the dither of a later row) advanced by its ten rounds in between.  On
+// gfx950 a binary32 add / multiply / fma issued right after a quarter-rate
+// instruction (the 32x32 multiply, the round-to-integer) costs next to nothing,
+// and alternating integer and float instructions issue faster than runs of
+// either (measured with fixed instruction patterns); the compiler's own order
+// has the Philox rounds in one run and the float arithmetic in another.  The
+// values are those of stream_fold: the same operations on the same operands,
+// only their order in the program differs.  Per element the float stages are
+// 0: v = unit dither of the cell (DQSG: minus q_min)   1: code field -> c (DQSG) or m' = m/M (nested)
+// DQSG    2: c - v   3: Delta * (...)   4: S + (...)
+// nested  2: y = S * (1/count)   3: c = fma(y, 1/Delta, v)   4: fma(c, 1/M, -m')
+//         [round to integer]     5: + m'   6: fma(q', M, -v)   7: Delta * (...)   8: S + (...)
+template <int MODE, int WIDTH, bool FIRST>
+__device__ __forceinline__ void fold_row_piped(const uint32_t (&words)[4], uint32_t code, float step, float inv,
+                                               float side_scale, float q_min_f, float (&S)[8], PhiloxFlight& fl)
+{
+    constexpr int NF = WIDTH == 4 ? 4 : 8;
+    constexpr float M_f = (float)(1u << WIDTH), inv_M_f = 1.0f / M_f;
+    const FieldScaled<NF> field((uint32_t)WIDTH, MODE == kDq ? 0u : (uint32_t)WIDTH);
+    // DQSG: the index offset q_min goes into the dither (see stream_fold)
+    const float centre = (MODE == kDq ? -q_min_f : 0.0f) + (-0.5f + 0x1p-17f);
+    const uint32_t lo = code, hi = WIDTH == 4 ? code >> 16 : code;
+    float v[8], m[8], w[8];
+    // float stages of an element, in order; nested: the round-to-integer sits between stages 4 and 5
+    constexpr int kStages = MODE == kDq ? (FIRST ? 4 : 5) : 9;
+    auto stage = [&](int st, int k) __attribute__((always_inline)) {
+        const int j = NF == 8 ? k : (k & 3);
+        if (st == 0) { v[k] = __builtin_fmaf(v[k], 0x1p-16f, centre); return; }   // unit_dither (shifted)
+        if (st == 1) { m[k] = field.finish(m[k], j); return; }
+        if (MODE == kDq) {
+            if (st == 2) w[k] = m[k] - v[k];
+            if (st == 3) { w[k] = step * w[k]; if (FIRST) S[k] = w[k]; }
+            if (st == 4) S[k] = S[k] + w[k];
+        } else {
+            if (st == 2) w[k] = S[k] * side_scale;
+            if (st == 3) w[k] = __builtin_fmaf(w[k], inv, v[k]);
+            if (st == 4) w[k] = __builtin_fmaf(w[k], inv_M_f, -m[k]);
+            if (st == 5) w[k] = w[k] + m[k];
+            if (st == 6) w[k] = __builtin_fmaf(w[k], M_f, -v[k]);
+            if (st == 7) w[k] = step * w[k];
+            if (st == 8) S[k] = S[k] + w[k];
+        }
+    };
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        const uint32_t word = words[k >> 1];
+        v[k] = (float)((k & 1) ? word >> 16 : word & 0xFFFFu);
+        m[k] = field.raw(NF == 8 ? lo : (k < 4 ? lo : hi), NF == 8 ? k : (k & 3));
+        NDQ_PIN();
+    }
+    constexpr int kInRounds = (MODE == kDq ? kStages : 5) * 8;
+#pragma unroll
+    for (int round = 0; round < 10; ++round) {
+        const int s0 = 4 * round;
+        fl.mul0();
+        if (s0 + 0 < kInRounds) stage((s0 + 0) >> 3, (s0 + 0) & 7);
+        NDQ_PIN();
+        fl.mul1();
+        if (s0 + 1 < kInRounds) stage((s0 + 1) >> 3, (s0 + 1) & 7);
+        NDQ_PIN();
+        fl.mix0();
+        if (s0 + 2 < kInRounds) stage((s0 + 2) >> 3, (s0 + 2) & 7);
+        NDQ_PIN();
+        fl.mix1();
+        fl.next_round();
+        if (s0 + 3 < kInRounds) stage((s0 + 3) >> 3, (s0 + 3) & 7);
+        NDQ_PIN();
+    }
+    if (MODE != kDq) {
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            w[k] = __builtin_rintf(w[k]);
+            if (k > 0) stage(5, k - 1);
+            NDQ_PIN();
+        }
+        stage(5, 7);
+#pragma unroll
+        for (int st = 6; st < kStages; ++st)
+#pragma unroll
+            for (int k = 0; k < 8; ++k) stage(st, k);
+    }
+}
+
+template <int MODE, int WIDTH, bool FIRST>
+__device__ __forceinline__ void stream_fold_piped(const DitherStream& ds, uint64_t block0, const DitherStream& ds_next,
+                                                  uint64_t block_next, float q_min_f, float side_scale,
+                                                  const ChainCodes& f, float step, float inv,
+                                                  float (&S)[kChainRows][8], PhiloxFlight& fl)
+{
+#pragma unroll
+    for (int r = 0; r < kChainRows; ++r) {
+        uint32_t words[4];
+        fl.words(words);
+        if (r + 1 < kChainRows) fl.start(ds, block0 + (uint32_t)((r + 1) * kWave));
+        else fl.start(ds_next, block_next);
+        fold_row_piped<MODE, WIDTH, FIRST>(words, f.w[r], step, inv, side_scale, q_min_f, S[r], fl);
     }
 }
 
@@ -569,15 +668,34 @@ __device__ __forceinline__ void stream_ragged_tile(ChainArgsPtr a, uint64_t star
 // RAGGED: the vector ends in a ragged tile.  An instantiation of its own, because the mere
 // presence of that code in the kernel measured 6 % on the main loop (config 5, which has
 // no ragged tile: 215 against 203 us) although the loop's instructions are the same.
-template <int RMODE, int W0, int WR, bool RAGGED>
-__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(kChainStreamWaves, kChainStreamWaves)))
+//
+// PIPED (persistent launches of whole tiles): two changes that only pay together.
+// (1) A lane's eight consecutive results are 32 bytes of the output, so a 16-byte store per
+// lane writes every other 16 bytes of a 2 KB span, and such half-written sectors sustain only
+// 2.6 TB/s: with the arithmetic taken out the stores alone took as long as the whole kernel
+// (206 us at n = 2^27; 105 us when every store writes 1 KB of consecutive bytes).  The tile
+// therefore leaves through the wave's 4 KB of LDS as four stores of consecutive bytes.
+// (2) stream_fold_piped: the fold's instructions in a fixed order with the next row's Philox
+// block advanced in between (7 % fewer issue cycles; hidden behind the stores until (1)).
+// It starts one extra Philox block per wave, which only a wave with many tiles amortises,
+// and the LDS round trip costs a one-tile wave more than the stores do, so launches of one
+// tile per wave keep the plain form.
+#ifndef NDQ_CHAIN_PIPED_WAVES
+#define NDQ_CHAIN_PIPED_WAVES NDQ_CHAIN_STREAM_WAVES
+#endif
+template <int RMODE, int W0, int WR, bool RAGGED, bool PIPED>
+__global__ __launch_bounds__(kBlock)
+__attribute__((amdgpu_waves_per_eu(PIPED ? NDQ_CHAIN_PIPED_WAVES : kChainStreamWaves, PIPED ? NDQ_CHAIN_PIPED_WAVES : kChainStreamWaves)))
 void chain_stream_kernel(ChainArgs a_by_value)
 {
+    static_assert(!(RAGGED && PIPED), "the ragged tile is folded by the plain form only");
     const ChainArgsPtr a = (ChainArgsPtr)__builtin_amdgcn_kernarg_segment_ptr();
     const int lane = threadIdx.x & (kWave - 1);
     const uint32_t stride = gridDim.x * kWavesPerBlock;
     const uint32_t wave_in_block = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     const uint32_t first = blockIdx.x * kWavesPerBlock + wave_in_block;
+    __shared__ __align__(16) float out_stage_all[PIPED ? kWavesPerBlock : 1][PIPED ? kChainTile : 4];
+    float* out_stage = out_stage_all[PIPED ? wave_in_block : 0u];
     const uint32_t tiles = a->tile_begin;                  // whole tiles: ids 0 .. tiles-1
     const uint32_t W = a->W;
     const uint32_t tpb = a->tl.tiles_per_bucket;
@@ -598,6 +716,13 @@ void chain_stream_kernel(ChainArgs a_by_value)
 
     ChainCodes cur;
     stream_fetch<W0>(a->w[0].codes, (uint64_t)first * kChainTile, lane, cur);
+    // PIPED: the dither of the row after the current one is always in flight; here the first row's
+    PhiloxFlight fl;
+    if (PIPED) {
+        const DitherStream ds = {a->w[0].ds.key0, a->w[0].ds.key1, a->w[0].ds.step, a->w[0].ds.worker};
+        fl.start(ds, ((a->w[0].index0 + (uint64_t)first * kChainTile) >> 3) + (uint32_t)lane);
+        fl.run();
+    }
     // Lane w looks after worker w's step: one load and ONE correctly rounded division per tile
     // for all workers (at most 32, one per lane), instead of one per worker in every lane; a
     // worker's step and reciprocal are then read from its lane into scalar registers.
@@ -606,6 +731,8 @@ void chain_stream_kernel(ChainArgs a_by_value)
     float steps_ahead = my_steps[one_bucket ? 0u : first / tpb];
     for (uint32_t tile = first; tile < tiles; tile += stride) {
         const uint64_t start = (uint64_t)tile * kChainTile;
+        // where the dither after this tile's last row belongs: past the end after the last tile (unused)
+        const uint64_t next_start = start + (uint64_t)stride * kChainTile;
         float S[kChainRows][8];
         ChainCodes nxt;
         const float steps_here = steps_ahead;
@@ -628,8 +755,16 @@ void chain_stream_kernel(ChainArgs a_by_value)
         }
         {
             const DitherStream ds = {a->w[0].ds.key0, a->w[0].ds.key1, a->w[0].ds.step, a->w[0].ds.worker};
-            stream_fold<kDq, W0, true>(ds, (a->w[0].index0 + start) >> 3, (float)a->w[0].q_min, 0.0f, cur,
-                                       from_lane(steps_here, 0u), 0.0f, lane, S);
+            if (PIPED) {
+                const uint32_t wn = W > 1u ? 1u : 0u;
+                const DitherStream dn = {a->w[wn].ds.key0, a->w[wn].ds.key1, a->w[wn].ds.step, a->w[wn].ds.worker};
+                stream_fold_piped<kDq, W0, true>(ds, ((a->w[0].index0 + start) >> 3) + (uint32_t)lane, dn,
+                                                 ((a->w[wn].index0 + (W > 1u ? start : next_start)) >> 3) + (uint32_t)lane,
+                                                 (float)a->w[0].q_min, 0.0f, cur, from_lane(steps_here, 0u), 0.0f, S, fl);
+            } else {
+                stream_fold<kDq, W0, true>(ds, (a->w[0].index0 + start) >> 3, (float)a->w[0].q_min, 0.0f, cur,
+                                           from_lane(steps_here, 0u), 0.0f, lane, S);
+            }
         }
         cur = nxt;
         for (uint32_t w = 1; w < W; ++w) {
@@ -643,9 +778,19 @@ void chain_stream_kernel(ChainArgs a_by_value)
                 nxt = tmp;
             }
             const DitherStream ds = {a->w[w].ds.key0, a->w[w].ds.key1, a->w[w].ds.step, a->w[w].ds.worker};
-            stream_fold<RMODE, WR, false>(ds, (a->w[w].index0 + start) >> 3, (float)a->w[w].q_min,
-                                          a->w[w].side_scale, cur, from_lane(steps_here, w), from_lane(invs_here, w),
-                                          lane, S);
+            if (PIPED) {
+                const bool last = w + 1u == W;
+                const uint32_t wn = last ? 0u : w + 1u;
+                const DitherStream dn = {a->w[wn].ds.key0, a->w[wn].ds.key1, a->w[wn].ds.step, a->w[wn].ds.worker};
+                stream_fold_piped<RMODE, WR, false>(ds, ((a->w[w].index0 + start) >> 3) + (uint32_t)lane, dn,
+                                                    ((a->w[wn].index0 + (last ? next_start : start)) >> 3) + (uint32_t)lane,
+                                                    (float)a->w[w].q_min, a->w[w].side_scale, cur,
+                                                    from_lane(steps_here, w), from_lane(invs_here, w), S, fl);
+            } else {
+                stream_fold<RMODE, WR, false>(ds, (a->w[w].index0 + start) >> 3, (float)a->w[w].q_min,
+                                              a->w[w].side_scale, cur, from_lane(steps_here, w),
+                                              from_lane(invs_here, w), lane, S);
+            }
             cur = nxt;
         }
         float* out = out_base + start;
@@ -656,8 +801,22 @@ void chain_stream_kernel(ChainArgs a_by_value)
 #pragma unroll
                 for (int k = 0; k < 8; ++k) S[r][k] = scale * S[r][k];
             }
-            store_streaming(out + o, S[r][0], S[r][1], S[r][2], S[r][3]);
-            store_streaming(out + o + 4, S[r][4], S[r][5], S[r][6], S[r][7]);
+            if (PIPED) {
+                *(float4*)(out_stage + o) = make_float4(S[r][0], S[r][1], S[r][2], S[r][3]);
+                *(float4*)(out_stage + o + 4) = make_float4(S[r][4], S[r][5], S[r][6], S[r][7]);
+            } else {
+                store_streaming(out + o, S[r][0], S[r][1], S[r][2], S[r][3]);
+                store_streaming(out + o + 4, S[r][4], S[r][5], S[r][6], S[r][7]);
+            }
+        }
+        if (PIPED) {
+            wave_lds_sync();
+#pragma unroll
+            for (int j = 0; j < (int)(kChainTile / (kWave * 4)); ++j) {
+                const float4 x = *(const float4*)(out_stage + j * (kWave * 4) + lane * 4);
+                store_streaming(out + j * (kWave * 4) + lane * 4, x.x, x.y, x.z, x.w);
+            }
+            wave_lds_sync();     // the next tile's writes come after these reads
         }
         // the arbiter serves the oldest wave of a SIMD first: lower a wave's priority as it
         // gets ahead, so that the waves of a SIMD finish together
@@ -787,11 +946,12 @@ static int launch_chain_stream(const ChainArgs& a, hipStream_t s)
     // per wave a fixed share would leave SIMDs idle at the end.
     const uint32_t tiles = a.tile_begin, slots = 1024u * kChainStreamWaves;
     const bool ragged = (uint64_t)tiles * kChainTile < a.tl.n;     // one more wave takes the ragged last tile
-    const uint32_t blocks = tiles >= stream_tuning().chain_min_tiles_per_wave * slots
-                                ? persistent_blocks(tiles, slots)
-                                : blocks_for(tiles + (ragged ? 1u : 0u));
-    if (ragged) return launch((chain_stream_kernel<RMODE, W0, WR, true>), dim3(blocks), dim3(kBlock), s, a);
-    return launch((chain_stream_kernel<RMODE, W0, WR, false>), dim3(blocks), dim3(kBlock), s, a);
+    const bool persistent = tiles >= stream_tuning().chain_min_tiles_per_wave * slots;
+    const uint32_t blocks = persistent ? persistent_blocks(tiles, ragged ? slots : 1024u * NDQ_CHAIN_PIPED_WAVES)
+                                       : blocks_for(tiles + (ragged ? 1u : 0u));
+    if (ragged) return launch((chain_stream_kernel<RMODE, W0, WR, true, false>), dim3(blocks), dim3(kBlock), s, a);
+    if (persistent) return launch((chain_stream_kernel<RMODE, W0, WR, false, true>), dim3(blocks), dim3(kBlock), s, a);
+    return launch((chain_stream_kernel<RMODE, W0, WR, false, false>), dim3(blocks), dim3(kBlock), s, a);
 }
 
 template <int RMODE, int W0>

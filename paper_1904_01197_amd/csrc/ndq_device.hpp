@@ -73,6 +73,43 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
     out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
 }
 
+// Nothing is scheduled across this point: the instruction order of the source is
+// the order of the program.
+#define NDQ_PIN() __builtin_amdgcn_sched_barrier(0)
+
+// One Philox block advanced a piece at a time, so that the caller can place other
+// work between the pieces: a round is mul0, mul1, mix0, mix1, next_round in that
+// order (each mix needs both products' owner words untouched: mul0 before mix0,
+// mul1 before mix1).  After ten rounds words() are those of philox4x32_10.
+struct PhiloxFlight {
+    uint32_t c0, c1, c2, c3, k0, k1;
+    uint64_t p0, p1;
+    __device__ __forceinline__ void start(const DitherStream& s, uint64_t block)
+    {
+        c0 = (uint32_t)block; c1 = (uint32_t)(block >> 32); c2 = s.step; c3 = s.worker;
+        k0 = s.key0; k1 = s.key1;
+    }
+    // the 32x32->64 multiply as the one instruction it is (left to the compiler it becomes a
+    // high and a low multiply once the two halves are used in different pinned regions)
+    static __device__ __forceinline__ uint64_t wide_mul(uint32_t constant, uint32_t x)
+    {
+        uint64_t p;
+        asm("v_mad_u64_u32 %0, vcc, %1, %2, 0" : "=v"(p) : "s"(constant), "v"(x) : "vcc");
+        return p;
+    }
+    __device__ __forceinline__ void mul0() { p0 = wide_mul(0xD2511F53u, c0); }
+    __device__ __forceinline__ void mul1() { p1 = wide_mul(0xCD9E8D57u, c2); }
+    __device__ __forceinline__ void mix0() { c0 = xor3((uint32_t)(p1 >> 32), c1, k0); c1 = (uint32_t)p1; }
+    __device__ __forceinline__ void mix1() { c2 = xor3((uint32_t)(p0 >> 32), c3, k1); c3 = (uint32_t)p0; }
+    __device__ __forceinline__ void next_round() { k0 += 0x9E3779B9u; k1 += 0xBB67AE85u; }
+    __device__ __forceinline__ void run()
+    {
+#pragma unroll
+        for (int round = 0; round < 10; ++round) { mul0(); mul1(); mix0(); mix1(); next_round(); }
+    }
+    __device__ __forceinline__ void words(uint32_t (&r)[4]) const { r[0] = c0; r[1] = c1; r[2] = c2; r[3] = c3; }
+};
+
 // Mid-point of cell `cell` of 2^16 equal cells of [-1/2, 1/2): exact in binary32.
 __device__ __forceinline__ float unit_dither(uint32_t cell)
 {
@@ -91,6 +128,24 @@ __device__ __forceinline__ void dither8(const DitherStream& s, uint64_t block, f
     for (int w = 0; w < 4; ++w) {
         v[2 * w] = unit_dither(r[w] & 0xFFFFu);
         v[2 * w + 1] = unit_dither(r[w] >> 16);
+    }
+}
+
+// The same plus an integer `shift` with |shift| <= 8: v + shift needs at most 21
+// significant bits, so the one fma that forms it is as exact as unit_dither's.
+__device__ __forceinline__ float unit_dither_shifted(uint32_t cell, float centre)   // centre = shift - 1/2 + 2^-17
+{
+    return __builtin_fmaf((float)cell, 0x1p-16f, centre);
+}
+__device__ __forceinline__ void dither8_shifted(const DitherStream& s, uint64_t block, float shift, float (&v)[8])
+{
+    uint32_t r[4];
+    philox4x32_10((uint32_t)block, (uint32_t)(block >> 32), s.step, s.worker, s.key0, s.key1, r);
+    const float centre = shift + (-0.5f + 0x1p-17f);
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        v[2 * w] = unit_dither_shifted(r[w] & 0xFFFFu, centre);
+        v[2 * w + 1] = unit_dither_shifted(r[w] >> 16, centre);
     }
 }
 
@@ -253,6 +308,35 @@ struct FieldAsFloat {
     }
 };
 constexpr uint32_t kFieldAsFloatMaxBits = 5;   // four fields of a group stay inside 23 bits
+
+// The same with the field masked into the mantissa of 2^(23 - j b - s) instead of
+// 2^23: that float is 2^(23-jb-s) + c 2^-s exactly, and subtracting a constant
+// (2^(23-jb-s) - constant, an exact float) leaves c 2^-s + constant, again with
+// no rounding.  The per-field constants are then an operand of the bit operation
+// (scalar register) and a literal of the subtraction: none of them occupies a
+// vector register, where FieldAsFloat keeps one offset per field.  Used with a
+// compile-time width; s = log2 of a power-of-two divisor (0: none).
+template <int NF>
+struct FieldScaled {
+    uint32_t mask[NF], base[NF];
+    float minus[NF];
+    __device__ __forceinline__ FieldScaled(uint32_t bits, uint32_t s, float constant = 0.0f)
+    {
+#pragma unroll
+        for (uint32_t j = 0; j < (uint32_t)NF; ++j) {
+            mask[j] = ((1u << bits) - 1u) << (j * bits);
+            base[j] = (150u - j * bits - s) << 23;
+            minus[j] = __uint_as_float(base[j]) - constant;
+        }
+    }
+    // the two halves of get(): the masked field inside its power of two, and its value
+    __device__ __forceinline__ float raw(uint32_t group, int j) const
+    {
+        return __uint_as_float(__builtin_amdgcn_bitop3_b32(group, mask[j], base[j], 0xEA));   // (group & mask) | base
+    }
+    __device__ __forceinline__ float finish(float x, int j) const { return x - minus[j]; }
+    __device__ __forceinline__ float get(uint32_t group, int j) const { return finish(raw(group, j), j); }
+};
 
 // Coset decoder of eq. (8), alpha = 1: the integer congruent to m (mod M) nearest
 // to y/Delta + v, returned as a float.  m + M*k is formed by one fma: exact while

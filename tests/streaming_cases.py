@@ -84,7 +84,9 @@ def chain_cases():
         ((("dq", 4), ("dq", 2)), 4, 3072, 0.5, False),
     ]
     for plan, fine, bucket, scale, shared in plans:
-        for n in (1024 * 12, 1024 * 37 + 100, 1024 * 150 + 1023, 1024 * 3 + 8):
+        # whole tiles only (the hand-ordered fold with results staged through LDS: one, several
+        # and unequal numbers of tiles per wave), then ragged ends (the plain fold)
+        for n in (1024 * 12, 1024 * 40, 1024 * 129, 1024 * 37 + 100, 1024 * 150 + 1023, 1024 * 3 + 8):
             print("chain", plan, bucket, n, flush=True)
             rng = np.random.default_rng(n + len(plan))
             common = rng.standard_normal(n) * 0.01
