@@ -92,12 +92,14 @@ def chain_cases():
             common = rng.standard_normal(n) * 0.01
             host = [(common + rng.standard_normal(n) * 0.002).astype(F) for _ in plan]
             seeds = [7 + w for w in range(len(plan))]
-            ds_o = opipe.dithers(len(plan), seeds, step=3)
+            # the call is a slice of a longer vector: its first element is element `offset` of the dither stream
+            offset = 8 * (n % 4099)
+            ds_o = opipe.dithers(len(plan), seeds, step=3, offset=offset)
             c_ref, s_ref, _ = opipe.encode_all(plan, fine, bucket, shared, host, ds_o)
             ref = opipe.decode_chain(plan, bucket, n, c_ref, s_ref, ds_o, scale)
             workers = [(torch.from_numpy(c_ref[w]).cuda(), torch.from_numpy(s_ref[w]).cuda(),
                         ndq.NDQ_WORKER_DQ if kind == "dq" else ndq.NDQ_WORKER_NESTED, arg,
-                        ndq.ndq_dither(seeds[w], 3, w, 0)) for w, (kind, arg) in enumerate(plan)]
+                        ndq.ndq_dither(seeds[w], 3, w, offset)) for w, (kind, arg) in enumerate(plan)]
             out = ndq.ndq_decode_chain(workers, n, bucket, scale)
             assert np.array_equal(out.cpu().numpy(), ref), (plan, n)
             count += 1
