@@ -9,6 +9,8 @@
 // between the waves of a workgroup.
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include "ndq.h"
 #include "ndq_device.hpp"
 #include "ndq_host.hpp"
@@ -75,15 +77,19 @@ __device__ __forceinline__ float tile_max(const TileRegs<DT>& regs)
 // step comes from `kappa`, the max-norm of the tile's bucket, found in registers.
 // MULTI (with FUSED): the bucket is a whole number of rows and several buckets
 // share the tile, each with its own step.
-template <int DT, int MODE, bool FUSED, bool FULL, bool MULTI, int BITSW = 0>
+// REFILL: as soon as a row is quantized its registers are loaded again, with the same row of
+// the whole tile at `refill` (lane `refill_lane`'s share), so that one set of registers holds
+// the current tile and, by the end, the next one.
+template <int DT, int MODE, bool FUSED, bool FULL, bool MULTI, int BITSW = 0, bool REFILL = false>
 __device__ __forceinline__ void encode_tile(const EncodeArgs& a, const TileRef& t, uint32_t tile_id,
-                                            const TileRegs<DT>& regs, float kappa, bool writes_step,
-                                            unsigned char* stage, int lane)
+                                            typename std::conditional<REFILL, TileRegs<DT>, const TileRegs<DT>>::type& regs,
+                                            float kappa, bool writes_step, unsigned char* stage, int lane,
+                                            const void* refill = nullptr, int refill_lane = 0)
 {
     using T = Elem<DT>;
     constexpr int ROWS = EncRows<DT>::R;
     const uint32_t bits = BITSW ? (uint32_t)BITSW : a.qp.bits;   // BITSW: the code width, known at compile time
-    const typename T::Row (&raw)[ROWS] = regs.row;
+    auto& raw = regs.row;
 
     // 1/step per row (alpha/step for a nested worker that shrinks), wave-uniform
     float inv_row[ROWS];
@@ -193,6 +199,8 @@ __device__ __forceinline__ void encode_tile(const EncodeArgs& a, const TileRef& 
             default:
                 for (uint32_t k = 0; k < bits; ++k) p[k] = (unsigned char)(chunk8 >> (8 * k));
         }
+        if constexpr (REFILL)
+            raw[r] = load_row<DT, true>(refill, (uint32_t)(r * kWave + refill_lane) * kLaneElems, EncTile<DT>::N);
     }
     if (lane == 0) *(uint64_t*)(stage + (size_t)EncTile<DT>::N / 8 * bits) = 0;  // pad unit
 }
@@ -301,17 +309,25 @@ __device__ __forceinline__ void stage_to_stream_full(const EncodeArgs& a, const 
 // ---------------------------------------------------------------------------
 // Streaming encoder for vectors made of whole tiles (bucket == tile with the
 // max-norm found in registers, or one step for the whole vector): every wave
-// walks over the tiles wave, wave + W, wave + 2W, ... (W = waves in the grid) and
-// keeps the NEXT tile's loads in flight in a second set of registers while it
-// quantizes the current one.  No wave is ever new: the instruction arbiter serves
-// older waves first, so in a one-tile-per-wave grid a new wave crawls through its
-// address arithmetic, its loads and its max-norm behind seven busy neighbours,
-// and the SIMD idles whenever those neighbours run out at the same time.
+// walks over the tiles wave, wave + W, wave + 2W, ... (W = waves in the grid).
+// One set of registers holds the current tile and, by the end of it, the next
+// one: as soon as a row is quantized its registers are loaded again with the
+// same row of the wave's next tile, so the loads leave one row at a time
+// instead of a tile at a time, and a row has the rest of the tile's arithmetic
+// (the first) down to the copy-out (the last) to arrive.  Measured against two
+// register sets with the whole next tile requested at the start of the current
+// one: 49.7 against 52.6 us (1-bit nested) and 57.5 against 59.9 us (2-bit
+// DQSG) at 2^27 bfloat16 elements; with the registers this frees, 5, 6 or 8
+// waves per SIMD are slower than 4 (55, 55, 54 us), and so are 3 and 2.
+// No wave is ever new: the instruction arbiter serves older waves first, so in
+// a one-tile-per-wave grid a new wave crawls through its address arithmetic,
+// its loads and its max-norm behind busy neighbours, and the SIMD idles
+// whenever those neighbours run out at the same time.
 // ---------------------------------------------------------------------------
 #ifndef NDQ_STREAM_WAVES
 #define NDQ_STREAM_WAVES 4
 #endif
-constexpr int kStreamWaves = NDQ_STREAM_WAVES;   // per SIMD: two tiles of registers per wave
+constexpr int kStreamWaves = NDQ_STREAM_WAVES;   // per SIMD
 
 template <int DT>
 __device__ __forceinline__ TileRef stream_tile_ref(const EncodeArgs& a, uint32_t tile_id, bool fused)
@@ -321,18 +337,6 @@ __device__ __forceinline__ TileRef stream_tile_ref(const EncodeArgs& a, uint32_t
     t.len = EncTile<DT>::N;
     t.bucket = fused ? tile_id : 0u;
     return t;
-}
-
-template <int DT, int MODE, bool FUSED, int BITSW>
-__device__ __forceinline__ void stream_one(const EncodeArgs& a, uint32_t tile_id, const TileRegs<DT>& regs,
-                                           unsigned char* stage, int lane)
-{
-    const TileRef t = stream_tile_ref<DT>(a, tile_id, FUSED);
-    const float kappa = FUSED ? tile_max<DT>(regs) : 0.0f;
-    wave_lds_sync();     // the previous tile's copy-out has read the stage
-    encode_tile<DT, MODE, FUSED, true, false, BITSW>(a, t, tile_id, regs, kappa, true, stage, lane);
-    wave_lds_sync();
-    stage_to_stream_full<DT, BITSW>(a, t, stage, lane);
 }
 
 template <int DT, int MODE, bool FUSED, int BITSW>
@@ -348,12 +352,12 @@ void encode_stream_kernel(EncodeArgs a, uint32_t full_tiles)
     const uint32_t first = blockIdx.x * kWavesPerBlock + wave;
     if (!FUSED && a.preset_step > 0.0f && first == 0u && lane == 0) a.steps[0] = a.preset_step;
     if (first < full_tiles) {
-        // Two register sets, ra and rb.  Every pass issues exactly eight loads before it
-        // waits for the other set, also the last one (then eight loads of the vector's
-        // first 16 bytes per row, all lanes alike: one cache line, no traffic to speak of),
-        // so that the count of loads in flight at every wait is known at compile time and
-        // a wait for the current tile never covers the prefetch.
-        TileRegs<DT> ra, rb;
+        // Every pass over a tile issues exactly one load per row, also the last one (then of the
+        // vector's first 16 bytes per row, all lanes alike: one cache line, no traffic to speak
+        // of), and the code width is a compile-time constant, so that the number of memory
+        // operations in flight at every wait is known at compile time: they complete in order,
+        // and a wait must cover a row's load but not the loads and stores issued after it.
+        TileRegs<DT> regs;
         uint32_t cur = first;
         // The arbiter serves the oldest wave of a SIMD first, so left alone the waves of a
         // SIMD finish one after the other and the last one runs alone, at a third of the
@@ -361,24 +365,24 @@ void encode_stream_kernel(EncodeArgs a, uint32_t full_tiles)
         const uint32_t my_tiles = (full_tiles - first + stride - 1) / stride;
         uint32_t done = 0;
         __builtin_amdgcn_s_setprio(3);
-#define NDQ_FAIR_STEP() do { ++done; const uint32_t q = 4u * done / my_tiles; \
-            if (q == 1u) __builtin_amdgcn_s_setprio(2); else if (q == 2u) __builtin_amdgcn_s_setprio(1); \
-            else if (q >= 3u) __builtin_amdgcn_s_setprio(0); } while (0)
-        load_tile<DT, true>(a.g, stream_tile_ref<DT>(a, cur, FUSED), lane, ra);
+        load_tile<DT, true>(a.g, stream_tile_ref<DT>(a, cur, FUSED), lane, regs);
         for (;;) {
-            uint32_t nxt = cur + stride;
-            bool more = nxt < full_tiles;
-            load_tile<DT, true>(a.g, stream_tile_ref<DT>(a, more ? nxt : 0u, FUSED), more ? lane : 0, rb);
-            stream_one<DT, MODE, FUSED, BITSW>(a, cur, ra, stage, lane);
+            const uint32_t nxt = cur + stride;
+            const bool more = nxt < full_tiles;
+            const TileRef t = stream_tile_ref<DT>(a, cur, FUSED);
+            const float kappa = FUSED ? tile_max<DT>(regs) : 0.0f;
+            wave_lds_sync();     // the previous tile's copy-out has read the stage
+            encode_tile<DT, MODE, FUSED, true, false, BITSW, true>(
+                a, t, cur, regs, kappa, true, stage, lane,
+                (const typename Elem<DT>::scalar*)a.g + (uint64_t)(more ? nxt : 0u) * TILE, more ? lane : 0);
+            wave_lds_sync();
+            stage_to_stream_full<DT, BITSW>(a, t, stage, lane);
             if (!more) break;
-            NDQ_FAIR_STEP();
-            cur = nxt;
-            nxt = cur + stride;
-            more = nxt < full_tiles;
-            load_tile<DT, true>(a.g, stream_tile_ref<DT>(a, more ? nxt : 0u, FUSED), more ? lane : 0, ra);
-            stream_one<DT, MODE, FUSED, BITSW>(a, cur, rb, stage, lane);
-            if (!more) break;
-            NDQ_FAIR_STEP();
+            ++done;
+            const uint32_t quarter = 4u * done / my_tiles;
+            if (quarter == 1u) __builtin_amdgcn_s_setprio(2);
+            else if (quarter == 2u) __builtin_amdgcn_s_setprio(1);
+            else if (quarter >= 3u) __builtin_amdgcn_s_setprio(0);
             cur = nxt;
         }
     }
