@@ -116,7 +116,7 @@ struct StreamTuning {
 inline const StreamTuning& stream_tuning()
 {
     static const StreamTuning t = [] {
-        StreamTuning v = {8u, 12u, 0u};
+        StreamTuning v = {2u, 3u, 0u};     // measured: config 5 at 2^25 elements, encoders -3..-5 %, chain -5 % against 8 and 12
         if (const char* e = getenv("NDQ_STREAM_MIN_TILES_PER_WAVE")) {
             v.enc_min_tiles_per_wave = v.chain_min_tiles_per_wave = (uint32_t)strtoul(e, nullptr, 10);
         }
