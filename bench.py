@@ -322,6 +322,37 @@ def main():
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / reps   # ms
 
+    # The brackets above put an event before and after every call; the event itself costs a few
+    # microseconds between two kernels, which a 50 us encoder shows and a 200 us decoder hides.
+    # Second figure per kernel: the same call launched back to back inside ONE pair of events,
+    # an encoder reading another worker's vector every time (no input is still in a cache) and
+    # writing to buffers of its own.
+    alone_reps = max(4, min(args.kernel_reps, 24))
+    for rec in kernels:
+        group = [c for c in calls if c[0] == rec["kernel"]]
+        if rec["kernel"].startswith(("dq_encode", "nested_encode")):
+            w0 = next(w for w, c in enumerate(calls[:wl.W]) if c[0] == rec["kernel"])
+            arg = wl.plan[w0][1]
+            out_c, out_s = torch.empty_like(bufs.codes[w0]), torch.empty_like(bufs.steps[w0])
+            if wl.plan[w0][0] == "dq":
+                fns = [lambda w=w: ndq.ndq_dq_encode(dev[w], preset, arg, wl.bucket, ds[w0], out_c, out_s)
+                       for w in range(wl.W)]
+            else:
+                fns = [lambda w=w: ndq.ndq_nested_encode(dev[w], preset, wl.fine_levels, arg, 1.0, wl.bucket,
+                                                         ds[w0], out_c, out_s) for w in range(wl.W)]
+        else:
+            fns = [c[1] for c in group]
+        turn = [0]
+
+        def rotate(fns=fns, turn=turn):
+            fns[turn[0] % len(fns)]()
+            turn[0] += 1
+        ms = timed(rotate, alone_reps)
+        rec["alone_ms"] = round(ms, 5)
+        rec["alone_GBps"] = round(rec["algorithmic_bytes"] / (ms * 1e-3) / 1e9, 1)
+    one_step()     # the in-place decoders above have run out of turn: leave the buffers as a step leaves them
+    torch.cuda.synchronize()
+
     dominant = max(kernels, key=lambda r: r["avg_ms"] * r["launches_per_step"])
     sec = dominant["avg_ms"] * 1e-3
     hbm_frac = dominant["algorithmic_bytes"] / sec / 1e9 / HBM_PEAK_GBS
@@ -516,6 +547,9 @@ def main():
         "coset_error_fraction": diagnostics["coset_error_fraction"] if diagnostics else None,
         "kernels": kernels,
         "kernel_ms_sum_per_step": round(sum(r["avg_ms"] * r["launches_per_step"] for r in kernels), 4),
+        "kernels_note": "avg_ms: an event before and after every call inside whole steps (carries about 3 us of event "
+                        "handling per call); alone_ms: the call launched back to back inside one pair of events, "
+                        "encoders reading another worker's vector each time",
         "other_schedule": {
             "schedule": other, "ms_per_step": round(other_ms, 4),
             "value": round(grad_bytes / (other_ms * 1e-3) / 1e9, 2),
