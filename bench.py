@@ -171,7 +171,8 @@ def main():
     ds = pipeline.dithers(wl)
     preset = 0.0
     if wl.shared_step:   # the shared step is a preset (read back once, outside the timed region)
-        preset = pipeline.encode_all(wl, dev, bufs, ds)
+        pipeline.encode_all(wl, dev, bufs, ds)
+        preset = float(bufs.steps[0][0].item())
     torch.cuda.synchronize()
     gen_s = time.time() - t0
 

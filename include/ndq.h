@@ -22,7 +22,7 @@
  *     checked before anything is launched: with NDQ_EINVAL, NDQ_EALIGN or
  *     NDQ_EUNSUPPORTED nothing has been enqueued.  NDQ_ELAUNCH comes from the
  *     runtime's launch call itself; calls made of several kernels (a max-norm
- *     pass before the encoder, ndq_code_entropy, ndq_sqdiff, more than 32 workers
+ *     pass or a step copy before the encoder, ndq_code_entropy, ndq_sqdiff, more than 32 workers
  *     in ndq_decode_chain / ndq_aggregate) may then already have enqueued their
  *     first kernels, and the outputs are unspecified.  n == 0 is a successful no-op.
  *   - g, codes, out and side must be 16-byte aligned; steps 4-byte aligned.
@@ -150,6 +150,23 @@ int ndq_dq_decode_half(const void* codes, size_t n, uint32_t levels, uint32_t bu
 int ndq_nested_encode(const void* g, int dt, size_t n, float delta, uint32_t levels,
                       uint32_t M, float alpha, uint32_t bucket, const ndq_dither* d,
                       void* codes_out, float* steps_out, void* stream);
+
+/* ndq_dq_encode / ndq_nested_encode with one step for the whole vector that already
+ * lies in DEVICE memory: Algorithms 1 and 2 are written for steps Delta (Delta_1,
+ * Delta_2) that all workers and the server share (their initialisation), and the
+ * natural source of such a step is the steps_out of the worker that chose it.  The
+ * call reads *step_in when its kernels run, so no device-to-host copy sits between
+ * the two encode calls.  Codes: exactly those of the call above with bucket == 0 and
+ * delta == *step_in; for *step_in == 0 every fine index is 0 (1/Delta := 0, as for an
+ * all-zero vector).  *step_in must be finite and >= 0; this is not checked.
+ * step_in: one float (device, 4-byte aligned).  steps_out: one float, set to
+ * *step_in (step_in == steps_out is allowed).  The nested form takes no `levels`:
+ * that argument only ever served to derive a step. */
+int ndq_dq_encode_with_step(const void* g, int dt, size_t n, const float* step_in, uint32_t levels,
+                            const ndq_dither* d, void* codes_out, float* steps_out, void* stream);
+int ndq_nested_encode_with_step(const void* g, int dt, size_t n, const float* step_in, uint32_t M,
+                                float alpha, const ndq_dither* d, void* codes_out, float* steps_out,
+                                void* stream);
 
 /* Server side of Algorithm 2 for a worker of group P2 (eq. (8)).
  * The side information is y_i = side[i] * side_scale, so `side` may be the

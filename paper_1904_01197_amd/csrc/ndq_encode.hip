@@ -482,6 +482,12 @@ __global__ void steps_from_kappa_kernel(float* steps, uint64_t K, uint32_t level
     if (b < K) steps[b] = step_from_kappa(steps[b], levels);
 }
 
+// A step that already lies in device memory becomes this worker's transmitted step.
+__global__ void copy_step_kernel(const float* step_in, float* steps)
+{
+    if (threadIdx.x == 0 && blockIdx.x == 0) steps[0] = step_in[0];
+}
+
 // ---------------------------------------------------------------------------
 // Host side: dispatch
 // ---------------------------------------------------------------------------
@@ -561,9 +567,11 @@ static int run_encode(const EncodeArgs& a, bool fused, bool multi, uint32_t buck
     return launch((encode_kernel<DT, MODE, false, false, false>), grid, block, s, a);
 }
 
-static int encode_common(const void* g, int dt, size_t n, float delta, uint32_t levels,
-                         uint32_t M, bool nested, float alpha, uint32_t bucket, const ndq_dither* d,
-                         void* codes_out, float* steps_out, void* stream)
+// step_in != nullptr: one step for the whole vector, read from device memory when the
+// kernels run (bucket and delta are then 0, and `levels` is not used to derive a step).
+static int encode_common(const void* g, int dt, size_t n, float delta, const float* step_in,
+                         uint32_t levels, uint32_t M, bool nested, float alpha, uint32_t bucket,
+                         const ndq_dither* d, void* codes_out, float* steps_out, void* stream)
 {
     EncodeArgs a;
     int rc = make_quant(levels, M, nested, alpha, &a.qp);
@@ -575,6 +583,7 @@ static int encode_common(const void* g, int dt, size_t n, float delta, uint32_t 
     if (!(delta == delta)) return NDQ_EINVAL;
     if (n >= kMaxN) return NDQ_EUNSUPPORTED;
     if (!aligned16(g) || !aligned16(codes_out) || !aligned4(steps_out)) return NDQ_EALIGN;
+    if (step_in && !aligned4(step_in)) return NDQ_EALIGN;
     if (bucket % 64u != 0u || (d->offset & 7u) != 0u) return NDQ_EALIGN;
 
     const uint32_t tile = dt == NDQ_F32 ? EncTile<0>::N : EncTile<1>::N;
@@ -600,7 +609,12 @@ static int encode_common(const void* g, int dt, size_t n, float delta, uint32_t 
     hipStream_t s = (hipStream_t)stream;
 
     const bool fused = (bucket != 0u && bucket <= tile) || block_fused;   // (multi implies fused)
-    if (!fused && a.preset_step == 0.0f) {
+    if (step_in) {
+        // the kernels read steps_out[0], as after the max-norm passes below
+        if (step_in != steps_out &&
+            launch(copy_step_kernel, dim3(1), dim3(kWave), s, step_in, steps_out) != NDQ_OK)
+            return NDQ_ELAUNCH;
+    } else if (!fused && a.preset_step == 0.0f) {
         // two passes: max-norm per bucket, then steps, then the encoder reads them
         const uint64_t K = bucket ? (n + bucket - 1) / bucket : 1;
         rc = dt == NDQ_F32 ? run_absmax<0>(g, a.tl, K, steps_out, s)
@@ -613,11 +627,11 @@ static int encode_common(const void* g, int dt, size_t n, float delta, uint32_t 
 #ifndef NDQ_NARROW_MAX_BITS
 #define NDQ_NARROW_MAX_BITS 6u
 #endif
-    // a step derived from the data bounds |g/Delta|; a caller's preset step does not
+    // a step derived from the data bounds |g/Delta|; a caller's step (preset, or in device memory) does not
+    const bool own_step = a.preset_step == 0.0f && !step_in;
     const int mode = !nested ? (a.qp.bits <= NDQ_NARROW_MAX_BITS ? kDqNarrow : kDq)
-                             : (!is_pow2(M) ? ((a.preset_step > 0.0f || a.qp.bits > 6u) ? kNestedAnyM
-                                                                                       : kNestedAnyMBounded)
-                                            : (a.preset_step > 0.0f ? kNestedPow2 : kNestedPow2Bounded));
+                             : (!is_pow2(M) ? ((!own_step || a.qp.bits > 6u) ? kNestedAnyM : kNestedAnyMBounded)
+                                            : (!own_step ? kNestedPow2 : kNestedPow2Bounded));
     if (dt == NDQ_F32) {
         if (mode == kDqNarrow) return run_encode<0, kDqNarrow>(a, fused, multi, bucket, s);
         if (mode == kDq) return run_encode<0, kDq>(a, fused, multi, bucket, s);
@@ -665,7 +679,15 @@ int ndq_dq_encode(const void* g, int dt, size_t n, float delta, uint32_t levels,
                   uint32_t bucket, const ndq_dither* d, void* codes_out, float* steps_out,
                   void* stream)
 {
-    return ndq::encode_common(g, dt, n, delta, levels, 0u, false, 1.0f, bucket, d, codes_out,
+    return ndq::encode_common(g, dt, n, delta, nullptr, levels, 0u, false, 1.0f, bucket, d, codes_out,
+                              steps_out, stream);
+}
+
+int ndq_dq_encode_with_step(const void* g, int dt, size_t n, const float* step_in, uint32_t levels,
+                            const ndq_dither* d, void* codes_out, float* steps_out, void* stream)
+{
+    if (!step_in && n != 0) return NDQ_EINVAL;
+    return ndq::encode_common(g, dt, n, 0.0f, step_in, levels, 0u, false, 1.0f, 0u, d, codes_out,
                               steps_out, stream);
 }
 
@@ -673,7 +695,17 @@ int ndq_nested_encode(const void* g, int dt, size_t n, float delta, uint32_t lev
                       uint32_t M, float alpha, uint32_t bucket, const ndq_dither* d,
                       void* codes_out, float* steps_out, void* stream)
 {
-    return ndq::encode_common(g, dt, n, delta, levels, M, true, alpha, bucket, d, codes_out,
+    return ndq::encode_common(g, dt, n, delta, nullptr, levels, M, true, alpha, bucket, d, codes_out,
+                              steps_out, stream);
+}
+
+int ndq_nested_encode_with_step(const void* g, int dt, size_t n, const float* step_in, uint32_t M,
+                                float alpha, const ndq_dither* d, void* codes_out, float* steps_out,
+                                void* stream)
+{
+    if (!step_in && n != 0) return NDQ_EINVAL;
+    // the number of fine levels only ever served to derive a step: any valid value will do
+    return ndq::encode_common(g, dt, n, 0.0f, step_in, 2u, M, true, alpha, 0u, d, codes_out,
                               steps_out, stream);
 }
 

@@ -18,6 +18,7 @@ NDQ_F32, NDQ_BF16 = 0, 1
 NDQ_OK, NDQ_EINVAL, NDQ_EALIGN, NDQ_EUNSUPPORTED, NDQ_ELAUNCH = 0, -1, -2, -3, -4
 
 EXPORTS = ("ndq_code_bits", "ndq_packed_bytes", "ndq_num_buckets", "ndq_absmax", "ndq_dq_encode",
+           "ndq_dq_encode_with_step", "ndq_nested_encode_with_step",
            "ndq_dq_decode", "ndq_dq_decode_half", "ndq_nested_encode", "ndq_nested_decode", "ndq_aggregate",
            "ndq_decode_chain", "ndq_code_entropy", "ndq_dense_group", "ndq_dense_bytes",
            "ndq_dense_pack", "ndq_dense_unpack", "ndq_alpha_for_equal_variance",
@@ -72,6 +73,10 @@ def lib():
         L.ndq_dq_decode_half.restype = ci
         L.ndq_nested_encode.argtypes = [vp, ci, sz, f32, u32, u32, f32, u32, dp, vp, vp, vp]
         L.ndq_nested_encode.restype = ci
+        L.ndq_dq_encode_with_step.argtypes = [vp, ci, sz, vp, u32, dp, vp, vp, vp]
+        L.ndq_dq_encode_with_step.restype = ci
+        L.ndq_nested_encode_with_step.argtypes = [vp, ci, sz, vp, u32, f32, dp, vp, vp, vp]
+        L.ndq_nested_encode_with_step.restype = ci
         L.ndq_nested_decode.argtypes = [vp, sz, u32, f32, u32, vp, dp, vp, f32, vp, ci, vp]
         L.ndq_nested_decode.restype = ci
         L.ndq_aggregate.argtypes, L.ndq_aggregate.restype = [vp, u32, sz, f32, vp, vp], ci
@@ -171,6 +176,32 @@ def ndq_nested_encode(g, delta, levels, M, alpha, bucket, d, codes_out=None, ste
     _check(lib().ndq_nested_encode(_dev(g, "g"), _dt(g), g.numel(), delta, levels, M, alpha, bucket,
                                    C.byref(d), _dev(codes_out, "codes_out"),
                                    _dev(steps_out, "steps_out"), _stream()), "ndq_nested_encode")
+    return codes_out, steps_out
+
+
+def _step_in(step_in):
+    ptr = _dev(step_in, "step_in")
+    if step_in.dtype != torch.float32 or step_in.numel() < 1:
+        raise ValueError("step_in must hold one float32")
+    return ptr
+
+
+def ndq_dq_encode_with_step(g, step_in, levels, d, codes_out=None, steps_out=None):
+    """-> (codes, steps); the step is read from the device tensor step_in"""
+    codes_out, steps_out = _enc_outputs(g, ndq_code_bits(levels), 0, codes_out, steps_out)
+    _check(lib().ndq_dq_encode_with_step(_dev(g, "g"), _dt(g), g.numel(), _step_in(step_in), levels,
+                                         C.byref(d), _dev(codes_out, "codes_out"),
+                                         _dev(steps_out, "steps_out"), _stream()),
+           "ndq_dq_encode_with_step")
+    return codes_out, steps_out
+
+
+def ndq_nested_encode_with_step(g, step_in, M, alpha, d, codes_out=None, steps_out=None):
+    codes_out, steps_out = _enc_outputs(g, ndq_code_bits(M), 0, codes_out, steps_out)
+    _check(lib().ndq_nested_encode_with_step(_dev(g, "g"), _dt(g), g.numel(), _step_in(step_in), M, alpha,
+                                             C.byref(d), _dev(codes_out, "codes_out"),
+                                             _dev(steps_out, "steps_out"), _stream()),
+           "ndq_nested_encode_with_step")
     return codes_out, steps_out
 
 

@@ -46,18 +46,21 @@ def allocate(wl: Workload, n: int, device="cuda", separate=False) -> Buffers:
 
 
 def encode_all(wl: Workload, grads, bufs: Buffers, ds, preset_step: float = 0.0):
-    """Worker side.  With wl.shared_step the step of worker 0 is read back once
-    and handed to the other workers as a preset (Algorithm 1, initialisation)."""
-    delta = preset_step
+    """Worker side.  With wl.shared_step and no preset, worker 0 chooses the step and
+    the other workers read it from worker 0's steps in device memory (Algorithm 1,
+    initialisation: one Delta for all): no host round trip between the calls."""
     for w, (kind, arg) in enumerate(wl.plan):
-        if kind == "dq":
-            ndq.ndq_dq_encode(grads[w], delta, arg, wl.bucket, ds[w], bufs.codes[w], bufs.steps[w])
+        shared = wl.shared_step and w > 0 and preset_step == 0.0
+        if kind == "dq" and shared:
+            ndq.ndq_dq_encode_with_step(grads[w], bufs.steps[0], arg, ds[w], bufs.codes[w], bufs.steps[w])
+        elif kind == "dq":
+            ndq.ndq_dq_encode(grads[w], preset_step, arg, wl.bucket, ds[w], bufs.codes[w], bufs.steps[w])
+        elif shared:
+            ndq.ndq_nested_encode_with_step(grads[w], bufs.steps[0], arg, 1.0, ds[w], bufs.codes[w],
+                                            bufs.steps[w])
         else:
-            ndq.ndq_nested_encode(grads[w], delta, wl.fine_levels, arg, 1.0, wl.bucket, ds[w],
+            ndq.ndq_nested_encode(grads[w], preset_step, wl.fine_levels, arg, 1.0, wl.bucket, ds[w],
                                   bufs.codes[w], bufs.steps[w])
-        if wl.shared_step and w == 0 and delta == 0.0:
-            delta = float(bufs.steps[0][0].item())
-    return delta
 
 
 def decode_chain(wl: Workload, n: int, bufs: Buffers, ds):
@@ -101,52 +104,6 @@ def step(wl: Workload, grads, bufs: Buffers, ds, preset_step: float = 0.0):
     n = grads[0].numel()
     encode_all(wl, grads, bufs, ds, preset_step)
     return decode_chain(wl, n, bufs, ds)
-
-
-class TwoStreams:
-    """Two HIP streams (default priority) and one event per worker, so that the
-    compute-bound encoders overlap the bandwidth-bound decoders."""
-
-    def __init__(self, W: int):
-        self.enc = torch.cuda.Stream()
-        self.dec = torch.cuda.Stream()
-        self.encoded = [torch.cuda.Event() for _ in range(W)]
-
-
-def step_overlapped(wl: Workload, grads, bufs: Buffers, ds, ts: TwoStreams,
-                    preset_step: float = 0.0):
-    """The same work as step(), enqueued on two streams: worker w's decode waits
-    only for worker w's encode (and the decode before it), so encode w+1 runs
-    beside decode w.  Results are identical to step()."""
-    assert not (wl.shared_step and preset_step == 0.0), "shared step must be preset"
-    n = grads[0].numel()
-    main = torch.cuda.current_stream()
-    ts.enc.wait_stream(main)
-    ts.dec.wait_stream(main)
-    with torch.cuda.stream(ts.enc):
-        for w, (kind, arg) in enumerate(wl.plan):
-            if kind == "dq":
-                ndq.ndq_dq_encode(grads[w], preset_step, arg, wl.bucket, ds[w], bufs.codes[w],
-                                  bufs.steps[w])
-            else:
-                ndq.ndq_nested_encode(grads[w], preset_step, wl.fine_levels, arg, 1.0, wl.bucket,
-                                      ds[w], bufs.codes[w], bufs.steps[w])
-            ts.encoded[w].record(ts.enc)
-    S = bufs.total
-    with torch.cuda.stream(ts.dec):
-        for w, (kind, arg) in enumerate(wl.plan):
-            ts.dec.wait_event(ts.encoded[w])
-            if kind == "dq":
-                ndq.ndq_dq_decode(bufs.codes[w], n, arg, wl.bucket, bufs.steps[w], ds[w], S,
-                                  accumulate=w > 0)
-            else:
-                ndq.ndq_nested_decode(bufs.codes[w], n, arg, 1.0, wl.bucket, bufs.steps[w], ds[w], S,
-                                      1.0 / w, S, accumulate=True)
-        if wl.out_scale != 1.0:
-            ndq.ndq_aggregate([S], wl.out_scale, S)
-    main.wait_stream(ts.enc)
-    main.wait_stream(ts.dec)
-    return S
 
 
 def step_fused(wl: Workload, grads, bufs: Buffers, ds, preset_step: float = 0.0):

@@ -4,9 +4,10 @@ a process of its own by test_gpu_streaming.py with
     NDQ_STREAM_MIN_TILES_PER_WAVE=0  NDQ_STREAM_MAX_BLOCKS=3
 
 so that vectors of a few hundred thousand elements -- small enough for the oracle
--- go through the persistent kernels on twelve waves: several tiles per wave (both
-register sets in turn, even and odd tile counts), waves with one tile fewer, and a
-ragged last tile.  Everything is compared with the oracle bit for bit.
+-- go through the persistent kernels on twelve waves: several tiles per wave (the
+next tile's rows loaded into the registers of the rows just consumed, even and odd
+tile counts), waves with one tile fewer, and a ragged last tile.  Everything is
+compared with the oracle bit for bit.
 """
 import os
 import sys
@@ -61,6 +62,13 @@ def encoder_cases():
                         assert np.array_equal(steps.cpu().numpy(), s_ref)
                         assert codes.cpu().numpy().tobytes() == c_ref.tobytes()
                         count += 1
+                    # the same preset step, handed over in device memory
+                    print("dq encode with step", dtype, n, offset, levels, flush=True)
+                    step_d = torch.tensor([preset], dtype=torch.float32, device="cuda")
+                    codes, steps = ndq.ndq_dq_encode_with_step(g_d, step_d, levels, d_g)
+                    assert np.array_equal(steps.cpu().numpy(), s_ref)
+                    assert codes.cpu().numpy().tobytes() == c_ref.tobytes()
+                    count += 1
                 for M, levels in ((2, 4), (4, 16), (16, 64), (2, 2)):
                     preset = float(F(2 * np.abs(gf).max() / (levels - 1)))
                     for bucket, delta in ((tile, 0.0), (0, 0.0), (0, preset)):
@@ -70,6 +78,12 @@ def encoder_cases():
                         assert np.array_equal(steps.cpu().numpy(), s_ref)
                         assert codes.cpu().numpy().tobytes() == c_ref.tobytes()
                         count += 1
+                    print("nested encode with step", dtype, n, offset, M, flush=True)
+                    step_d = torch.tensor([preset], dtype=torch.float32, device="cuda")
+                    codes, steps = ndq.ndq_nested_encode_with_step(g_d, step_d, M, 1.0, d_g)
+                    assert np.array_equal(steps.cpu().numpy(), s_ref)
+                    assert codes.cpu().numpy().tobytes() == c_ref.tobytes()
+                    count += 1
     return count
 
 

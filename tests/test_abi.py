@@ -66,6 +66,19 @@ def test_validation_rejects_bad_arguments_without_a_gpu():
     d_bad = ndq.ndq_dither(0, 0, 0, 2)
     assert lib.ndq_dq_encode(p, 0, 64, 0.0, 4, 0, C.byref(d_bad), p, p, null) == ndq.NDQ_EALIGN
     assert lib.ndq_nested_encode(p, 0, 64, 0.0, 4, 1, 1.0, 0, C.byref(d), p, p, null) == ndq.NDQ_EINVAL
+    # a step handed over in device memory
+    assert lib.ndq_dq_encode_with_step(p, 0, 64, null, 4, C.byref(d), p, p, null) == ndq.NDQ_EINVAL
+    assert lib.ndq_dq_encode_with_step(p, 0, 64, p, 1, C.byref(d), p, p, null) == ndq.NDQ_EINVAL
+    assert lib.ndq_dq_encode_with_step(p, 2, 64, p, 4, C.byref(d), p, p, null) == ndq.NDQ_EINVAL
+    assert lib.ndq_dq_encode_with_step(p, 0, 64, C.c_void_p(0x1002), 4, C.byref(d), p, p, null) == ndq.NDQ_EALIGN
+    assert lib.ndq_dq_encode_with_step(p, 0, 64, p, 4, C.byref(d_bad), p, p, null) == ndq.NDQ_EALIGN
+    assert lib.ndq_dq_encode_with_step(p, 0, 1 << 40, p, 4, C.byref(d), p, p, null) == ndq.NDQ_EUNSUPPORTED
+    assert lib.ndq_dq_encode_with_step(null, 0, 0, null, 4, C.byref(d), null, null, null) == ndq.NDQ_OK
+    assert lib.ndq_nested_encode_with_step(p, 0, 64, null, 4, 1.0, C.byref(d), p, p, null) == ndq.NDQ_EINVAL
+    assert lib.ndq_nested_encode_with_step(p, 0, 64, p, 1, 1.0, C.byref(d), p, p, null) == ndq.NDQ_EINVAL
+    assert lib.ndq_nested_encode_with_step(p, 0, 64, p, 4, 1.5, C.byref(d), p, p, null) == ndq.NDQ_EINVAL
+    assert lib.ndq_nested_encode_with_step(p, 0, 64, p, 4, 1.0, None, p, p, null) == ndq.NDQ_EINVAL
+    assert lib.ndq_nested_encode_with_step(null, 0, 0, null, 4, 1.0, C.byref(d), null, null, null) == ndq.NDQ_OK
     assert lib.ndq_nested_decode(p, 64, 300, 1.0, 0, p, C.byref(d), p, 1.0, p, 0, null) == ndq.NDQ_EINVAL
     assert lib.ndq_nested_decode(p, 64, 4, 1.0, 0, p, C.byref(d), null, 1.0, p, 0, null) == ndq.NDQ_EINVAL
     q = C.c_void_p(0x1010)           # side and out overlap partially

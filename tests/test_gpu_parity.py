@@ -91,6 +91,49 @@ def test_dq_encode_decode_matches_oracle(dtype, levels, bucket, preset):
         assert np.array_equal(acc.cpu().numpy(), ref_acc)
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_encode_with_a_step_in_device_memory_matches_oracle(dtype):
+    """One Delta for all workers (Algorithm 1 / 2, initialisation), handed over as a
+    device pointer: the codes are those of the oracle's preset-step encoder; worker 0's
+    own steps_out serves as step_in; a zero step gives index 0 everywhere."""
+    dev = _gpu()
+    for n in SIZES:
+        if n == 0:
+            continue
+        g0, g1 = _make(n, dtype, seed=n + 31), _make(n, dtype, seed=n + 32)
+        g1f = workloads.bf16_bits_to_f32(g1) if dtype == "bf16" else g1
+        d0_o, d1_o = oracle.dither(9, 4, 0), oracle.dither(9, 4, 1)
+        d0_g, d1_g = ndq.ndq_dither(9, 4, 0, 0), ndq.ndq_dither(9, 4, 1, 0)
+        for levels, M in ((4, 2), (16, 4), (100, 3), (256, 16)):
+            _, s0_ref = oracle.dq_encode(g0, 0.0, levels, 0, d0_o)
+            _, steps0 = ndq.ndq_dq_encode(_to_dev(g0), 0.0, levels, 0, d0_g)
+            assert np.array_equal(steps0.cpu().numpy(), s0_ref)
+            delta = float(s0_ref[0])
+            # worker 1 (values partly outside worker 0's range: it saturates / wraps as the oracle does)
+            c_ref, s_ref = oracle.dq_encode(g1, delta, levels, 0, d1_o)
+            codes, steps = ndq.ndq_dq_encode_with_step(_to_dev(g1), steps0, levels, d1_g)
+            assert np.array_equal(steps.cpu().numpy(), s_ref), (n, levels)
+            assert codes.cpu().numpy().tobytes() == c_ref.tobytes(), (n, levels)
+            for alpha in (1.0, 0.75):
+                c_ref, s_ref = oracle.nested_encode(g1, delta, levels, M, 0, d1_o, alpha=alpha)
+                codes, steps = ndq.ndq_nested_encode_with_step(_to_dev(g1), steps0, M, alpha, d1_g)
+                assert np.array_equal(steps.cpu().numpy(), s_ref), (n, M, alpha)
+                assert codes.cpu().numpy().tobytes() == c_ref.tobytes(), (n, M, alpha)
+            # step_in and steps_out are the same address
+            inout = steps0.clone()
+            codes, steps = ndq.ndq_dq_encode_with_step(_to_dev(g1), inout, levels, d1_g, steps_out=inout)
+            c_ref, _ = oracle.dq_encode(g1, delta, levels, 0, d1_o)
+            assert codes.cpu().numpy().tobytes() == c_ref.tobytes() and float(inout.item()) == delta
+        # a zero step (what an all-zero vector's encoder sends): fine index 0 everywhere
+        zero = torch.zeros(1, dtype=torch.float32, device=dev)
+        codes, steps = ndq.ndq_dq_encode_with_step(_to_dev(g1), zero, 5, d1_g)
+        want = oracle.pack(np.full(n, 2, dtype=np.uint32), 3)
+        assert codes.cpu().numpy().tobytes() == want.tobytes() and float(steps.item()) == 0.0
+        codes, steps = ndq.ndq_nested_encode_with_step(_to_dev(g1), zero, 4, 1.0, d1_g)
+        assert not codes.cpu().numpy().any() and float(steps.item()) == 0.0
+        assert np.abs(g1f).max() > 0
+
+
 @pytest.mark.parametrize("levels,bucket", [(3, 0), (5, 2048), (9, 64), (16, 4096), (256, 2112), (7, 0)])
 def test_half_dithered_decode_matches_oracle(levels, bucket):
     """Reconstruction without dither subtraction (stochastic / ternary quantizers'
@@ -450,8 +493,9 @@ def _run_both(wl, n, separate=False):
     dev = pipeline.to_device(wl, host)
     bufs = pipeline.allocate(wl, n, separate=separate)
     ds_g = pipeline.dithers(wl)
-    delta_g = pipeline.encode_all(wl, dev, bufs, ds_g)
-    assert delta_g == delta
+    pipeline.encode_all(wl, dev, bufs, ds_g)       # a shared step stays in device memory
+    if wl.shared_step:
+        assert float(bufs.steps[0][0].item()) == delta
     for w in range(wl.W):
         assert np.array_equal(bufs.steps[w].cpu().numpy(), s_ref[w]), ("steps", w)
         assert bufs.codes[w].cpu().numpy().tobytes() == c_ref[w].tobytes(), ("codes", w)
@@ -615,25 +659,6 @@ def test_runs_are_deterministic():
     assert not torch.equal(b1.codes[0], b2.codes[0])
 
 
-def test_two_stream_schedule_gives_identical_results():
-    """Encoders and decoders on two streams (encode w+1 beside decode w) must
-    produce exactly what the single-stream schedule does."""
-    wl = workloads.CONFIGS[5]
-    n = (1 << 22) + 4096 * 3
-    dev = pipeline.to_device(wl, workloads.gradients(wl, n))
-    ds = pipeline.dithers(wl)
-    b1, b2 = pipeline.allocate(wl, n), pipeline.allocate(wl, n)
-    ref = pipeline.step(wl, dev, b1, ds).clone()
-    ts = pipeline.TwoStreams(wl.W)
-    for _ in range(3):
-        b2.total.zero_()
-        out = pipeline.step_overlapped(wl, dev, b2, ds, ts)
-        torch.cuda.synchronize()
-        assert torch.equal(out, ref)
-    for w in range(wl.W):
-        assert torch.equal(b1.codes[w], b2.codes[w]) and torch.equal(b1.steps[w], b2.steps[w])
-
-
 # --------------------------------------------------------------------------
 # the whole server loop of Algorithm 2 in one call
 # --------------------------------------------------------------------------
@@ -700,9 +725,13 @@ def test_fused_step_equals_call_by_call_step_on_the_configs():
         ds = pipeline.dithers(wl)
         b1, b2 = pipeline.allocate(wl, n), pipeline.allocate(wl, n)
         ref = pipeline.step(wl, dev, b1, ds).clone()
-        preset = float(b1.steps[0][0].item()) if wl.shared_step else 0.0
-        out = pipeline.step_fused(wl, dev, b2, ds, preset)
+        # a shared step read from worker 0's message on the device, then the same step as a host preset
+        out = pipeline.step_fused(wl, dev, b2, ds)
         assert torch.equal(out, ref), cfg
+        if wl.shared_step:
+            b2.total.zero_()
+            out = pipeline.step_fused(wl, dev, b2, ds, float(b1.steps[0][0].item()))
+            assert torch.equal(out, ref), cfg
 
 
 # --------------------------------------------------------------------------
