@@ -31,6 +31,58 @@ constexpr uint32_t kHistThreads = 1024;
 constexpr uint32_t kHistBlocks = 256;
 constexpr uint32_t kHistCopies = 32;
 
+// The workgroup that finishes last closes the histogram inside the counting kernel
+// (no launch of its own): it fills in a bin that was left to be derived and computes
+// the entropy.  `ticket` is a 64-bit word that is zero when the kernel starts.
+// Every thread calls this after its last atomic on the histogram; the fence orders
+// those atomics before the workgroup's ticket, so the workgroup that draws the last
+// ticket finds all counts in memory (it reads them with atomics of device scope,
+// like the additions that made them).
+__device__ __forceinline__ bool last_workgroup(unsigned long long* ticket, uint32_t* flag)
+{
+    __threadfence();
+    __syncthreads();
+    if (threadIdx.x == 0u) *flag = atomicAdd(ticket, 1ull) == (unsigned long long)gridDim.x - 1ull ? 1u : 0u;
+    __syncthreads();
+    return *flag != 0u;
+}
+
+// -sum p log2 p over at most 256 bins, binary64, fixed reduction order; called by all
+// threads of one workgroup of at least 256 threads.  derive_bin0 (at most 4 bins):
+// bin 0 was not counted and is what the other bins leave of n.
+__device__ __forceinline__ void close_histogram(unsigned long long* hist, uint32_t nbins, uint64_t n,
+                                                double* entropy_out, bool derive_bin0, double* term,
+                                                unsigned long long* few)
+{
+    const uint32_t tid = threadIdx.x;
+    unsigned long long h = 0ull;
+    if (tid < nbins && !(derive_bin0 && tid == 0u))
+        h = __hip_atomic_load(hist + tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (derive_bin0) {
+        if (tid >= 1u && tid < nbins) few[tid] = h;
+        __syncthreads();
+        if (tid == 0u) {
+            unsigned long long rest = n;
+            for (uint32_t b = 1; b < nbins; ++b) rest -= few[b];
+            hist[0] = rest;
+            h = rest;
+        }
+    }
+    if (!entropy_out) return;     // (the same for every thread)
+    double t = 0.0;
+    if (tid < nbins && h) {
+        const double p = (double)h / (double)n;
+        t = -p * log2(p);
+    }
+    if (tid < 256u) term[tid] = t;
+    __syncthreads();
+    for (uint32_t s = 128; s >= 1; s >>= 1) {
+        if (tid < s) term[tid] += term[tid + s];
+        __syncthreads();
+    }
+    if (tid == 0u) entropy_out[0] = term[0];
+}
+
 template <int BITS>
 __device__ __forceinline__ void load_unit(const uint32_t* __restrict__ words, uint64_t u, uint32_t (&w)[BITS])
 {
@@ -49,11 +101,13 @@ __device__ __forceinline__ void load_unit(const uint32_t* __restrict__ words, ui
 
 template <int BITS>
 __global__ __launch_bounds__(kHistThreads) void histogram_kernel(const uint32_t* __restrict__ words, uint64_t n,
-                                                                 unsigned long long* hist)
+                                                                 unsigned long long* hist, double* entropy_out)
 {
     constexpr uint32_t NB = 1u << BITS;
     constexpr uint32_t MASK = NB - 1u;
     __shared__ uint32_t cnt[NB * kHistCopies];
+    __shared__ double term[256];
+    __shared__ uint32_t flag;
     const uint32_t tid = threadIdx.x;
     for (uint32_t i = tid; i < NB * kHistCopies; i += kHistThreads) cnt[i] = 0u;
     __syncthreads();
@@ -95,6 +149,9 @@ __global__ __launch_bounds__(kHistThreads) void histogram_kernel(const uint32_t*
         for (uint32_t c = 0; c < kHistCopies; ++c) sum += cnt[b * kHistCopies + ((c + b) & (kHistCopies - 1u))];
         if (sum) atomicAdd(hist + b, sum);
     }
+    // the entropy's eight bytes hold the ticket until the last workgroup writes the entropy there
+    if (entropy_out && last_workgroup(reinterpret_cast<unsigned long long*>(entropy_out), &flag))
+        close_histogram(hist, NB, n, entropy_out, false, term, nullptr);
 }
 
 // 1- and 2-bit codes: a thread takes 16 bytes (128 or 64 codes) at a time, eight
@@ -126,9 +183,13 @@ __device__ __forceinline__ void count_small(const uint4& x, uint32_t bits, uint3
 }
 
 __global__ __launch_bounds__(kSmallThreads) void histogram_small_kernel(const uint4* __restrict__ vec, uint64_t n,
-                                                                        uint32_t bits, unsigned long long* hist)
+                                                                        uint32_t bits, unsigned long long* hist,
+                                                                        double* entropy_out)
 {
     __shared__ uint32_t part[3][kSmallThreads / 64];
+    __shared__ double term[256];
+    __shared__ unsigned long long few[4];
+    __shared__ uint32_t flag;
     const uint32_t tid = threadIdx.x;
     // whole 16-byte vectors here; the last, partial one (the stream is allocated in
     // multiples of 16 bytes) is masked to its valid bits below.  Bits masked away
@@ -162,52 +223,23 @@ __global__ __launch_bounds__(kSmallThreads) void histogram_small_kernel(const ui
         if ((tid & 63u) == 0u) part[b][tid >> 6] = c[b];
     }
     __syncthreads();
-    // bins 1..3 (or bin 1) by atomics; bin 0 follows from n in entropy_kernel
+    // bins 1..3 (or bin 1) by atomics; bin 0 is not counted: its eight bytes hold the
+    // ticket, and the last workgroup writes there what the other bins leave of n
     const uint32_t nbins = 1u << bits;
     if (tid >= 1u && tid < nbins) {
         unsigned long long sum = 0u;
         for (uint32_t w = 0; w < kSmallThreads / 64u; ++w) sum += part[tid - 1u][w];
         if (sum) atomicAdd(hist + tid, sum);
     }
+    if (last_workgroup(hist, &flag)) close_histogram(hist, nbins, n, entropy_out, true, term, few);
 }
 
-__global__ void fill_zero64_kernel(unsigned long long* p, uint32_t count)
+// clears the bins and, when an entropy is wanted, its eight bytes (+0.0: the entropy of
+// an empty stream, and the zero the ticket starts from)
+__global__ void clear_histogram_kernel(unsigned long long* hist, uint32_t nbins, unsigned long long* entropy_bits)
 {
-    if (threadIdx.x < count) p[threadIdx.x] = 0ull;
-}
-
-// -sum p log2 p over at most 256 bins, binary64, fixed reduction order
-// (derive_bin0: the 1- and 2-bit histogram leaves bin 0 to be filled in here as
-// what the other bins leave of n; entropy_out may then be null)
-__global__ __launch_bounds__(256) void entropy_kernel(unsigned long long* hist, uint32_t nbins,
-                                                      uint64_t n, double* entropy_out, int derive_bin0)
-{
-    __shared__ double term[256];
-    const uint32_t tid = threadIdx.x;
-    if (derive_bin0) {
-        if (tid == 0) {
-            unsigned long long rest = n;
-            for (uint32_t b = 1; b < nbins; ++b) rest -= hist[b];
-            hist[0] = rest;
-        }
-        __syncthreads();
-        if (!entropy_out) return;
-    }
-    double t = 0.0;
-    if (tid < nbins && n) {
-        const unsigned long long h = hist[tid];
-        if (h) {
-            const double p = (double)h / (double)n;
-            t = -p * log2(p);
-        }
-    }
-    term[tid] = t;
-    __syncthreads();
-    for (uint32_t s = 128; s >= 1; s >>= 1) {
-        if (tid < s) term[tid] += term[tid + s];
-        __syncthreads();
-    }
-    if (tid == 0) entropy_out[0] = term[0];
+    if (threadIdx.x < nbins) hist[threadIdx.x] = 0ull;
+    if (threadIdx.x == 0u && entropy_bits) entropy_bits[0] = 0ull;
 }
 
 // ---------------------------------------------------------------------------
@@ -448,42 +480,33 @@ int ndq_code_entropy(const void* codes, size_t n, uint32_t bits, uint64_t* hist_
     if (n != 0 && !aligned16(codes)) return NDQ_EALIGN;
     hipStream_t s = (hipStream_t)stream;
     const uint32_t nbins = 1u << bits;
-    if (launch(fill_zero64_kernel, dim3(1), dim3(256), s, (unsigned long long*)hist_out, nbins) != NDQ_OK)
+    if (launch(clear_histogram_kernel, dim3(1), dim3(256), s, (unsigned long long*)hist_out, nbins,
+               (unsigned long long*)entropy_out) != NDQ_OK)
         return NDQ_ELAUNCH;
-    if (n != 0 && bits <= 2u) {
+    if (n == 0) return NDQ_OK;
+    if (bits <= 2u) {
         const uint64_t vectors = ((uint64_t)n * bits) >> 7;
         uint64_t blocks = (vectors + kSmallInFlight * kSmallThreads - 1) / (kSmallInFlight * kSmallThreads);
         if (blocks > kSmallBlocks) blocks = kSmallBlocks;
         if (blocks == 0u) blocks = 1u;
-        if (launch(histogram_small_kernel, dim3((uint32_t)blocks), dim3(kSmallThreads), s, (const uint4*)codes,
-                   (uint64_t)n, bits, (unsigned long long*)hist_out) != NDQ_OK)
-            return NDQ_ELAUNCH;
-    } else if (n != 0) {
-        const uint64_t units = (uint64_t)n >> 5;
-        uint64_t blocks = (units + kHistThreads - 1) / kHistThreads;
-        if (blocks > kHistBlocks) blocks = kHistBlocks;
-        if (blocks == 0u) blocks = 1u;
-        const dim3 grid((uint32_t)blocks), block(kHistThreads);
-        const uint32_t* words = (const uint32_t*)codes;
-        unsigned long long* h = (unsigned long long*)hist_out;
-        int rc_hist;
-        switch (bits) {
-        case 3: rc_hist = launch(histogram_kernel<3>, grid, block, s, words, (uint64_t)n, h); break;
-        case 4: rc_hist = launch(histogram_kernel<4>, grid, block, s, words, (uint64_t)n, h); break;
-        case 5: rc_hist = launch(histogram_kernel<5>, grid, block, s, words, (uint64_t)n, h); break;
-        case 6: rc_hist = launch(histogram_kernel<6>, grid, block, s, words, (uint64_t)n, h); break;
-        case 7: rc_hist = launch(histogram_kernel<7>, grid, block, s, words, (uint64_t)n, h); break;
-        default: rc_hist = launch(histogram_kernel<8>, grid, block, s, words, (uint64_t)n, h); break;
-        }
-        if (rc_hist != NDQ_OK) return NDQ_ELAUNCH;
+        return launch(histogram_small_kernel, dim3((uint32_t)blocks), dim3(kSmallThreads), s, (const uint4*)codes,
+                      (uint64_t)n, bits, (unsigned long long*)hist_out, entropy_out);
     }
-    const int derive_bin0 = n != 0 && bits <= 2u;
-    if (entropy_out || derive_bin0) {
-        if (launch(entropy_kernel, dim3(1), dim3(256), s, (unsigned long long*)hist_out, nbins, (uint64_t)n,
-                   entropy_out, derive_bin0) != NDQ_OK)
-            return NDQ_ELAUNCH;
+    const uint64_t units = (uint64_t)n >> 5;
+    uint64_t blocks = (units + kHistThreads - 1) / kHistThreads;
+    if (blocks > kHistBlocks) blocks = kHistBlocks;
+    if (blocks == 0u) blocks = 1u;
+    const dim3 grid((uint32_t)blocks), block(kHistThreads);
+    const uint32_t* words = (const uint32_t*)codes;
+    unsigned long long* h = (unsigned long long*)hist_out;
+    switch (bits) {
+    case 3: return launch(histogram_kernel<3>, grid, block, s, words, (uint64_t)n, h, entropy_out);
+    case 4: return launch(histogram_kernel<4>, grid, block, s, words, (uint64_t)n, h, entropy_out);
+    case 5: return launch(histogram_kernel<5>, grid, block, s, words, (uint64_t)n, h, entropy_out);
+    case 6: return launch(histogram_kernel<6>, grid, block, s, words, (uint64_t)n, h, entropy_out);
+    case 7: return launch(histogram_kernel<7>, grid, block, s, words, (uint64_t)n, h, entropy_out);
+    default: return launch(histogram_kernel<8>, grid, block, s, words, (uint64_t)n, h, entropy_out);
     }
-    return NDQ_OK;
 }
 
 uint32_t ndq_dense_group(uint32_t levels)

@@ -291,18 +291,22 @@ def ndq_decode_chain(workers, n, bucket, scale=1.0, out=None):
     return out
 
 
-def ndq_code_entropy(codes, n, bits, hist_out=None, entropy_out=None):
-    """-> (histogram int64 tensor of 2^bits counts, entropy float64 tensor of 1 element)"""
+def ndq_code_entropy(codes, n, bits, hist_out=None, entropy_out=None, want_entropy=True):
+    """-> (histogram int64 tensor of 2^bits counts, entropy float64 tensor of 1 element;
+    None with want_entropy=False: the C call then gets a null entropy_out)"""
     dev = codes.device
     if n and codes.numel() * codes.element_size() < ndq_packed_bytes(n, bits):
         raise ValueError("codes hold fewer than ndq_packed_bytes(n, bits) bytes")
     if hist_out is None:
         hist_out = torch.empty(1 << bits, dtype=torch.int64, device=dev)
-    if entropy_out is None:
+    if not want_entropy:
+        entropy_out = None
+    elif entropy_out is None:
         entropy_out = torch.empty(1, dtype=torch.float64, device=dev)
     cptr = _dev(codes, "codes") if n else C.c_void_p(0)
-    _check(lib().ndq_code_entropy(cptr, n, bits, _dev(hist_out, "hist_out"),
-                                  _dev(entropy_out, "entropy_out"), _stream()), "ndq_code_entropy")
+    eptr = _dev(entropy_out, "entropy_out") if want_entropy else C.c_void_p(0)
+    _check(lib().ndq_code_entropy(cptr, n, bits, _dev(hist_out, "hist_out"), eptr, _stream()),
+           "ndq_code_entropy")
     return hist_out, entropy_out
 
 

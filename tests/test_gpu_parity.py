@@ -749,9 +749,18 @@ def test_code_histogram_and_entropy_match_oracle(bits):
         packed = oracle.pack(codes, bits)
         ref_h = oracle.code_histogram(packed, n, bits)
         ref_e = oracle.entropy_bits(ref_h)
-        hist, ent = ndq.ndq_code_entropy(torch.from_numpy(packed).to(dev), n, bits)
+        packed_d = torch.from_numpy(packed).to(dev)
+        # outputs that hold something else before the call (the call clears them itself)
+        hist = torch.full((1 << bits,), 12345, dtype=torch.int64, device=dev)
+        ent = torch.full((1,), 7.5, dtype=torch.float64, device=dev)
+        ndq.ndq_code_entropy(packed_d, n, bits, hist, ent)
         assert np.array_equal(hist.cpu().numpy().astype(np.uint64), ref_h), (bits, n)
         assert abs(float(ent.item()) - ref_e) <= 1e-9, (bits, n)
+        # the histogram alone (null entropy_out), twice in a row into the same buffer
+        for _ in range(2):
+            hist2, none = ndq.ndq_code_entropy(packed_d, n, bits, hist, want_entropy=False)
+            assert none is None
+            assert np.array_equal(hist2.cpu().numpy().astype(np.uint64), ref_h), (bits, n)
 
 
 @pytest.mark.parametrize("bits", [1, 2, 3, 8])
