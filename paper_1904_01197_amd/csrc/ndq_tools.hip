@@ -34,15 +34,20 @@ constexpr uint32_t kHistCopies = 32;
 // The workgroup that finishes last closes the histogram inside the counting kernel
 // (no launch of its own): it fills in a bin that was left to be derived and computes
 // the entropy.  `ticket` is a 64-bit word that is zero when the kernel starts.
-// Every thread calls this after its last atomic on the histogram; the fence orders
-// those atomics before the workgroup's ticket, so the workgroup that draws the last
-// ticket finds all counts in memory (it reads them with atomics of device scope,
-// like the additions that made them).
+// Every thread calls this after its last atomic on the histogram.  The barrier makes
+// every wave wait until its atomics are done; one thread's fence then orders them
+// before the workgroup's ticket (a fence per thread would write back and invalidate
+// the L2 sixteen times per workgroup while the others still stream through it).  The
+// workgroup that draws the last ticket therefore finds all counts in memory; it reads
+// them with atomics of device scope, like the additions that made them.
 __device__ __forceinline__ bool last_workgroup(unsigned long long* ticket, uint32_t* flag)
 {
-    __threadfence();
     __syncthreads();
-    if (threadIdx.x == 0u) *flag = atomicAdd(ticket, 1ull) == (unsigned long long)gridDim.x - 1ull ? 1u : 0u;
+    if (threadIdx.x == 0u) {
+        __threadfence();
+        *flag = atomicAdd(ticket, 1ull) == (unsigned long long)gridDim.x - 1ull ? 1u : 0u;
+        __threadfence();
+    }
     __syncthreads();
     return *flag != 0u;
 }
@@ -367,6 +372,173 @@ __global__ __launch_bounds__(kDenseBlock) void dense_unpack_kernel(DenseArgs a)
     for (uint32_t i = tid; i < words_out; i += kDenseBlock) fixed32[i] = st.fixed[i];
 }
 
+// The level counts of the paper's own experiments (Sec. 4: three levels, M = 1, and five,
+// M = 2) with everything known at compile time: the same partition as above (a thread
+// owns 8 dense words = 8 K indices = TB = K * BITS bytes of the fixed-width stream), but
+// the thread's bytes sit in registers as one bit string, every index at a fixed
+// position, the digits come and go with constant multipliers, and both streams move
+// between memory and LDS sixteen bytes at a time.
+template <uint32_t L, uint32_t K, uint32_t BITS> struct DenseFixed {
+    static constexpr uint32_t TB = K * BITS;                       // a thread's bytes of the fixed-width stream
+    static constexpr uint32_t NX = (TB + 3u) / 4u;                 // as 32-bit words
+    static constexpr uint32_t NR = TB % 4u == 0u ? NX : TB / 4u + 2u;   // aligned words that cover them at any offset
+    static constexpr uint32_t FIXED_WORDS = kDenseBlock * TB / 4u;  // per workgroup (256 * TB is a multiple of 16)
+    static constexpr uint32_t DENSE_WORDS = kDenseBlock * kDenseWordsPerThread;
+    static_assert(TB <= kDenseThreadBytes && FIXED_WORDS % 4u == 0u, "partition");
+};
+
+// keeps the first `valid_bits` bits of a bit string held in NX words
+template <uint32_t NX>
+__device__ __forceinline__ void keep_bits(uint32_t (&x)[NX], uint32_t valid_bits)
+{
+#pragma unroll
+    for (uint32_t i = 0; i < NX; ++i) {
+        const uint32_t have = valid_bits > 32u * i ? valid_bits - 32u * i : 0u;
+        x[i] &= have >= 32u ? 0xffffffffu : ((1u << have) - 1u);
+    }
+}
+
+// bits of the thread's share that belong to indices below n
+template <uint32_t K, uint32_t BITS>
+__device__ __forceinline__ uint32_t dense_valid_bits(const DenseArgs& a, uint64_t first_word)
+{
+    const uint64_t first = first_word * K;
+    if (first >= a.n) return 0u;
+    const uint64_t left = a.n - first;
+    return left >= 8u * K ? 8u * K * BITS : (uint32_t)left * BITS;
+}
+
+template <uint32_t L, uint32_t K, uint32_t BITS>
+__global__ __launch_bounds__(kDenseBlock) void dense_pack_fixed_kernel(DenseArgs a)
+{
+    using D = DenseFixed<L, K, BITS>;
+    __shared__ __align__(16) DenseStage st;
+    const uint32_t tid = threadIdx.x;
+    const uint64_t block_byte0 = (uint64_t)blockIdx.x * kDenseBlock * D::TB;
+    const uint64_t block_w0 = (uint64_t)blockIdx.x * D::DENSE_WORDS;
+    const uint32_t vectors_in = dense_block_bytes(a, block_byte0) / 16u;
+    const uint4* fixed128 = reinterpret_cast<const uint4*>(a.fixed + block_byte0);
+    uint4* stage128 = reinterpret_cast<uint4*>(st.fixed);
+    for (uint32_t i = tid; i < D::FIXED_WORDS / 4u; i += kDenseBlock)
+        stage128[i] = i < vectors_in ? fixed128[i] : make_uint4(0u, 0u, 0u, 0u);
+    __syncthreads();
+
+    // the thread's TB bytes, from the aligned words around them
+    const uint32_t byte0 = tid * D::TB;
+    uint32_t r[D::NR], x[D::NX];
+#pragma unroll
+    for (uint32_t i = 0; i < D::NR; ++i) {
+        const uint32_t w = byte0 / 4u + i;
+        r[i] = w < D::FIXED_WORDS ? st.fixed[w] : 0u;
+    }
+    if constexpr (D::TB % 4u == 0u) {
+#pragma unroll
+        for (uint32_t i = 0; i < D::NX; ++i) x[i] = r[i];
+    } else {
+#pragma unroll
+        for (uint32_t i = 0; i < D::NX; ++i) x[i] = __builtin_amdgcn_alignbyte(r[i + 1], r[i], byte0 & 3u);
+    }
+    // indices at or beyond n count as digit 0, whatever the padding holds
+    keep_bits<D::NX>(x, dense_valid_bits<K, BITS>(a, block_w0 + (uint64_t)tid * kDenseWordsPerThread));
+
+    uint32_t value[kDenseWordsPerThread];
+#pragma unroll
+    for (uint32_t j = 0; j < kDenseWordsPerThread; ++j) {
+        uint32_t v = 0u;
+#pragma unroll
+        for (int d = (int)K - 1; d >= 0; --d) {       // sum_d c_d L^d, highest digit first
+            constexpr uint32_t MASK = (1u << BITS) - 1u;
+            const uint32_t bit = (j * K + (uint32_t)d) * BITS, k = bit >> 5, sh = bit & 31u;
+            uint32_t c = x[k] >> sh;
+            if (sh + BITS > 32u) c |= x[k + 1] << (32u - sh);
+            v = v * L + (c & MASK);
+        }
+        value[j] = v;
+    }
+    uint4* mine = reinterpret_cast<uint4*>(st.dense + tid * kDenseWordsPerThread);
+    mine[0] = make_uint4(value[0], value[1], value[2], value[3]);
+    mine[1] = make_uint4(value[4], value[5], value[6], value[7]);
+    __syncthreads();
+    const uint4* out128 = reinterpret_cast<const uint4*>(st.dense);
+    uint4* dense128 = reinterpret_cast<uint4*>(a.dense + block_w0);
+    for (uint32_t i = tid; i < D::DENSE_WORDS / 4u; i += kDenseBlock)
+        if (block_w0 + 4u * i < a.dense_total) dense128[i] = out128[i];      // dense_total is a multiple of 4
+}
+
+template <uint32_t L, uint32_t K, uint32_t BITS>
+__global__ __launch_bounds__(kDenseBlock) void dense_unpack_fixed_kernel(DenseArgs a)
+{
+    using D = DenseFixed<L, K, BITS>;
+    __shared__ __align__(16) DenseStage st;
+    const uint32_t tid = threadIdx.x;
+    const uint64_t block_byte0 = (uint64_t)blockIdx.x * kDenseBlock * D::TB;
+    const uint64_t block_w0 = (uint64_t)blockIdx.x * D::DENSE_WORDS;
+    const uint4* dense128 = reinterpret_cast<const uint4*>(a.dense + block_w0);
+    uint4* in128 = reinterpret_cast<uint4*>(st.dense);
+    for (uint32_t i = tid; i < D::DENSE_WORDS / 4u; i += kDenseBlock)
+        in128[i] = block_w0 + 4u * i < a.dense_total ? dense128[i] : make_uint4(0u, 0u, 0u, 0u);
+    __syncthreads();
+
+    const uint4* mine = reinterpret_cast<const uint4*>(st.dense + tid * kDenseWordsPerThread);
+    const uint4 lo4 = mine[0], hi4 = mine[1];
+    const uint32_t value[kDenseWordsPerThread] = {lo4.x, lo4.y, lo4.z, lo4.w, hi4.x, hi4.y, hi4.z, hi4.w};
+    uint32_t x[D::NX];
+#pragma unroll
+    for (uint32_t i = 0; i < D::NX; ++i) x[i] = 0u;
+    auto put = [&](uint32_t index, uint32_t c) __attribute__((always_inline)) {
+        const uint32_t bit = index * BITS, k = bit >> 5, sh = bit & 31u;
+        x[k] |= c << sh;
+        if (sh + BITS > 32u) x[k + 1] |= c >> (32u - sh);
+    };
+#pragma unroll
+    for (uint32_t j = 0; j < kDenseWordsPerThread; ++j) {
+        if constexpr (L == 3u && K == 20u) {
+            // two halves of ten digits, each below 3^10 < 2^16, taken two digits at a time:
+            // y / 9 = (y * 58255) >> 19 exactly for y < 2^16, and for the remainder r in 0..8
+            // the two codes c0 + 4 c1 = r + r / 3 with r / 3 = (r * 11) >> 5.  All factors lie
+            // below 2^24 and the products fit 32 bits, which the compiler sees: it picks
+            // the multiplies of the fast 24-bit kind.
+            const uint32_t top = value[j] / 59049u;
+            uint32_t half[2] = {value[j] - top * 59049u, top};
+#pragma unroll
+            for (uint32_t h = 0; h < 2u; ++h) {
+                uint32_t y = half[h] & 0xffffu;       // (a word that is not a valid number stays in range)
+#pragma unroll
+                for (uint32_t d = 0; d < 10u; d += 2u) {
+                    const uint32_t q = (y * 58255u) >> 19;
+                    const uint32_t r = y - q * 9u;
+                    put(j * K + 10u * h + d, r + ((r * 11u) >> 5));     // an even index: four bits inside one word
+                    y = q;
+                }
+            }
+        } else {
+            uint32_t v = value[j];
+#pragma unroll
+            for (uint32_t d = 0; d < K; ++d) {
+                const uint32_t q = v / L;
+                put(j * K + d, v - q * L);
+                v = q;
+            }
+        }
+    }
+    keep_bits<D::NX>(x, dense_valid_bits<K, BITS>(a, block_w0 + (uint64_t)tid * kDenseWordsPerThread));
+
+    const uint32_t byte0 = tid * D::TB;
+    if constexpr (D::TB % 4u == 0u) {
+#pragma unroll
+        for (uint32_t i = 0; i < D::NX; ++i) st.fixed[byte0 / 4u + i] = x[i];
+    } else {
+        unsigned char* bytes = reinterpret_cast<unsigned char*>(st.fixed) + byte0;
+#pragma unroll
+        for (uint32_t b = 0; b < D::TB; ++b) bytes[b] = (unsigned char)(x[b / 4u] >> (8u * (b & 3u)));
+    }
+    __syncthreads();
+    const uint32_t vectors_out = dense_block_bytes(a, block_byte0) / 16u;
+    const uint4* stage128 = reinterpret_cast<const uint4*>(st.fixed);
+    uint4* fixed128 = reinterpret_cast<uint4*>(a.fixed + block_byte0);
+    for (uint32_t i = tid; i < vectors_out; i += kDenseBlock) fixed128[i] = stage128[i];
+}
+
 // ---------------------------------------------------------------------------
 // sum_i (a_i - b_i)^2 in binary64 (the sigma_z^2 estimate behind Thm 4's parameter
 // choice).  Two passes over a fixed grid so that the reduction order, and hence
@@ -553,8 +725,16 @@ static int dense_common(const void* fixed, const void* dense, size_t n, uint32_t
     const uint64_t blocks = (threads + 255u) / 256u;
     if (blocks >= ((uint64_t)1 << 31)) return NDQ_EUNSUPPORTED;
     if (per_thread_bytes > kDenseThreadBytes) return NDQ_EUNSUPPORTED;   // cannot happen for levels <= 256
-    if (pack) return launch(dense_pack_kernel, dim3((uint32_t)blocks), dim3(kDenseBlock), (hipStream_t)stream, a);
-    return launch(dense_unpack_kernel, dim3((uint32_t)blocks), dim3(kDenseBlock), (hipStream_t)stream, a);
+    const dim3 grid((uint32_t)blocks), block(kDenseBlock);
+    hipStream_t s = (hipStream_t)stream;
+    if (levels == 3u && a.k == 20u && a.bits == 2u)
+        return pack ? launch((dense_pack_fixed_kernel<3, 20, 2>), grid, block, s, a)
+                    : launch((dense_unpack_fixed_kernel<3, 20, 2>), grid, block, s, a);
+    if (levels == 5u && a.k == 13u && a.bits == 3u)
+        return pack ? launch((dense_pack_fixed_kernel<5, 13, 3>), grid, block, s, a)
+                    : launch((dense_unpack_fixed_kernel<5, 13, 3>), grid, block, s, a);
+    if (pack) return launch(dense_pack_kernel, grid, block, s, a);
+    return launch(dense_unpack_kernel, grid, block, s, a);
 }
 
 int ndq_dense_pack(const void* codes, size_t n, uint32_t levels, void* dense_out, void* stream)
