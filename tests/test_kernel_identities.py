@@ -161,3 +161,29 @@ def test_magic_constant_addition_is_round_to_nearest_even():
         word = struct.unpack("<I", struct.pack("<f", float(s)))[0]
         for bits in (1, 2, 4):
             assert (word & ((1 << bits) - 1)) == int(rint(t)) % (1 << bits)
+
+
+def test_base_three_digits_two_at_a_time_with_small_multiplies():
+    # the dense base-3 stream (Table 1's log2(3) bits per index): a 32-bit word holds 20 digits;
+    # its halves below 3^10 fit 16 bits, where y // 9 == (y * 58255) >> 19 with a product below
+    # 2^32 and factors below 2^24, and the two 2-bit codes c0 + 4 c1 of a remainder r = c0 + 3 c1
+    # are r + r // 3 with r // 3 == (r * 11) >> 5
+    assert 3 ** 20 < 2 ** 32 <= 3 ** 21 and 3 ** 10 < 2 ** 16
+    for y in range(1 << 16):
+        assert (y * 58255) >> 19 == y // 9 and y * 58255 < 1 << 32
+    for r in range(9):
+        assert r + ((r * 11) >> 5) == (r % 3) + 4 * (r // 3)
+    rng = random.Random(17)
+    for _ in range(2000):
+        digits = [rng.randrange(3) for _ in range(20)]
+        value = sum(c * 3 ** d for d, c in enumerate(digits))
+        top = value // 59049
+        got = []
+        for y in (value - top * 59049, top):
+            for _pair in range(5):
+                q = (y * 58255) >> 19
+                r = y - 9 * q
+                pair = r + ((r * 11) >> 5)
+                got += [pair & 3, pair >> 2]
+                y = q
+        assert got == digits
