@@ -1,12 +1,13 @@
 // libndq, worker side (gfx950): max-norm scale factors, DQSG / NDQSG encoders.
 // See include/ndq.h for the contract.
 //
-// Every kernel of the library is a streaming pass: one wave owns one tile of
-// consecutive elements, issues all of its 16-byte loads up front, regenerates
-// the dither with Philox in registers and writes coalesced vectors.  Nothing
-// is a contraction, so no MFMA; LDS only transposes the small packed codes into
-// stream order and, for buckets of two or four tiles, carries the tile maxima
-// between the waves of a workgroup.
+// Every kernel of the library is a streaming pass: a wave owns a tile of
+// consecutive elements at a time (one tile per wave in the short-vector kernels,
+// tile after tile in the persistent ones), loads it with 16-byte loads,
+// regenerates the dither with Philox in registers and writes coalesced vectors.
+// Nothing is a contraction, so no MFMA; LDS only transposes the small packed
+// codes into stream order and, for buckets of two or four tiles, carries the
+// tile maxima between the waves of a workgroup.
 #include <hip/hip_runtime.h>
 
 #include <type_traits>
@@ -23,7 +24,7 @@ namespace ndq {
 struct EncodeArgs {
     const void* g;
     unsigned char* codes;
-    float* steps;          // written (fused / preset) or read (two-pass)
+    float* steps;          // written (fused / preset) or read (two-pass, or a step handed over in device memory)
     Tiling tl;
     uint64_t index0;       // dither offset of element 0
     uint64_t total_bytes;  // size of the packed stream incl. zero padding
@@ -216,6 +217,19 @@ __device__ __forceinline__ void encode_tile(const EncodeArgs& a, const TileRef& 
     if (lane == 0) *(uint64_t*)(stage + (size_t)EncTile<DT>::N / 8 * bits) = 0;  // pad unit
 }
 
+// Copies a tile's packed codes from the wave's stage to the stream, 8 bytes per lane.
+__device__ __forceinline__ void stage_to_stream(const EncodeArgs& a, const TileRef& t, uint32_t bits,
+                                                const unsigned char* stage, int lane)
+{
+    const uint64_t byte0 = (t.start >> 3) * bits;                 // tile start is a multiple of 64
+    const bool last = t.start + t.len == a.tl.n;
+    const uint64_t nbytes = last ? a.total_bytes - byte0 : (uint64_t)(t.len >> 3) * bits;
+    const uint32_t units = (uint32_t)(nbytes >> 3);
+    uint64_t* dst = (uint64_t*)(a.codes + byte0);
+    const uint64_t* src = (const uint64_t*)stage;
+    for (uint32_t u = lane; u < units; u += kWave) dst[u] = src[u];
+}
+
 // Occupancy target.  The bfloat16 encoder is bound by instruction issue with a
 // burst of loads at the start of every tile; eight waves per SIMD (64 registers)
 // hide that burst better than four (+8 % measured).  The binary32 encoder moves
@@ -274,28 +288,7 @@ void encode_kernel(EncodeArgs a)
         encode_tile<DT, MODE, FUSED, false, MULTI>(a, t, tile_id, regs, kappa, true, stage, lane);
     }
     wave_lds_sync();     // a wave copies out only the stage it filled itself
-    if (t.len != 0) {
-        const uint64_t byte0 = (t.start >> 3) * bits;                 // tile start is a multiple of 64
-        const bool last = t.start + t.len == a.tl.n;
-        const uint64_t nbytes = last ? a.total_bytes - byte0 : (uint64_t)(t.len >> 3) * bits;
-        const uint32_t units = (uint32_t)(nbytes >> 3);
-        uint64_t* dst = (uint64_t*)(a.codes + byte0);
-        const uint64_t* src = (const uint64_t*)stage;
-        for (uint32_t u = lane; u < units; u += kWave) dst[u] = src[u];
-    }
-}
-
-// Copies a tile's packed codes from the wave's stage to the stream, 8 bytes per lane.
-__device__ __forceinline__ void stage_to_stream(const EncodeArgs& a, const TileRef& t, uint32_t bits,
-                                                const unsigned char* stage, int lane)
-{
-    const uint64_t byte0 = (t.start >> 3) * bits;                 // tile start is a multiple of 64
-    const bool last = t.start + t.len == a.tl.n;
-    const uint64_t nbytes = last ? a.total_bytes - byte0 : (uint64_t)(t.len >> 3) * bits;
-    const uint32_t units = (uint32_t)(nbytes >> 3);
-    uint64_t* dst = (uint64_t*)(a.codes + byte0);
-    const uint64_t* src = (const uint64_t*)stage;
-    for (uint32_t u = lane; u < units; u += kWave) dst[u] = src[u];
+    if (t.len != 0) stage_to_stream(a, t, bits, stage, lane);
 }
 
 // The same for a full tile that is not the vector's last, with the code width known
