@@ -408,6 +408,16 @@ def main():
         extra("code_entropy_b%d" % b0, lambda: ndq.ndq_code_entropy(bufs.codes[0], n, b0, hist, ent),
               pk0, "histogram + entropy of worker 0's index stream")
         entropy0 = float(ent.item())
+        # the same call on streams long enough to stream: the 4n bytes of `scratch` read as 2-bit
+        # and as 8-bit codes (any byte is a valid group of such codes)
+        raw = scratch.view(torch.uint8)
+        hist2 = torch.empty(4, dtype=torch.int64, device="cuda")
+        hist8 = torch.empty(256, dtype=torch.int64, device="cuda")
+        ent8 = torch.empty(1, dtype=torch.float64, device="cuda")
+        extra("code_entropy_b2_long", lambda: ndq.ndq_code_entropy(raw, 16 * n, 2, hist2, ent8), 4 * n,
+              "a 2-bit stream of 16 n codes (4n bytes)")
+        extra("code_entropy_b8_long", lambda: ndq.ndq_code_entropy(raw, 4 * n, 8, hist8, ent8), 4 * n,
+              "an 8-bit stream of 4 n codes (4n bytes)")
         # bits per gradient element that each worker sends (Sec. 4, the kind of number in
         # Table 2, here on the synthetic workload): fixed-width codes, and what an ideal
         # entropy coder would leave of them; both with the 32-bit step of every bucket

@@ -169,9 +169,10 @@ constexpr uint32_t kSmallBlocks = 256;
 constexpr uint32_t kSmallThreads = 1024;
 constexpr int kSmallInFlight = 8;
 
-__device__ __forceinline__ void count_small(uint32_t w, uint32_t bits, uint32_t& c1, uint32_t& c2, uint32_t& c3)
+template <int BITS>
+__device__ __forceinline__ void count_small(uint32_t w, uint32_t& c1, uint32_t& c2, uint32_t& c3)
 {
-    if (bits == 1u) {
+    if (BITS == 1) {
         c1 += __builtin_popcount(w);
     } else {
         const uint32_t lo = w & 0x55555555u, hi = (w >> 1) & 0x55555555u;
@@ -181,16 +182,21 @@ __device__ __forceinline__ void count_small(uint32_t w, uint32_t bits, uint32_t&
     }
 }
 
-__device__ __forceinline__ void count_small(const uint4& x, uint32_t bits, uint32_t& c1, uint32_t& c2, uint32_t& c3)
+template <int BITS>
+__device__ __forceinline__ void count_small(const uint4& x, uint32_t& c1, uint32_t& c2, uint32_t& c3)
 {
-    count_small(x.x, bits, c1, c2, c3); count_small(x.y, bits, c1, c2, c3);
-    count_small(x.z, bits, c1, c2, c3); count_small(x.w, bits, c1, c2, c3);
+    count_small<BITS>(x.x, c1, c2, c3); count_small<BITS>(x.y, c1, c2, c3);
+    count_small<BITS>(x.z, c1, c2, c3); count_small<BITS>(x.w, c1, c2, c3);
 }
 
+// (the code width is a template parameter: as a run-time value it put a branch around every
+// word's counting, and the loop then waited for all its loads before the first count)
+template <int BITS>
 __global__ __launch_bounds__(kSmallThreads) void histogram_small_kernel(const uint4* __restrict__ vec, uint64_t n,
-                                                                        uint32_t bits, unsigned long long* hist,
+                                                                        unsigned long long* hist,
                                                                         double* entropy_out)
 {
+    constexpr uint32_t bits = BITS;
     __shared__ uint32_t part[3][kSmallThreads / 64];
     __shared__ double term[256];
     __shared__ unsigned long long few[4];
@@ -208,9 +214,9 @@ __global__ __launch_bounds__(kSmallThreads) void histogram_small_kernel(const ui
 #pragma unroll
         for (int j = 0; j < kSmallInFlight; ++j) x[j] = vec[u + (uint64_t)j * stride];
 #pragma unroll
-        for (int j = 0; j < kSmallInFlight; ++j) count_small(x[j], bits, c[0], c[1], c[2]);
+        for (int j = 0; j < kSmallInFlight; ++j) count_small<BITS>(x[j], c[0], c[1], c[2]);
     }
-    for (; u < vectors; u += stride) count_small(vec[u], bits, c[0], c[1], c[2]);
+    for (; u < vectors; u += stride) count_small<BITS>(vec[u], c[0], c[1], c[2]);
     const uint32_t tail_bits = (uint32_t)((n * bits) & 127u);
     if (blockIdx.x == 0 && tid == 0 && tail_bits != 0u) {
         const uint4 x = vec[vectors];
@@ -219,7 +225,7 @@ __global__ __launch_bounds__(kSmallThreads) void histogram_small_kernel(const ui
         for (uint32_t j = 0; j < 4u; ++j) {
             const uint32_t have = tail_bits > 32u * j ? tail_bits - 32u * j : 0u;
             const uint32_t mask = have >= 32u ? 0xffffffffu : ((1u << have) - 1u);
-            count_small(w[j] & mask, bits, c[0], c[1], c[2]);
+            count_small<BITS>(w[j] & mask, c[0], c[1], c[2]);
         }
     }
 #pragma unroll
@@ -661,8 +667,11 @@ int ndq_code_entropy(const void* codes, size_t n, uint32_t bits, uint64_t* hist_
         uint64_t blocks = (vectors + kSmallInFlight * kSmallThreads - 1) / (kSmallInFlight * kSmallThreads);
         if (blocks > kSmallBlocks) blocks = kSmallBlocks;
         if (blocks == 0u) blocks = 1u;
-        return launch(histogram_small_kernel, dim3((uint32_t)blocks), dim3(kSmallThreads), s, (const uint4*)codes,
-                      (uint64_t)n, bits, (unsigned long long*)hist_out, entropy_out);
+        if (bits == 1u)
+            return launch(histogram_small_kernel<1>, dim3((uint32_t)blocks), dim3(kSmallThreads), s,
+                          (const uint4*)codes, (uint64_t)n, (unsigned long long*)hist_out, entropy_out);
+        return launch(histogram_small_kernel<2>, dim3((uint32_t)blocks), dim3(kSmallThreads), s,
+                      (const uint4*)codes, (uint64_t)n, (unsigned long long*)hist_out, entropy_out);
     }
     const uint64_t units = (uint64_t)n >> 5;
     uint64_t blocks = (units + kHistThreads - 1) / kHistThreads;
