@@ -123,12 +123,12 @@ __device__ __forceinline__ void encode_tile(const EncodeArgs& a, const TileRef& 
         float step;
         if (FUSED) {
             step = step_from_kappa(kappa, a.qp.levels);
-            if (BITSW != 0 && FULL) a.steps[t.bucket] = step;     // every lane, the same value: no branch around the store
+            if (REFILL) a.steps[t.bucket] = step;     // every lane, the same value: no branch around the store
             else if (lane == 0 && writes_step) a.steps[t.bucket] = step;
         } else if (a.preset_step > 0.0f) {
             step = a.preset_step;
             // (the streaming kernel writes the preset step itself, outside its tile loop)
-            if (!(BITSW != 0 && FULL) && tile_id == 0 && lane == 0) a.steps[0] = step;
+            if (!REFILL && tile_id == 0 && lane == 0) a.steps[0] = step;
         } else {
             step = a.steps[t.bucket];
         }
@@ -242,7 +242,9 @@ template <int DT> struct EncWaves { static constexpr int W = DT == 1 ? NDQ_ENC_W
 // bucket is 2 or 4 tiles, all held by the waves of one workgroup.  In all three
 // the max-norm is found in registers and the step written; otherwise the step is
 // the preset one or read from `steps` (absmax + steps_from_kappa kernels).
-template <int DT, int MODE, bool FUSED, bool MULTI, bool BLOCK>
+// BITSW: the code width when it is 1, 2 or 4 (the common ones: the packing and the store of a
+// row's codes are then straight-line code); 0: any width, read from the arguments.
+template <int DT, int MODE, bool FUSED, bool MULTI, bool BLOCK, int BITSW = 0>
 __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(EncWaves<DT>::W)))
 void encode_kernel(EncodeArgs a)
 {
@@ -254,7 +256,7 @@ void encode_kernel(EncodeArgs a)
 
     const uint32_t tile_id = blockIdx.x * kWavesPerBlock + wave;
     const TileRef t = locate_tile(a.tl, tile_id, TILE);
-    const uint32_t bits = a.qp.bits;
+    const uint32_t bits = BITSW ? (uint32_t)BITSW : a.qp.bits;
     if (BLOCK) {
         // A bucket of 2 or 4 tiles lies inside one workgroup (tile ids are consecutive
         // and buckets start at multiples of their length): the waves exchange their
@@ -280,12 +282,12 @@ void encode_kernel(EncodeArgs a)
         TileRegs<DT> regs;
         load_tile<DT, true>(a.g, t, lane, regs);
         const float kappa = (FUSED && !MULTI) ? tile_max<DT>(regs) : 0.0f;
-        encode_tile<DT, MODE, FUSED, true, MULTI>(a, t, tile_id, regs, kappa, true, stage, lane);
+        encode_tile<DT, MODE, FUSED, true, MULTI, BITSW>(a, t, tile_id, regs, kappa, true, stage, lane);
     } else if (t.len != 0) {
         TileRegs<DT> regs;
         load_tile<DT, false>(a.g, t, lane, regs);
         const float kappa = (FUSED && !MULTI) ? tile_max<DT>(regs) : 0.0f;
-        encode_tile<DT, MODE, FUSED, false, MULTI>(a, t, tile_id, regs, kappa, true, stage, lane);
+        encode_tile<DT, MODE, FUSED, false, MULTI, BITSW>(a, t, tile_id, regs, kappa, true, stage, lane);
     }
     wave_lds_sync();     // a wave copies out only the stage it filled itself
     if (t.len != 0) stage_to_stream(a, t, bits, stage, lane);
@@ -556,6 +558,18 @@ static int run_encode(const EncodeArgs& a, bool fused, bool multi, uint32_t buck
     const dim3 grid(blocks_for(a.tl.total_tiles)), block(kBlock);
     if (a.waves_log2 != 0u) return launch((encode_kernel<DT, MODE, true, false, true>), grid, block, s, a);
     if (multi) return launch((encode_kernel<DT, MODE, true, true, false>), grid, block, s, a);
+    if constexpr (MODE == kDqNarrow || MODE == kNestedPow2Bounded || MODE == kNestedPow2) {
+        const uint32_t bits = a.qp.bits;
+        if (fused) {
+            if (bits == 1u) return launch((encode_kernel<DT, MODE, true, false, false, 1>), grid, block, s, a);
+            if (bits == 2u) return launch((encode_kernel<DT, MODE, true, false, false, 2>), grid, block, s, a);
+            if (bits == 4u) return launch((encode_kernel<DT, MODE, true, false, false, 4>), grid, block, s, a);
+        } else {
+            if (bits == 1u) return launch((encode_kernel<DT, MODE, false, false, false, 1>), grid, block, s, a);
+            if (bits == 2u) return launch((encode_kernel<DT, MODE, false, false, false, 2>), grid, block, s, a);
+            if (bits == 4u) return launch((encode_kernel<DT, MODE, false, false, false, 4>), grid, block, s, a);
+        }
+    }
     if (fused) return launch((encode_kernel<DT, MODE, true, false, false>), grid, block, s, a);
     return launch((encode_kernel<DT, MODE, false, false, false>), grid, block, s, a);
 }
