@@ -436,6 +436,16 @@ def main():
               c3.numel() + dense.numel(), "2-bit stream -> 1.6 bits per index")
         extra("dense_unpack_L3", lambda: ndq.ndq_dense_unpack(dense, n, lv, back),
               c3.numel() + dense.numel(), "")
+        # the same transcoders on streams long enough to stream: the 4n bytes of `scratch` read as
+        # n dense words (any word expands to twenty valid three-level codes), expanded and packed again
+        n_long = 20 * n
+        fixed_long = torch.empty(ndq.ndq_packed_bytes(n_long, 2), dtype=torch.uint8, device="cuda")
+        dense_long = torch.empty(ndq.ndq_dense_bytes(n_long, lv), dtype=torch.uint8, device="cuda")
+        extra("dense_unpack_L3_long", lambda: ndq.ndq_dense_unpack(raw, n_long, lv, fixed_long),
+              raw.numel() + fixed_long.numel(), "20 n codes: 4n bytes dense -> 5n bytes at fixed width")
+        extra("dense_pack_L3_long", lambda: ndq.ndq_dense_pack(fixed_long, n_long, lv, dense_long),
+              fixed_long.numel() + dense_long.numel(), "")
+        del fixed_long, dense_long
         ws = torch.empty(ndq.ndq_sqdiff_workspace() // 8, dtype=torch.float64, device="cuda")
         sq = torch.empty(1, dtype=torch.float64, device="cuda")
         other_f32 = torch.empty(n, dtype=torch.float32, device="cuda").normal_()
