@@ -1118,6 +1118,13 @@ def test_randomized_differential_against_oracle():
         mc, ms = ndq.ndq_nested_encode(gd, delta, levels, M, alpha, bucket, d_g)
         assert np.array_equal(ms.cpu().numpy(), t_ref), tag
         assert mc.cpu().numpy().tobytes() == m_ref.tobytes(), tag
+        if preset and delta > 0.0:
+            # the same preset step handed over in device memory
+            step_d = torch.tensor([delta], dtype=torch.float32, device=dev)
+            c2, s2 = ndq.ndq_dq_encode_with_step(gd, step_d, levels, d_g)
+            assert torch.equal(c2, codes) and torch.equal(s2, steps), tag
+            m2, t2 = ndq.ndq_nested_encode_with_step(gd, step_d, M, alpha, d_g)
+            assert torch.equal(m2, mc) and torch.equal(t2, ms), tag
         S_ref = ref.copy()
         oracle.nested_decode(m_ref, n, M, bucket, t_ref, d_o, S_ref, 1.0, out=S_ref, alpha=alpha)
         S = torch.from_numpy(ref).to(dev)
