@@ -7,7 +7,9 @@ so that vectors of a few hundred thousand elements -- small enough for the oracl
 -- go through the persistent kernels on twelve waves: several tiles per wave (the
 next tile's rows loaded into the registers of the rows just consumed, even and odd
 tile counts), waves with one tile fewer, and a ragged last tile.  Everything is
-compared with the oracle bit for bit.
+compared with the oracle bit for bit.  (The persistent encoder serves bfloat16 input;
+binary32 input takes the one-tile-per-wave encoder whatever the environment says, and
+its cases here run through that.)
 """
 import os
 import sys
