@@ -460,14 +460,21 @@ typedef const __attribute__((address_space(4))) ChainArgs* ChainArgsPtr;
 
 struct ChainCodes { uint32_t w[kChainRows]; float step; };
 
-// a lane's eight codes of a row: `WIDTH` bytes at a multiple of WIDTH (full tiles)
+// a lane's eight codes of a row: `WIDTH` bytes at a multiple of WIDTH (full tiles).
+// `limit`: the largest byte offset inside the tile's codes that may be read (a multiple of
+// WIDTH); lanes past it read there instead.  Whole tiles pass 0xFFFFFFFF; for the vector's
+// ragged last tile it is the stream's last WIDTH bytes, so that the tile can be fetched and
+// folded like a whole one (what lanes past the end compute is never stored).
 template <int WIDTH>
-__device__ __forceinline__ void stream_fetch(const unsigned char* codes, uint64_t start, int lane, ChainCodes& f)
+__device__ __forceinline__ void stream_fetch(const unsigned char* codes, uint64_t start, int lane, ChainCodes& f,
+                                             uint32_t limit = 0xFFFFFFFFu)
 {
-    const unsigned char* mine = codes + (start >> 3) * WIDTH + (uint32_t)lane * WIDTH;
+    const unsigned char* tile = codes + (start >> 3) * WIDTH;
 #pragma unroll
     for (int r = 0; r < kChainRows; ++r) {
-        const unsigned char* p = mine + (uint32_t)(r * kWave) * WIDTH;
+        uint32_t off = (uint32_t)(r * kWave + lane) * WIDTH;
+        off = off < limit ? off : limit;
+        const unsigned char* p = tile + off;
         f.w[r] = WIDTH == 1 ? (uint32_t)*p : WIDTH == 2 ? (uint32_t)*(const uint16_t*)p : *(const uint32_t*)p;
     }
     f.step = 0.0f;     // whole tiles take their steps from the step lanes of the kernel
@@ -668,6 +675,11 @@ __device__ __forceinline__ void stream_ragged_tile(ChainArgsPtr a, uint64_t star
 // RAGGED: the vector ends in a ragged tile.  An instantiation of its own, because the mere
 // presence of that code in the kernel measured 6 % on the main loop (config 5, which has
 // no ragged tile: 215 against 203 us) although the loop's instructions are the same.
+// Without PIPED one wave folds that tile with guarded code of its own (stream_ragged_tile).
+// With PIPED it is one more tile of the loop: its codes are fetched with the lane offsets
+// clamped to the end of the stream, it is folded like a whole tile, and only its copy-out is
+// guarded (a persistent ragged launch in the plain form is 7-9 % slower than one tile per
+// wave at two to three tiles per wave slot, where the piped form is 1-5 % faster).
 //
 // PIPED (persistent launches of whole tiles): two changes that only pay together.
 // (1) A lane's eight consecutive results are 32 bytes of the output, so a 16-byte store per
@@ -688,7 +700,7 @@ __global__ __launch_bounds__(kBlock)
 __attribute__((amdgpu_waves_per_eu(PIPED ? NDQ_CHAIN_PIPED_WAVES : kChainStreamWaves, PIPED ? NDQ_CHAIN_PIPED_WAVES : kChainStreamWaves)))
 void chain_stream_kernel(ChainArgs a_by_value)
 {
-    static_assert(!(RAGGED && PIPED), "the ragged tile is folded by the plain form only");
+    constexpr bool TAIL = RAGGED && PIPED;     // the ragged tile runs through the main loop
     const ChainArgsPtr a = (ChainArgsPtr)__builtin_amdgcn_kernarg_segment_ptr();
     const int lane = threadIdx.x & (kWave - 1);
     const uint32_t stride = gridDim.x * kWavesPerBlock;
@@ -697,6 +709,7 @@ void chain_stream_kernel(ChainArgs a_by_value)
     __shared__ __align__(16) float out_stage_all[PIPED ? kWavesPerBlock : 1][PIPED ? kChainTile : 4];
     float* out_stage = out_stage_all[PIPED ? wave_in_block : 0u];
     const uint32_t tiles = a->tile_begin;                  // whole tiles: ids 0 .. tiles-1
+    const uint32_t tiles_all = TAIL ? tiles + 1u : tiles;  // TAIL: and the ragged one, id `tiles`
     const uint32_t W = a->W;
     const uint32_t tpb = a->tl.tiles_per_bucket;
     const bool one_bucket = a->tl.bucket_len == a->tl.n;   // bucket == 0
@@ -707,15 +720,28 @@ void chain_stream_kernel(ChainArgs a_by_value)
     // (one tile per wave), else to wave 0: at the start every SIMD is full and hides its
     // latencies; as a kernel of its own, or at the end, it would run alone at a fifth of the rate.
     const uint64_t whole = (uint64_t)tiles * kChainTile;
-    if (RAGGED && whole < a->tl.n && first == (stride > tiles ? tiles : 0u))
+    if (RAGGED && !PIPED && whole < a->tl.n && first == (stride > tiles ? tiles : 0u))
         stream_ragged_tile<RMODE, W0, WR>(a, whole, (uint32_t)(a->tl.n - whole), one_bucket ? 0u : tiles / tpb, lane);
-    if (first >= tiles) return;
-    const uint32_t my_tiles = (tiles - first + stride - 1u) / stride;
+    if (first >= tiles_all) return;
+    const uint32_t my_tiles = (tiles_all - first + stride - 1u) / stride;
+    // TAIL: elements of the ragged tile, and per code width the last byte offset inside its
+    // codes that a lane may read: the stream is padded to a multiple of 16 bytes, the tile
+    // starts at one, so at least 16 bytes of it exist
+    const uint32_t tail_len = TAIL ? (uint32_t)(a->tl.n - whole) : 0u;
+    auto tail_limit = [&](uint32_t width) __attribute__((always_inline)) {
+        const uint64_t total = ((((uint64_t)a->tl.n * width + 7u) >> 3) + 15u) & ~(uint64_t)15u;
+        return (uint32_t)(total - (whole >> 3) * width) - width;
+    };
+    const uint32_t limit0 = TAIL ? tail_limit((uint32_t)W0) : 0xFFFFFFFFu;
+    const uint32_t limitr = TAIL ? tail_limit((uint32_t)WR) : 0xFFFFFFFFu;
+    auto limit_for = [&](uint32_t tile_id, uint32_t tail) __attribute__((always_inline)) {
+        return (TAIL && tile_id == tiles) ? tail : 0xFFFFFFFFu;
+    };
     uint32_t done = 0;
     if (my_tiles > 1u) __builtin_amdgcn_s_setprio(3);
 
     ChainCodes cur;
-    stream_fetch<W0>(a->w[0].codes, (uint64_t)first * kChainTile, lane, cur);
+    stream_fetch<W0>(a->w[0].codes, (uint64_t)first * kChainTile, lane, cur, limit_for(first, limit0));
     // PIPED: the dither of the row after the current one is always in flight; here the first row's
     PhiloxFlight fl;
     if (PIPED) {
@@ -729,7 +755,7 @@ void chain_stream_kernel(ChainArgs a_by_value)
     const uint32_t my_worker = (uint32_t)lane < W ? (uint32_t)lane : W - 1u;
     const float* my_steps = a->w[my_worker].steps;
     float steps_ahead = my_steps[one_bucket ? 0u : first / tpb];
-    for (uint32_t tile = first; tile < tiles; tile += stride) {
+    for (uint32_t tile = first; tile < tiles_all; tile += stride) {
         const uint64_t start = (uint64_t)tile * kChainTile;
         // where the dither after this tile's last row belongs: past the end after the last tile (unused)
         const uint64_t next_start = start + (uint64_t)stride * kChainTile;
@@ -737,7 +763,7 @@ void chain_stream_kernel(ChainArgs a_by_value)
         ChainCodes nxt;
         const float steps_here = steps_ahead;
         {
-            const uint32_t nt = tile + stride < tiles ? tile + stride : tile;
+            const uint32_t nt = tile + stride < tiles_all ? tile + stride : tile;
             steps_ahead = my_steps[one_bucket ? 0u : nt / tpb];
         }
         const float invs_here = inv_step(steps_here);
@@ -746,11 +772,11 @@ void chain_stream_kernel(ChainArgs a_by_value)
         };
         // first worker: DQSG, starts the sum; meanwhile the second worker's codes (or the next tile's)
         if (W > 1u) {
-            stream_fetch<WR>(a->w[1].codes, start, lane, nxt);
+            stream_fetch<WR>(a->w[1].codes, start, lane, nxt, limit_for(tile, limitr));
         } else {
-            const uint32_t nt = tile + stride < tiles ? tile + stride : tile;
+            const uint32_t nt = tile + stride < tiles_all ? tile + stride : tile;
             ChainCodes tmp;
-            stream_fetch<W0>(a->w[0].codes, (uint64_t)nt * kChainTile, lane, tmp);
+            stream_fetch<W0>(a->w[0].codes, (uint64_t)nt * kChainTile, lane, tmp, limit_for(nt, limit0));
             nxt = tmp;
         }
         {
@@ -770,11 +796,11 @@ void chain_stream_kernel(ChainArgs a_by_value)
         for (uint32_t w = 1; w < W; ++w) {
             // the codes of worker w are in `cur`; fetch worker w+1's, or the first worker's of the next tile
             if (w + 1u < W) {
-                stream_fetch<WR>(a->w[w + 1u].codes, start, lane, nxt);
+                stream_fetch<WR>(a->w[w + 1u].codes, start, lane, nxt, limit_for(tile, limitr));
             } else {
-                const uint32_t nt = tile + stride < tiles ? tile + stride : tile;
+                const uint32_t nt = tile + stride < tiles_all ? tile + stride : tile;
                 ChainCodes tmp;
-                stream_fetch<W0>(a->w[0].codes, (uint64_t)nt * kChainTile, lane, tmp);
+                stream_fetch<W0>(a->w[0].codes, (uint64_t)nt * kChainTile, lane, tmp, limit_for(nt, limit0));
                 nxt = tmp;
             }
             const DitherStream ds = {a->w[w].ds.key0, a->w[w].ds.key1, a->w[w].ds.step, a->w[w].ds.worker};
@@ -811,10 +837,25 @@ void chain_stream_kernel(ChainArgs a_by_value)
         }
         if (PIPED) {
             wave_lds_sync();
+            if (TAIL && tile == tiles) {       // the ragged tile: only the elements that exist
 #pragma unroll
-            for (int j = 0; j < (int)(kChainTile / (kWave * 4)); ++j) {
-                const float4 x = *(const float4*)(out_stage + j * (kWave * 4) + lane * 4);
-                store_streaming(out + j * (kWave * 4) + lane * 4, x.x, x.y, x.z, x.w);
+                for (int j = 0; j < (int)(kChainTile / (kWave * 4)); ++j) {
+                    const uint32_t e = (uint32_t)(j * (kWave * 4) + lane * 4);
+                    const float4 x = *(const float4*)(out_stage + e);
+                    if (e + 4u <= tail_len) {
+                        store_streaming(out + e, x.x, x.y, x.z, x.w);
+                    } else {
+                        if (e < tail_len) out[e] = x.x;
+                        if (e + 1u < tail_len) out[e + 1u] = x.y;
+                        if (e + 2u < tail_len) out[e + 2u] = x.z;
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < (int)(kChainTile / (kWave * 4)); ++j) {
+                    const float4 x = *(const float4*)(out_stage + j * (kWave * 4) + lane * 4);
+                    store_streaming(out + j * (kWave * 4) + lane * 4, x.x, x.y, x.z, x.w);
+                }
             }
             wave_lds_sync();     // the next tile's writes come after these reads
         }
@@ -946,9 +987,15 @@ static int launch_chain_stream(const ChainArgs& a, hipStream_t s)
     // per wave a fixed share would leave SIMDs idle at the end.
     const uint32_t tiles = a.tile_begin, slots = 1024u * kChainStreamWaves;
     const bool ragged = (uint64_t)tiles * kChainTile < a.tl.n;     // one more wave takes the ragged last tile
-    const bool persistent = tiles >= stream_tuning().chain_min_tiles_per_wave * slots;
-    const uint32_t blocks = persistent ? persistent_blocks(tiles, ragged ? slots : 1024u * NDQ_CHAIN_PIPED_WAVES)
+    // (the more workers a tile folds in, the earlier a persistent wave pays: W = 16 gains 3-4 % at
+    // one and a half tiles per wave slot, where W = 4 still loses 4 %)
+    const StreamTuning& tuning = stream_tuning();
+    const bool persistent = tiles >= tuning.chain_min_tiles_per_wave * slots ||
+                            (!tuning.threshold_from_env && a.W >= 8u && 2u * (uint64_t)tiles >= 3u * (uint64_t)slots);
+    const uint32_t blocks = persistent ? persistent_blocks(tiles + (ragged ? 1u : 0u), 1024u * NDQ_CHAIN_PIPED_WAVES)
                                        : blocks_for(tiles + (ragged ? 1u : 0u));
+    if (persistent && ragged)
+        return launch((chain_stream_kernel<RMODE, W0, WR, true, true>), dim3(blocks), dim3(kBlock), s, a);
     if (ragged) return launch((chain_stream_kernel<RMODE, W0, WR, true, false>), dim3(blocks), dim3(kBlock), s, a);
     if (persistent) return launch((chain_stream_kernel<RMODE, W0, WR, false, true>), dim3(blocks), dim3(kBlock), s, a);
     return launch((chain_stream_kernel<RMODE, W0, WR, false, false>), dim3(blocks), dim3(kBlock), s, a);

@@ -111,14 +111,19 @@ inline uint32_t blocks_for(uint32_t tiles) { return (tiles + kWavesPerBlock - 1)
 //   NDQ_STREAM_MAX_BLOCKS           cap on the persistent grid, in workgroups (0: none)
 struct StreamTuning {
     uint32_t enc_min_tiles_per_wave, chain_min_tiles_per_wave, max_blocks;
+    bool threshold_from_env;
 };
 
 inline const StreamTuning& stream_tuning()
 {
     static const StreamTuning t = [] {
-        StreamTuning v = {2u, 3u, 0u};     // measured: config 5 at 2^25 elements, encoders -3..-5 %, chain -5 % against 8 and 12
+        // measured over vector lengths, each kernel in both forms in one run: the persistent bfloat16
+        // encoders win by 3-9 % from two tiles per wave slot on, the persistent chain decoder by 2-9 %
+        // (chains of eight or more workers already from one and a half: see launch_chain_stream)
+        StreamTuning v = {2u, 2u, 0u, false};
         if (const char* e = getenv("NDQ_STREAM_MIN_TILES_PER_WAVE")) {
             v.enc_min_tiles_per_wave = v.chain_min_tiles_per_wave = (uint32_t)strtoul(e, nullptr, 10);
+            v.threshold_from_env = true;
         }
         if (const char* e = getenv("NDQ_STREAM_MAX_BLOCKS")) v.max_blocks = (uint32_t)strtoul(e, nullptr, 10);
         return v;
