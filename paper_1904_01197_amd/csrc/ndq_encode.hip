@@ -241,7 +241,7 @@ template <int DT> struct EncWaves { static constexpr int W = DT == 1 ? NDQ_ENC_W
 // FUSED: the bucket fits one tile.  MULTI: several buckets to a tile.  BLOCK: the
 // bucket is 2 or 4 tiles, all held by the waves of one workgroup.  In all three
 // the max-norm is found in registers and the step written; otherwise the step is
-// the preset one or read from `steps` (absmax + steps_from_kappa kernels).
+// the preset one or read from `steps` (written by the max-norm pass, or handed over).
 // BITSW: the code width when it is 1, 2 or 4 (the common ones: the packing and the store of a
 // row's codes are then straight-line code); 0: any width, read from the arguments.
 template <int DT, int MODE, bool FUSED, bool MULTI, bool BLOCK, int BITSW = 0>
@@ -416,8 +416,19 @@ __global__ void fill_zero_kernel(uint32_t* p, uint64_t n)
     if (i < n) p[i] = 0u;
 }
 
+// levels != 0: the bucket's step is wanted, not its max-norm.  The step rule is monotone in
+// kappa (an exact doubling, one correctly rounded division, a threshold), so the maximum of
+// the parts' steps is the step of the maximum: each part converts before its atomic, and no
+// pass over the buckets is needed afterwards.
+__device__ __forceinline__ uint32_t absmax_word(float m, uint32_t levels)
+{
+    // non-negative floats order like their bit patterns
+    return __float_as_uint(levels ? step_from_kappa(m, levels) : m);
+}
+
 template <int DT>
-__global__ __launch_bounds__(kBlock) void absmax_kernel(const void* g, Tiling tl, uint32_t* kappa_bits)
+__global__ __launch_bounds__(kBlock) void absmax_kernel(const void* g, Tiling tl, uint32_t* kappa_bits,
+                                                       uint32_t levels)
 {
     using T = Elem<DT>;
     constexpr uint32_t TILE = EncTile<DT>::N;
@@ -430,8 +441,7 @@ __global__ __launch_bounds__(kBlock) void absmax_kernel(const void* g, Tiling tl
     if (t.len == TILE) load_tile<DT, true>(g, t, lane, regs);
     else load_tile<DT, false>(g, t, lane, regs);
     const float m = tile_max<DT>(regs);
-    // non-negative floats order like their bit patterns
-    if (lane == 0) atomicMax(kappa_bits + t.bucket, __float_as_uint(m));
+    if (lane == 0) atomicMax(kappa_bits + t.bucket, absmax_word(m, levels));
 }
 
 // The same for buckets of many tiles (a whole vector at the extreme), where one
@@ -440,7 +450,7 @@ __global__ __launch_bounds__(kBlock) void absmax_kernel(const void* g, Tiling tl
 // the workgroup issues a single atomic at the end.
 template <int DT>
 __global__ __launch_bounds__(kBlock) void absmax_span_kernel(const void* g, Tiling tl, uint32_t* kappa_bits,
-                                                            uint32_t blocks_per_bucket)
+                                                            uint32_t blocks_per_bucket, uint32_t levels)
 {
     using T = Elem<DT>;
     constexpr uint32_t TILE = EncTile<DT>::N;
@@ -467,14 +477,8 @@ __global__ __launch_bounds__(kBlock) void absmax_span_kernel(const void* g, Tili
         float all = part[0];
 #pragma unroll
         for (int w = 1; w < kWavesPerBlock; ++w) all = __builtin_fmaxf(all, part[w]);
-        atomicMax(kappa_bits + bucket, __float_as_uint(all));
+        atomicMax(kappa_bits + bucket, absmax_word(all, levels));
     }
-}
-
-__global__ void steps_from_kappa_kernel(float* steps, uint64_t K, uint32_t levels)
-{
-    const uint64_t b = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (b < K) steps[b] = step_from_kappa(steps[b], levels);
 }
 
 // A step that already lies in device memory becomes this worker's transmitted step.
@@ -487,7 +491,7 @@ __global__ void copy_step_kernel(const float* step_in, float* steps)
 // Host side: dispatch
 // ---------------------------------------------------------------------------
 template <int DT>
-static int run_absmax(const void* g, const Tiling& tl, uint64_t K, float* kappa, hipStream_t s)
+static int run_absmax(const void* g, const Tiling& tl, uint64_t K, float* kappa, uint32_t levels, hipStream_t s)
 {
     if (launch(fill_zero_kernel, dim3((uint32_t)((K + 255) / 256)), dim3(256), s, (uint32_t*)kappa, K) != NDQ_OK)
         return NDQ_ELAUNCH;
@@ -499,9 +503,10 @@ static int run_absmax(const void* g, const Tiling& tl, uint64_t K, float* kappa,
         if (per_bucket > most) per_bucket = most;
         if (per_bucket < 1) per_bucket = 1;
         return launch(absmax_span_kernel<DT>, dim3((uint32_t)K * per_bucket), dim3(kBlock), s, g, tl,
-                      (uint32_t*)kappa, per_bucket);
+                      (uint32_t*)kappa, per_bucket, levels);
     }
-    return launch(absmax_kernel<DT>, dim3(blocks_for(tl.total_tiles)), dim3(kBlock), s, g, tl, (uint32_t*)kappa);
+    return launch(absmax_kernel<DT>, dim3(blocks_for(tl.total_tiles)), dim3(kBlock), s, g, tl, (uint32_t*)kappa,
+                  levels);
 }
 
 // Waves of the streaming kernel: kStreamWaves on each of the 1,024 SIMDs.
@@ -626,14 +631,11 @@ static int encode_common(const void* g, int dt, size_t n, float delta, const flo
             launch(copy_step_kernel, dim3(1), dim3(kWave), s, step_in, steps_out) != NDQ_OK)
             return NDQ_ELAUNCH;
     } else if (!fused && a.preset_step == 0.0f) {
-        // two passes: max-norm per bucket, then steps, then the encoder reads them
+        // two passes: the step of every bucket from its max-norm, then the encoder reads them
         const uint64_t K = bucket ? (n + bucket - 1) / bucket : 1;
-        rc = dt == NDQ_F32 ? run_absmax<0>(g, a.tl, K, steps_out, s)
-                           : run_absmax<1>(g, a.tl, K, steps_out, s);
+        rc = dt == NDQ_F32 ? run_absmax<0>(g, a.tl, K, steps_out, levels, s)
+                           : run_absmax<1>(g, a.tl, K, steps_out, levels, s);
         if (rc != NDQ_OK) return rc;
-        if (launch(steps_from_kappa_kernel, dim3((uint32_t)((K + 255) / 256)), dim3(256), s, steps_out, K,
-                   levels) != NDQ_OK)
-            return NDQ_ELAUNCH;
     }
 #ifndef NDQ_NARROW_MAX_BITS
 #define NDQ_NARROW_MAX_BITS 6u
@@ -683,7 +685,7 @@ int ndq_absmax(const void* g, int dt, size_t n, uint32_t bucket, float* kappa_ou
     int rc = make_tiling(n, bucket, tile, &tl);
     if (rc != NDQ_OK) return rc;
     const uint64_t K = bucket ? (n + bucket - 1) / bucket : 1;
-    return dt == NDQ_F32 ? run_absmax<0>(g, tl, K, kappa_out, s) : run_absmax<1>(g, tl, K, kappa_out, s);
+    return dt == NDQ_F32 ? run_absmax<0>(g, tl, K, kappa_out, 0u, s) : run_absmax<1>(g, tl, K, kappa_out, 0u, s);
 }
 
 int ndq_dq_encode(const void* g, int dt, size_t n, float delta, uint32_t levels,

@@ -187,3 +187,30 @@ def test_base_three_digits_two_at_a_time_with_small_multiplies():
                 got += [pair & 3, pair >> 2]
                 y = q
         assert got == digits
+
+
+def test_step_rule_is_monotone_so_the_maximum_of_steps_is_the_step_of_the_maximum():
+    # Sec. 3.1 eq. (2): Delta = 2 kappa / (L - 1), kappa = max |g|.  The two-pass encoder lets every
+    # part of a bucket convert its own max-norm and takes the maximum of the steps; that equals the
+    # step of the bucket's max-norm because each operation of the rule (an exact doubling, a correctly
+    # rounded division, the threshold below 2^-100) is monotone.
+    def step(kappa, levels):
+        s = np.float32(np.float32(2.0) * kappa) / np.float32(levels - 1)
+        return s if s >= np.float32(2.0 ** -100) else np.float32(0.0)
+
+    rng = np.random.default_rng(41)
+    for levels in (2, 3, 4, 5, 7, 16, 100, 255, 256):
+        parts = np.abs(rng.standard_normal((400, 9)).astype(np.float32)) * \
+            np.float32(10.0) ** rng.integers(-38, 6, size=(400, 1)).astype(np.float32)
+        parts[::7, 3] = 0.0
+        parts[5] = 0.0
+        with np.errstate(over="ignore", under="ignore"):
+            for row in parts:
+                assert max(step(k, levels) for k in row) == step(row.max(), levels)
+            # neighbours in binary32 around the threshold and around a power of two
+            for centre in (2.0 ** -101, 2.0 ** -100, 2.0 ** -99, 1.0, 3.0e38):
+                k = np.float32(centre)
+                for _ in range(200):
+                    nxt = np.nextafter(k, np.float32(np.inf))
+                    assert step(k, levels) <= step(nxt, levels)
+                    k = nxt
