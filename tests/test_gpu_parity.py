@@ -642,6 +642,35 @@ def test_config5_full_size_whole_vectors():
     assert int(hist.sum().item()) == n
 
 
+@pytest.mark.parametrize("n", [2 * 6144 * 1024 + 5 * 1024 + 517, 3 * 6144 * 1024 + 1, 2 * 4096 * 4096 + 4096 * 3 + 64])
+def test_config5_plan_with_a_ragged_end_at_the_persistent_grid_size(n):
+    """Config 5's workers on vectors long enough for the persistent kernels on their full
+    grids (two to three tiles per wave slot) that do not end on a tile: the encoders'
+    ragged last tile and the chain decoder's, which runs through the hand-ordered loop
+    with clamped code fetches and a guarded copy-out.  Whole vectors against the oracle
+    (on bucket-aligned slices, all host cores), and against the call-by-call schedule."""
+    wl = workloads.CONFIGS[5]
+    host = workloads.gradients(wl, n, threads=16)
+    dev = pipeline.to_device(wl, host)
+    bufs = pipeline.allocate(wl, n)
+    # guard words behind the result: the ragged tile's copy-out must not reach them
+    guarded = torch.full((n + 1024,), 12345.0, dtype=torch.float32, device=dev[0].device)
+    bufs.total = guarded[:n]
+    ds_g = pipeline.dithers(wl)
+    out = pipeline.step_fused(wl, dev, bufs, ds_g)
+    torch.cuda.synchronize()
+    seeds = [workloads.dither_seed(wl, w) for w in range(wl.W)]
+    c_ref, s_ref, ref = opipe.step_sliced(wl.plan, wl.fine_levels, wl.bucket, host, seeds, wl.out_scale,
+                                          threads=min(16, os.cpu_count() or 1))
+    for w in range(wl.W):
+        assert bufs.codes[w].cpu().numpy().tobytes() == c_ref[w].tobytes(), ("codes", w)
+        assert np.array_equal(bufs.steps[w].cpu().numpy(), s_ref[w]), ("steps", w)
+    assert np.array_equal(out.cpu().numpy(), ref)
+    assert bool((guarded[n:] == 12345.0).all())
+    bufs2 = pipeline.allocate(wl, n)
+    assert torch.equal(pipeline.step(wl, dev, bufs2, ds_g), out)
+
+
 def test_runs_are_deterministic():
     wl = workloads.CONFIGS[5]
     n = 1 << 20
