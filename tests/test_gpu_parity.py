@@ -1014,6 +1014,62 @@ def test_step_can_be_captured_in_a_hip_graph_and_replayed():
             assert torch.equal(bufs.steps[w], eager.steps[w]), (rep, w)
 
 
+def test_tools_can_be_captured_in_a_hip_graph_and_replayed():
+    """The calls beyond the headline path in one graph: a two-pass encode (max-norm pass and
+    encoder), an encode that reads its step from device memory, the histogram with its
+    entropy (cleared by a kernel, closed by the last workgroup's ticket), the dense
+    transcoders and the sum of squared differences from the library's own scratch.  Every
+    replay, with the outputs overwritten in between, must reproduce the eager results."""
+    dev = _gpu()
+    n = 3 * 40960 + 12345
+    g0, g1 = _to_dev(_make(n, "f32", seed=77)), _to_dev(_make(n, "bf16", seed=78))
+    d0, d1 = ndq.ndq_dither(3, 1, 0, 0), ndq.ndq_dither(3, 1, 1, 0)
+
+    def run(o):
+        ndq.ndq_dq_encode(g0, 0.0, 3, 0, d0, o["c0"], o["s0"])
+        ndq.ndq_nested_encode_with_step(g1, o["s0"], 4, 1.0, d1, o["c1"], o["s1"])
+        ndq.ndq_code_entropy(o["c0"], n, 2, o["hist"], o["ent"])
+        ndq.ndq_dense_pack(o["c0"], n, 3, o["dense"])
+        ndq.ndq_dense_unpack(o["dense"], n, 3, o["back"])
+        ndq.ndq_sqdiff_static(g0, o["f"], o["sq"])
+
+    def outputs():
+        return {"c0": torch.empty(ndq.ndq_packed_bytes(n, 2), dtype=torch.uint8, device=dev),
+                "s0": torch.empty(1, dtype=torch.float32, device=dev),
+                "c1": torch.empty(ndq.ndq_packed_bytes(n, 2), dtype=torch.uint8, device=dev),
+                "s1": torch.empty(1, dtype=torch.float32, device=dev),
+                "hist": torch.empty(4, dtype=torch.int64, device=dev),
+                "ent": torch.empty(1, dtype=torch.float64, device=dev),
+                "dense": torch.empty(ndq.ndq_dense_bytes(n, 3), dtype=torch.uint8, device=dev),
+                "back": torch.empty(ndq.ndq_packed_bytes(n, 2), dtype=torch.uint8, device=dev),
+                "f": torch.zeros(n, dtype=torch.float32, device=dev),
+                "sq": torch.empty(1, dtype=torch.float64, device=dev)}
+
+    eager = outputs()
+    run(eager)
+    torch.cuda.synchronize()
+    assert torch.equal(eager["back"], eager["c0"]) and int(eager["hist"].sum().item()) == n
+    bufs = outputs()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):              # warm-up on the capture stream (first use of the static scratch)
+        run(bufs)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        run(bufs)
+    for rep in range(4):
+        for k, t in bufs.items():              # eager work between replays: the outputs hold something else
+            if k != "f":
+                t.fill_(rep + 1)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for k in bufs:
+            assert torch.equal(bufs[k], eager[k]), (rep, k)
+
+
 def test_vector_longer_than_2_pow_32_elements():
     """Largest practical size: n > 2^32 elements per worker (8.6 GB of bf16), so that
     element indices, bit offsets and Philox counters leave 32 bits.  Inputs are
